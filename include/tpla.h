@@ -1,0 +1,177 @@
+/*
+ * libtpla -- shard-local latent-attention decode for Tensor-Parallel Latent
+ * Attention (TPLA, arXiv 2508.15881) on AMD MI355X (gfx950).
+ *
+ * C ABI.  Conventions shared by every entry point:
+ *   - Tensor arguments are DEVICE pointers owned by the caller unless the
+ *     comment says "host".  The library never frees or keeps them.  All
+ *     tensors are dense, row-major, innermost index last.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Work is enqueued on it and the call returns without synchronising.
+ *   - Element type: shape->dtype selects the storage type of caches, queries
+ *     and weights: TPLA_F32 (float storage, float arithmetic) or TPLA_BF16
+ *     (bfloat16 storage, float accumulation).  Softmax statistics, latent
+ *     outputs and final outputs are always float.
+ *   - Return value: TPLA_OK (0) or a negative TPLA_ERR_* code.  On error
+ *     nothing has been launched and tpla_last_error() (thread-local, static
+ *     storage, never NULL) describes the failure.  Argument validation only
+ *     looks at the host-visible values; page ids and sequence lengths that
+ *     live in device memory are trusted (seq_lens[b] <= max_pages_per_seq *
+ *     page_tokens, page ids inside the pool).
+ *   - Every base pointer must be 16-byte aligned (TPLA_ERR_ALIGN).
+ *
+ * Symbols follow the paper: d_c latent width (4 d_h), d_r RoPE width, d_n /
+ * d_v per-head no-RoPE query / value width, H query heads handled by this
+ * device (Sec. 4.4: h_q / (k/g)), g number of latent slices, U the
+ * orthogonal reparameterisation (Sec. 4.1), mu the per-slice score factors
+ * of the softmax slicing condition (Sec. 4.2).
+ */
+#ifndef TPLA_H_
+#define TPLA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TPLA_OK 0
+#define TPLA_ERR_NULL (-1)        /* a required pointer is NULL                      */
+#define TPLA_ERR_SHAPE (-2)       /* a dimension is non-positive or inconsistent     */
+#define TPLA_ERR_ALIGN (-3)       /* a base pointer is not 16-byte aligned           */
+#define TPLA_ERR_WORKSPACE (-4)   /* workspace smaller than tpla_workspace_bytes()   */
+#define TPLA_ERR_DTYPE (-5)       /* shape->dtype is not TPLA_F32 / TPLA_BF16        */
+#define TPLA_ERR_HIP (-6)         /* the HIP runtime refused a launch                */
+#define TPLA_ERR_UNSUPPORTED (-7) /* valid request this build has no kernel for      */
+
+#define TPLA_F32 0
+#define TPLA_BF16 1
+
+#define TPLA_U_IDENTITY 0 /* U = I                                                  */
+#define TPLA_U_HADAMARD 1 /* U = diag(signs) H_{d_c} / sqrt(d_c), Sec. 4.3.1        */
+#define TPLA_U_DENSE 2    /* U given as a dense matrix (e.g. PCA, Sec. 4.3.2)       */
+
+#define TPLA_MAX_G 8 /* largest supported number of latent slices */
+
+typedef struct tpla_shape {
+  int32_t B;           /* sequences in the decode batch                              */
+  int32_t H;           /* query heads handled here                                   */
+  int32_t d_c;         /* full latent width                                          */
+  int32_t g;           /* latent slices; slice i = columns [i d_c/g, (i+1) d_c/g)    */
+  int32_t d_r;         /* RoPE key / query width (replicated on every slice)         */
+  int32_t d_n;         /* per-head no-RoPE query width                               */
+  int32_t d_v;         /* per-head value width                                       */
+  int32_t page_tokens; /* tokens per cache page                                      */
+  int32_t dtype;       /* TPLA_F32 or TPLA_BF16                                      */
+  float sm_scale;      /* softmax scale, 1/sqrt(d_n + d_r) in Sec. 3.3               */
+} tpla_shape_t;
+
+/* Description of the last error on the calling thread ("" if none). */
+const char* tpla_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int tpla_version(void);
+
+/*
+ * Orthogonal reparameterisation along one axis (Sec. 4.1: W_new = U^T W and
+ * c_new = c U; Sec. 4.3 for the choice of U).
+ * src and dst are [n_outer, d_c, n_inner] tensors of shape->dtype elements
+ * (dst may equal src).  For every (o, i):
+ *     inverse = 0:  dst[o, j, i] = sum_k src[o, k, i] * U[k, j]      (x U)
+ *     inverse = 1:  dst[o, j, i] = sum_k src[o, k, i] * U[j, k]      (x U^T)
+ * so cache rows and W_UK[h] ([.., d_c], n_inner = 1) and W_UV[h]
+ * ([d_c, d_v], n_inner = d_v) all use inverse = 0.
+ * mode = TPLA_U_IDENTITY: copy.  TPLA_U_HADAMARD: signs is NULL (all +1) or
+ * d_c floats of +-1; d_c must be a power of two.  TPLA_U_DENSE: U is
+ * [d_c, d_c] floats.  Arithmetic is float; one rounding on the way out.
+ * Only shape->d_c and shape->dtype are read.
+ */
+int tpla_transform_latent(const tpla_shape_t* shape, int mode, int inverse,
+                          const float* signs, const float* U,
+                          const void* src, void* dst,
+                          int64_t n_outer, int64_t n_inner, void* stream);
+
+/*
+ * Cache form of the reparameterisation (Sec. 4.1) plus the slicing of Sec. 4
+ * and the replication of the RoPE key of Sec. 4.2.  Reads MLA-style pages
+ * mla_pool [P, page_tokens, d_c + d_r] (row = latent then k_pe) and writes,
+ * for every listed page and every slice i, shard_pools[i]
+ * [P, page_tokens, d_c/g + d_r] with row = (c U)[i d_c/g : (i+1) d_c/g] then
+ * k_pe, at the same page id.  shard_pools is a HOST array of g device
+ * pointers.  page_ids: n_pages int32 page ids on the device, or NULL for
+ * pages 0..n_pages-1.  Every slot of a listed page is processed.
+ */
+int tpla_transform_latent_paged(const tpla_shape_t* shape, int mode,
+                                const float* signs, const float* U,
+                                const void* mla_pool, void* const* shard_pools,
+                                const int32_t* page_ids, int64_t n_pages, void* stream);
+
+/*
+ * MLA-style cache write (Sec. 3.3; norm weight absorbed as in Sec. 4.1):
+ * for token t < T, pool row slot_mapping[t] (= page * page_tokens + offset)
+ * of mla_pool [P, page_tokens, d_c + d_r] becomes
+ *     [ c_raw[t] / sqrt(mean(c_raw[t]^2) + rms_eps)  ||  k_pe[t] ].
+ * rms_eps < 0 stores c_raw unnormalised.  c_raw [T, d_c], k_pe [T, d_r] in
+ * shape->dtype; slot_mapping int32 [T]; a negative slot skips the token.
+ */
+int tpla_write_mla_cache(const tpla_shape_t* shape, const void* c_raw, const void* k_pe,
+                         const int32_t* slot_mapping, int64_t T, float rms_eps,
+                         void* mla_pool, void* stream);
+
+/*
+ * Absorbed query (Sec. 3.3) cut into slices (Sec. 4) with the factor of the
+ * softmax slicing condition folded in (Sec. 4.2):
+ *     q_lat[i, b, h, :] = mu[i] * (q_nope[b, h, :] @ W_UK_t[h])[i d_c/g : (i+1) d_c/g]
+ * q_nope [B, H, d_n], W_UK_t [H, d_n, d_c] (already in the U basis),
+ * q_lat [g, B, H, d_c/g], all shape->dtype.  mu: HOST array of g floats or
+ * NULL for all ones.
+ */
+int tpla_absorb_query(const tpla_shape_t* shape, const void* q_nope, const void* W_UK_t,
+                      const float* mu, void* q_lat, void* stream);
+
+/*
+ * Bytes of scratch tpla_decode_shard needs for the given split count
+ * (n_splits = 0 asks for the count the library would choose by itself).
+ * Returns 0 on invalid arguments.
+ */
+size_t tpla_workspace_bytes(const tpla_shape_t* shape, int32_t max_pages_per_seq, int32_t n_splits);
+
+/*
+ * One device's attention over its latent slice (Sec. 4, per-device softmax
+ * equation; RoPE key replicated, Sec. 4.2).  For every sequence b and head h,
+ * with row_t = pool row of token t of sequence b (latent slice, then k_pe):
+ *     s_t      = sm_scale * (q_lat_i[b,h] . row_t[:d_c/g] + q_pe[b,h] . row_t[d_c/g:])
+ *     p        = softmax over t in [0, seq_lens[b])
+ *     o_lat_i[b,h,:] = sum_t p_t * row_t[:d_c/g]        lse_i[b,h] = log sum_t exp(s_t)
+ * Token t of sequence b lives in page block_table[b, t / page_tokens], slot
+ * t % page_tokens of shard_pool [P, page_tokens, d_c/g + d_r].  Slots at or
+ * beyond seq_lens[b] are never read.  seq_lens[b] = 0 gives o = 0, lse = -inf.
+ * The sequence axis is processed in n_splits independent chunks per sequence
+ * (0 = library's choice) whose partial results go through `workspace` and are
+ * merged in a fixed order: for fixed arguments the result is bit-reproducible.
+ * q_lat_i [B,H,d_c/g], q_pe [B,H,d_r] in shape->dtype; block_table int32
+ * [B, max_pages_per_seq]; seq_lens int32 [B]; o_lat_i float [B,H,d_c/g];
+ * lse_i float [B,H] or NULL.
+ */
+int tpla_decode_shard(const tpla_shape_t* shape,
+                      const void* q_lat_i, const void* q_pe, const void* shard_pool,
+                      const int32_t* block_table, int32_t max_pages_per_seq,
+                      const int32_t* seq_lens, int32_t n_splits,
+                      void* workspace, size_t workspace_bytes,
+                      float* o_lat_i, float* lse_i, void* stream);
+
+/*
+ * Value up-projection of every slice and the sum over slices that the
+ * all-reduce of Sec. 4 performs (W_UV kept separate from W_O, Sec. 3.3):
+ *     o[b, h, :] = sum_i o_lat[i, b, h, :] @ W_UV_t[h, i d_c/g : (i+1) d_c/g, :]
+ * o_lat float [g, B, H, d_c/g]; W_UV_t [H, d_c, d_v] in shape->dtype (U
+ * basis); o float [B, H, d_v].
+ */
+int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t,
+                        float* o, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TPLA_H_ */

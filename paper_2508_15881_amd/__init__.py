@@ -1,0 +1,14 @@
+"""MI355X-native shard-local latent-attention decode for TPLA (arXiv 2508.15881).
+
+The compute lives in libtpla.so (HIP, gfx950) behind the C ABI declared in
+include/tpla.h; `binding` marshals torch tensors into it.  Importing the
+package does not load the library; the first call does, and fails loudly if
+the library has not been built (python -m paper_2508_15881_amd.build).
+"""
+from .binding import (  # noqa: F401
+    TPLA_BF16, TPLA_F32, TPLA_U_DENSE, TPLA_U_HADAMARD, TPLA_U_IDENTITY,
+    TplaError, TplaShape, lib_path, load_library,
+    tpla_absorb_query, tpla_combine_shards, tpla_decode_shard, tpla_last_error,
+    tpla_transform_latent, tpla_transform_latent_paged, tpla_version,
+    tpla_workspace_bytes, tpla_write_mla_cache,
+)

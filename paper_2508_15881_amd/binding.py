@@ -1,0 +1,165 @@
+"""ctypes binding of libtpla.so: argument marshalling only.
+
+Every function has the name and argument order of its C counterpart in
+include/tpla.h.  Tensor arguments may be torch tensors (their data_ptr() is
+passed; they must be contiguous) or plain integers (raw addresses).  The
+stream is torch's current stream unless given.
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "lib", "libtpla.so")
+
+TPLA_F32, TPLA_BF16 = 0, 1
+TPLA_U_IDENTITY, TPLA_U_HADAMARD, TPLA_U_DENSE = 0, 1, 2
+TPLA_MAX_G = 8
+
+EXPORTS = (
+    "tpla_last_error", "tpla_version", "tpla_transform_latent", "tpla_transform_latent_paged",
+    "tpla_write_mla_cache", "tpla_absorb_query", "tpla_workspace_bytes", "tpla_decode_shard",
+    "tpla_combine_shards",
+)
+
+
+class TplaError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libtpla error %d: %s" % (code, msg))
+        self.code = code
+
+
+class TplaShape(ctypes.Structure):
+    """Mirror of tpla_shape_t."""
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d_c", ctypes.c_int32), ("g", ctypes.c_int32),
+        ("d_r", ctypes.c_int32), ("d_n", ctypes.c_int32), ("d_v", ctypes.c_int32),
+        ("page_tokens", ctypes.c_int32), ("dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+    ]
+
+    @property
+    def dl(self):
+        return self.d_c // self.g
+
+
+_lib = None
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libtpla.so once.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            "libtpla.so not found at %s -- build it with `python -m paper_2508_15881_amd.build`" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, fp = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.POINTER(ctypes.c_float)
+    shp = ctypes.POINTER(TplaShape)
+    lib.tpla_last_error.restype = ctypes.c_char_p
+    lib.tpla_last_error.argtypes = []
+    lib.tpla_version.restype = ctypes.c_int
+    lib.tpla_version.argtypes = []
+    lib.tpla_transform_latent.restype = ctypes.c_int
+    lib.tpla_transform_latent.argtypes = [shp, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, i64, i64, vp]
+    lib.tpla_transform_latent_paged.restype = ctypes.c_int
+    lib.tpla_transform_latent_paged.argtypes = [shp, ctypes.c_int, vp, vp, vp, ctypes.POINTER(vp), vp, i64, vp]
+    lib.tpla_write_mla_cache.restype = ctypes.c_int
+    lib.tpla_write_mla_cache.argtypes = [shp, vp, vp, vp, i64, ctypes.c_float, vp, vp]
+    lib.tpla_absorb_query.restype = ctypes.c_int
+    lib.tpla_absorb_query.argtypes = [shp, vp, vp, fp, vp, vp]
+    lib.tpla_workspace_bytes.restype = ctypes.c_size_t
+    lib.tpla_workspace_bytes.argtypes = [shp, i32, i32]
+    lib.tpla_decode_shard.restype = ctypes.c_int
+    lib.tpla_decode_shard.argtypes = [shp, vp, vp, vp, vp, i32, vp, i32, vp, ctypes.c_size_t, vp, vp, vp]
+    lib.tpla_combine_shards.restype = ctypes.c_int
+    lib.tpla_combine_shards.argtypes = [shp, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    """Address of a tensor / raw address / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if not x.is_contiguous():
+        raise ValueError("libtpla needs contiguous tensors")
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    import torch
+    if torch.cuda.is_available():
+        return torch.cuda.current_stream().cuda_stream
+    return None
+
+
+def _check(rc):
+    if rc != 0:
+        raise TplaError(rc, tpla_last_error())
+
+
+def tpla_last_error():
+    return load_library().tpla_last_error().decode()
+
+
+def tpla_version():
+    return load_library().tpla_version()
+
+
+def tpla_transform_latent(shape, mode, inverse, signs, U, src, dst, n_outer, n_inner, stream=None):
+    _check(load_library().tpla_transform_latent(
+        ctypes.byref(shape), mode, inverse, _ptr(signs), _ptr(U), _ptr(src), _ptr(dst),
+        n_outer, n_inner, _stream(stream)))
+
+
+def tpla_transform_latent_paged(shape, mode, signs, U, mla_pool, shard_pools, page_ids, n_pages, stream=None):
+    if shard_pools is None:
+        arr = None
+    else:
+        # never read past g entries on the C side; sized generously so a
+        # wrong-length list is reported by the library, not by ctypes
+        arr = (ctypes.c_void_p * max(TPLA_MAX_G, len(shard_pools)))()
+        for i, p in enumerate(shard_pools):
+            arr[i] = _ptr(p)
+    _check(load_library().tpla_transform_latent_paged(
+        ctypes.byref(shape), mode, _ptr(signs), _ptr(U), _ptr(mla_pool), arr, _ptr(page_ids),
+        n_pages, _stream(stream)))
+
+
+def tpla_write_mla_cache(shape, c_raw, k_pe, slot_mapping, T, rms_eps, mla_pool, stream=None):
+    _check(load_library().tpla_write_mla_cache(
+        ctypes.byref(shape), _ptr(c_raw), _ptr(k_pe), _ptr(slot_mapping), T, rms_eps, _ptr(mla_pool),
+        _stream(stream)))
+
+
+def tpla_absorb_query(shape, q_nope, W_UK_t, mu, q_lat, stream=None):
+    mu_arr = None
+    if mu is not None:
+        mu_arr = (ctypes.c_float * max(TPLA_MAX_G, len(mu)))(*[float(m) for m in mu])
+    _check(load_library().tpla_absorb_query(
+        ctypes.byref(shape), _ptr(q_nope), _ptr(W_UK_t), mu_arr, _ptr(q_lat), _stream(stream)))
+
+
+def tpla_workspace_bytes(shape, max_pages_per_seq, n_splits):
+    return int(load_library().tpla_workspace_bytes(ctypes.byref(shape), max_pages_per_seq, n_splits))
+
+
+def tpla_decode_shard(shape, q_lat_i, q_pe, shard_pool, block_table, max_pages_per_seq, seq_lens,
+                      n_splits, workspace, workspace_bytes, o_lat_i, lse_i, stream=None):
+    _check(load_library().tpla_decode_shard(
+        ctypes.byref(shape), _ptr(q_lat_i), _ptr(q_pe), _ptr(shard_pool), _ptr(block_table),
+        max_pages_per_seq, _ptr(seq_lens), n_splits, _ptr(workspace), workspace_bytes,
+        _ptr(o_lat_i), _ptr(lse_i), _stream(stream)))
+
+
+def tpla_combine_shards(shape, o_lat, W_UV_t, o, stream=None):
+    _check(load_library().tpla_combine_shards(
+        ctypes.byref(shape), _ptr(o_lat), _ptr(W_UV_t), _ptr(o), _stream(stream)))

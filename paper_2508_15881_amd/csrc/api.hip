@@ -1,0 +1,261 @@
+// C ABI entry points of libtpla: argument validation, split planning and
+// dispatch to the kernels.  No kernel is launched when validation fails.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <math.h>
+#include "tpla_internal.h"
+
+namespace tpla {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(TPLA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return TPLA_OK;
+}
+
+int device_cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int check_dtype(const tpla_shape_t* sh) {
+  if (!sh) return fail(TPLA_ERR_NULL, "shape is NULL");
+  if (sh->dtype != TPLA_F32 && sh->dtype != TPLA_BF16)
+    return fail(TPLA_ERR_DTYPE, "dtype %d is neither TPLA_F32 nor TPLA_BF16", sh->dtype);
+  return TPLA_OK;
+}
+
+// Full consistency check of the attention geometry.
+static int check_shape(const tpla_shape_t* sh) {
+  int rc = check_dtype(sh);
+  if (rc) return rc;
+  if (sh->B < 1 || sh->H < 1 || sh->d_c < 1 || sh->g < 1 || sh->d_r < 1 || sh->d_n < 1 ||
+      sh->d_v < 1 || sh->page_tokens < 1)
+    return fail(TPLA_ERR_SHAPE, "every dimension must be positive (B=%d H=%d d_c=%d g=%d d_r=%d d_n=%d d_v=%d page_tokens=%d)",
+                sh->B, sh->H, sh->d_c, sh->g, sh->d_r, sh->d_n, sh->d_v, sh->page_tokens);
+  if (sh->g > TPLA_MAX_G) return fail(TPLA_ERR_SHAPE, "g=%d exceeds TPLA_MAX_G=%d", sh->g, TPLA_MAX_G);
+  if (sh->d_c % sh->g) return fail(TPLA_ERR_SHAPE, "d_c=%d is not divisible by g=%d", sh->d_c, sh->g);
+  const int dl = sh->d_c / sh->g;
+  if (dl % 8 || sh->d_r % 8)
+    return fail(TPLA_ERR_SHAPE, "d_c/g=%d and d_r=%d must be multiples of 8 (16-byte row pieces)", dl, sh->d_r);
+  if (!(sh->sm_scale > 0.0f) || !isfinite(sh->sm_scale))
+    return fail(TPLA_ERR_SHAPE, "sm_scale must be positive and finite");
+  return TPLA_OK;
+}
+
+SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages, int32_t n_splits_req) {
+  SplitPlan p;
+  int32_t n = n_splits_req;
+  if (n <= 0) {
+    // Aim for about three resident workgroups per compute unit, but keep a
+    // chunk at least 4 pages long so the partial results stay a small
+    // fraction of the cache bytes read.
+    const int slots = device_cu_count() * 3;
+    n = (slots + sh.B - 1) / sh.B;
+    const int32_t cap = (max_pages + 3) / 4;
+    if (n > cap) n = cap;
+    if (n < 1) n = 1;
+  }
+  if (n > max_pages) n = max_pages;
+  if (n < 1) n = 1;
+  p.pages_per_split = (max_pages + n - 1) / n;
+  p.n_splits = (max_pages + p.pages_per_split - 1) / p.pages_per_split;
+  return p;
+}
+
+static size_t workspace_for(const tpla_shape_t& sh, const SplitPlan& p) {
+  const size_t dl = (size_t)(sh.d_c / sh.g);
+  return (size_t)sh.B * p.n_splits * sh.H * (dl + 2) * sizeof(float);
+}
+
+}  // namespace tpla
+
+using namespace tpla;
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+const char* tpla_last_error(void) { return g_err; }
+
+int tpla_version(void) { return 100; }
+
+int tpla_transform_latent(const tpla_shape_t* shape, int mode, int inverse, const float* signs,
+                          const float* U, const void* src, void* dst, int64_t n_outer,
+                          int64_t n_inner, void* stream) {
+  int rc = check_dtype(shape);
+  if (rc) return rc;
+  if (!src || !dst) return fail(TPLA_ERR_NULL, "src/dst is NULL");
+  if (shape->d_c < 1 || n_outer < 0 || n_inner < 1)
+    return fail(TPLA_ERR_SHAPE, "d_c=%d n_outer=%lld n_inner=%lld", shape->d_c, (long long)n_outer, (long long)n_inner);
+  if (mode != TPLA_U_IDENTITY && mode != TPLA_U_HADAMARD && mode != TPLA_U_DENSE)
+    return fail(TPLA_ERR_SHAPE, "unknown transform mode %d", mode);
+  if (mode == TPLA_U_HADAMARD && (shape->d_c & (shape->d_c - 1)))
+    return fail(TPLA_ERR_SHAPE, "Hadamard transform needs a power-of-two d_c, got %d", shape->d_c);
+  if (mode == TPLA_U_DENSE && !U) return fail(TPLA_ERR_NULL, "dense mode needs U");
+  if (shape->d_c > 8192) return fail(TPLA_ERR_UNSUPPORTED, "d_c=%d above 8192", shape->d_c);
+  if (!aligned16(src) || !aligned16(dst) || !aligned16(signs) || !aligned16(U))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  if (n_outer == 0) return TPLA_OK;
+  if (n_outer * n_inner > (int64_t)2147483647)
+    return fail(TPLA_ERR_UNSUPPORTED, "n_outer*n_inner above 2^31-1");
+  TransformArgs t{shape->d_c, shape->dtype, mode, inverse ? 1 : 0, signs, U};
+  return launch_transform_axis(t, src, dst, n_outer, n_inner, (hipStream_t)stream);
+}
+
+int tpla_transform_latent_paged(const tpla_shape_t* shape, int mode, const float* signs,
+                                const float* U, const void* mla_pool, void* const* shard_pools,
+                                const int32_t* page_ids, int64_t n_pages, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!mla_pool || !shard_pools) return fail(TPLA_ERR_NULL, "mla_pool/shard_pools is NULL");
+  if (mode != TPLA_U_IDENTITY && mode != TPLA_U_HADAMARD && mode != TPLA_U_DENSE)
+    return fail(TPLA_ERR_SHAPE, "unknown transform mode %d", mode);
+  if (mode == TPLA_U_HADAMARD && (shape->d_c & (shape->d_c - 1)))
+    return fail(TPLA_ERR_SHAPE, "Hadamard transform needs a power-of-two d_c, got %d", shape->d_c);
+  if (mode == TPLA_U_DENSE && !U) return fail(TPLA_ERR_NULL, "dense mode needs U");
+  if (shape->d_c > 8192) return fail(TPLA_ERR_UNSUPPORTED, "d_c=%d above 8192", shape->d_c);
+  if (shape->d_c % 8) return fail(TPLA_ERR_SHAPE, "d_c must be a multiple of 8");
+  if (n_pages < 0 || n_pages * shape->page_tokens > (int64_t)2147483647)
+    return fail(TPLA_ERR_SHAPE, "n_pages=%lld out of range", (long long)n_pages);
+  ShardPools pools;
+  for (int i = 0; i < TPLA_MAX_G; ++i) pools.p[i] = nullptr;
+  for (int i = 0; i < shape->g; ++i) {
+    if (!shard_pools[i]) return fail(TPLA_ERR_NULL, "shard_pools[%d] is NULL", i);
+    if (!aligned16(shard_pools[i])) return fail(TPLA_ERR_ALIGN, "shard_pools[%d] not 16-byte aligned", i);
+    pools.p[i] = shard_pools[i];
+  }
+  if (!aligned16(mla_pool) || !aligned16(page_ids) || !aligned16(signs) || !aligned16(U))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  if (n_pages == 0) return TPLA_OK;
+  TransformArgs t{shape->d_c, shape->dtype, mode, 0, signs, U};
+  return launch_transform_paged(t, *shape, mla_pool, pools, page_ids, n_pages, (hipStream_t)stream);
+}
+
+int tpla_write_mla_cache(const tpla_shape_t* shape, const void* c_raw, const void* k_pe,
+                         const int32_t* slot_mapping, int64_t T, float rms_eps, void* mla_pool,
+                         void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!c_raw || !k_pe || !slot_mapping || !mla_pool) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
+  if (T < 0 || T > (int64_t)2147483647) return fail(TPLA_ERR_SHAPE, "T=%lld out of range", (long long)T);
+  if (shape->d_c % 8) return fail(TPLA_ERR_SHAPE, "d_c must be a multiple of 8");
+  if (!aligned16(c_raw) || !aligned16(k_pe) || !aligned16(slot_mapping) || !aligned16(mla_pool))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  if (isnan(rms_eps)) return fail(TPLA_ERR_SHAPE, "rms_eps is NaN");
+  if (T == 0) return TPLA_OK;
+  return launch_write_mla_cache(*shape, c_raw, k_pe, slot_mapping, T, rms_eps, mla_pool,
+                                (hipStream_t)stream);
+}
+
+int tpla_absorb_query(const tpla_shape_t* shape, const void* q_nope, const void* W_UK_t,
+                      const float* mu, void* q_lat, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q_nope || !W_UK_t || !q_lat) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
+  if (!aligned16(q_nope) || !aligned16(W_UK_t) || !aligned16(q_lat))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  MuFactors m;
+  for (int i = 0; i < TPLA_MAX_G; ++i) m.v[i] = 1.0f;
+  if (mu)
+    for (int i = 0; i < shape->g; ++i) {
+      if (!isfinite(mu[i])) return fail(TPLA_ERR_SHAPE, "mu[%d] is not finite", i);
+      m.v[i] = mu[i];
+    }
+  return launch_absorb_query(*shape, q_nope, W_UK_t, m, q_lat, (hipStream_t)stream);
+}
+
+size_t tpla_workspace_bytes(const tpla_shape_t* shape, int32_t max_pages_per_seq, int32_t n_splits) {
+  if (check_shape(shape) != TPLA_OK) return 0;
+  if (max_pages_per_seq < 1 || n_splits < 0) {
+    fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_splits=%d", max_pages_per_seq, n_splits);
+    return 0;
+  }
+  return workspace_for(*shape, plan_splits(*shape, max_pages_per_seq, n_splits));
+}
+
+int tpla_decode_shard(const tpla_shape_t* shape, const void* q_lat_i, const void* q_pe,
+                      const void* shard_pool, const int32_t* block_table,
+                      int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t n_splits,
+                      void* workspace, size_t workspace_bytes, float* o_lat_i, float* lse_i,
+                      void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q_lat_i || !q_pe || !shard_pool || !block_table || !seq_lens || !workspace || !o_lat_i)
+    return fail(TPLA_ERR_NULL, "a required pointer is NULL");
+  if (max_pages_per_seq < 1 || n_splits < 0)
+    return fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_splits=%d", max_pages_per_seq, n_splits);
+  if ((int64_t)max_pages_per_seq * shape->page_tokens > (int64_t)2147483647)
+    return fail(TPLA_ERR_SHAPE, "max_pages_per_seq * page_tokens overflows int32");
+  if (!aligned16(q_lat_i) || !aligned16(q_pe) || !aligned16(shard_pool) || !aligned16(block_table) ||
+      !aligned16(seq_lens) || !aligned16(workspace) || !aligned16(o_lat_i) || !aligned16(lse_i))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  const SplitPlan plan = plan_splits(*shape, max_pages_per_seq, n_splits);
+  const size_t need = workspace_for(*shape, plan);
+  if (workspace_bytes < need)
+    return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  if ((int64_t)shape->B * plan.n_splits > (int64_t)2147483647 / 4)
+    return fail(TPLA_ERR_UNSUPPORTED, "B * n_splits too large");
+
+  DecodeArgs a;
+  const int dl = shape->d_c / shape->g;
+  a.q_lat = q_lat_i;
+  a.q_pe = q_pe;
+  a.pool = shard_pool;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.part_acc = static_cast<float*>(workspace);
+  a.part_ml = a.part_acc + (size_t)shape->B * plan.n_splits * shape->H * dl;
+  a.o_lat = o_lat_i;
+  a.lse = lse_i;
+  a.B = shape->B;
+  a.H = shape->H;
+  a.dl = dl;
+  a.d_r = shape->d_r;
+  a.page_tokens = shape->page_tokens;
+  a.max_pages = max_pages_per_seq;
+  a.n_splits = plan.n_splits;
+  a.pages_per_split = plan.pages_per_split;
+  a.scale_log2 = shape->sm_scale * 1.4426950408889634f;
+
+  hipStream_t st = (hipStream_t)stream;
+  if (shape->dtype == TPLA_BF16 && decode_mfma_supported(*shape))
+    rc = launch_decode_mfma(a, st);
+  else
+    rc = launch_decode_generic(a, shape->dtype, st);
+  if (rc) return rc;
+  return launch_decode_merge(a, st);
+}
+
+int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t, float* o,
+                        void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!o_lat || !W_UV_t || !o) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
+  if (!aligned16(o_lat) || !aligned16(W_UV_t) || !aligned16(o))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  return launch_combine_shards(*shape, o_lat, W_UV_t, o, (hipStream_t)stream);
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,160 @@
+// Shape-agnostic shard decode (any widths, float or bf16 storage, float
+// arithmetic) and the merge of split partials.  This is the float-mode
+// implementation and the fallback for bf16 shapes the MFMA kernel does not
+// cover; it favours clarity over speed.
+#include "tpla_internal.h"
+
+namespace tpla {
+
+constexpr int GEN_THREADS = 128;
+constexpr int GEN_MAX_COLS = 8;   // output columns per thread: d_c/g <= 1024
+
+// One workgroup = one (sequence, split, head).  Tokens are processed in
+// chunks of GEN_THREADS: thread i scores token i, the chunk's weights go to
+// LDS, then thread j accumulates output columns j, j+GEN_THREADS, ...
+template <typename T>
+__global__ void __launch_bounds__(GEN_THREADS) decode_generic_kernel(DecodeArgs a) {
+  extern __shared__ float smem[];
+  const int dl = a.dl, dr = a.d_r, w = dl + dr;
+  float* q = smem;                  // [w]
+  float* p = smem + w;              // [GEN_THREADS]
+  float* red = p + GEN_THREADS;     // [GEN_THREADS]
+  const int tid = threadIdx.x;
+  const int b = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;
+  const int h = blockIdx.y;
+  const int L = a.seq_lens[b];
+  const int pt = a.page_tokens;
+  const int n_pages = (L + pt - 1) / pt;
+  const int p0 = s * a.pages_per_split;
+  if (p0 >= n_pages) return;
+  int p1 = p0 + a.pages_per_split;
+  if (p1 > n_pages) p1 = n_pages;
+  const int t_begin = p0 * pt;
+  const int t_end = min(p1 * pt, L);
+
+  const T* ql = static_cast<const T*>(a.q_lat) + ((size_t)b * a.H + h) * dl;
+  const T* qp = static_cast<const T*>(a.q_pe) + ((size_t)b * a.H + h) * dr;
+  for (int i = tid; i < dl; i += GEN_THREADS) q[i] = load_as_f32(ql + i);
+  for (int i = tid; i < dr; i += GEN_THREADS) q[dl + i] = load_as_f32(qp + i);
+  __syncthreads();
+
+  const T* pool = static_cast<const T*>(a.pool);
+  const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
+  float acc[GEN_MAX_COLS];
+#pragma unroll
+  for (int c = 0; c < GEN_MAX_COLS; ++c) acc[c] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  for (int t0 = t_begin; t0 < t_end; t0 += GEN_THREADS) {
+    const int t = t0 + tid;
+    float sc = -INFINITY;
+    if (t < t_end) {
+      const T* row = pool + ((size_t)bt[t / pt] * pt + (t % pt)) * w;
+      float d = 0.f;
+      for (int i = 0; i < w; ++i) d = fmaf(q[i], load_as_f32(row + i), d);
+      sc = d * a.scale_log2;
+    }
+    // chunk maximum
+    red[tid] = sc;
+    __syncthreads();
+    for (int o = GEN_THREADS / 2; o > 0; o >>= 1) {
+      if (tid < o) red[tid] = fmaxf(red[tid], red[tid + o]);
+      __syncthreads();
+    }
+    const float m_new = fmaxf(m_run, red[0]);
+    __syncthreads();
+    const float pv = (t < t_end) ? exp2f(sc - m_new) : 0.f;
+    p[tid] = pv;
+    red[tid] = pv;
+    __syncthreads();
+    for (int o = GEN_THREADS / 2; o > 0; o >>= 1) {
+      if (tid < o) red[tid] += red[tid + o];
+      __syncthreads();
+    }
+    const float alpha = exp2f(m_run - m_new);   // 0 on the first chunk
+    l_run = l_run * alpha + red[0];
+    m_run = m_new;
+    const int cnt = min(GEN_THREADS, t_end - t0);
+#pragma unroll
+    for (int c = 0; c < GEN_MAX_COLS; ++c) {
+      const int col = tid + c * GEN_THREADS;
+      if (col < dl) {
+        float v = acc[c] * alpha;
+        for (int i = 0; i < cnt; ++i) {
+          const int tt = t0 + i;
+          const T* row = pool + ((size_t)bt[tt / pt] * pt + (tt % pt)) * w;
+          v = fmaf(p[i], load_as_f32(row + col), v);
+        }
+        acc[c] = v;
+      }
+    }
+    __syncthreads();
+  }
+  const size_t item = ((size_t)b * a.n_splits + s) * a.H + h;
+#pragma unroll
+  for (int c = 0; c < GEN_MAX_COLS; ++c) {
+    const int col = tid + c * GEN_THREADS;
+    if (col < dl) a.part_acc[item * dl + col] = acc[c];
+  }
+  if (tid == 0) {
+    a.part_ml[item * 2 + 0] = m_run;
+    a.part_ml[item * 2 + 1] = l_run;
+  }
+}
+
+// One workgroup = one (sequence, head): combines the non-empty splits in
+// ascending split order (fixed order => reproducible bits).
+__global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
+  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
+  const int L = a.seq_lens[b];
+  const int n_pages = (L + a.page_tokens - 1) / a.page_tokens;
+  int cnt = (n_pages + a.pages_per_split - 1) / a.pages_per_split;
+  if (cnt > a.n_splits) cnt = a.n_splits;
+  const int dl = a.dl;
+  float* out = a.o_lat + ((size_t)b * a.H + h) * dl;
+  if (cnt == 0) {
+    for (int c = threadIdx.x; c < dl; c += blockDim.x) out[c] = 0.f;
+    if (a.lse && threadIdx.x == 0) a.lse[(size_t)b * a.H + h] = -INFINITY;
+    return;
+  }
+  const size_t item0 = ((size_t)b * a.n_splits) * a.H + h;
+  float M = -INFINITY;
+  for (int s = 0; s < cnt; ++s) M = fmaxf(M, a.part_ml[(item0 + (size_t)s * a.H) * 2]);
+  float lsum = 0.f;
+  for (int s = 0; s < cnt; ++s) {
+    const float* ml = a.part_ml + (item0 + (size_t)s * a.H) * 2;
+    lsum += ml[1] * exp2f(ml[0] - M);
+  }
+  const float inv = 1.0f / lsum;
+  for (int c = threadIdx.x; c < dl; c += blockDim.x) {
+    float v = 0.f;
+    for (int s = 0; s < cnt; ++s) {
+      const size_t item = item0 + (size_t)s * a.H;
+      v = fmaf(a.part_acc[item * dl + c], exp2f(a.part_ml[item * 2] - M), v);
+    }
+    out[c] = v * inv;
+  }
+  if (a.lse && threadIdx.x == 0)
+    a.lse[(size_t)b * a.H + h] = (M + log2f(lsum)) * 0.6931471805599453f;
+}
+
+int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st) {
+  if (a.dl > GEN_MAX_COLS * GEN_THREADS)
+    return fail(TPLA_ERR_UNSUPPORTED, "d_c/g=%d above %d", a.dl, GEN_MAX_COLS * GEN_THREADS);
+  const size_t smem = (size_t)(a.dl + a.d_r + 2 * GEN_THREADS) * sizeof(float);
+  if (smem > 64 * 1024) return fail(TPLA_ERR_UNSUPPORTED, "row too wide for the generic kernel");
+  if (a.H > 65535) return fail(TPLA_ERR_UNSUPPORTED, "H above 65535");
+  dim3 grid((unsigned)(a.B * a.n_splits), (unsigned)a.H);
+  if (dtype == TPLA_F32)
+    hipLaunchKernelGGL(decode_generic_kernel<float>, grid, dim3(GEN_THREADS), smem, st, a);
+  else
+    hipLaunchKernelGGL(decode_generic_kernel<bf16_t>, grid, dim3(GEN_THREADS), smem, st, a);
+  return check_launch("decode_generic_kernel");
+}
+
+int launch_decode_merge(const DecodeArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(a.B * a.H)), dim3(128), 0, st, a);
+  return check_launch("decode_merge_kernel");
+}
+
+}  // namespace tpla

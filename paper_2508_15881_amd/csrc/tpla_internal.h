@@ -1,0 +1,83 @@
+// Internal declarations shared by the translation units of libtpla.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "tpla.h"
+
+namespace tpla {
+
+// Records the message returned by tpla_last_error() and hands back `code`.
+int fail(int code, const char* fmt, ...);
+// Checks hipGetLastError() after a launch.
+int check_launch(const char* what);
+// Number of compute units of the current device (cached per device).
+int device_cu_count();
+
+typedef __bf16 bf16_t;
+
+// Split plan of the decode: the sequence axis of every sequence is cut into
+// chunks of pages_per_split pages; chunk s of sequence b is non-empty when
+// s * pages_per_split < ceil(seq_lens[b] / page_tokens).
+struct SplitPlan {
+  int32_t n_splits;
+  int32_t pages_per_split;
+};
+SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages_per_seq, int32_t n_splits_req);
+
+// Partial results of one (sequence, split): acc [B, S, H, dl] floats, then
+// ml [B, S, H, 2] floats (running max in log2 units, sum of weights).
+struct DecodeArgs {
+  const void* q_lat;     // [B, H, dl]
+  const void* q_pe;      // [B, H, d_r]
+  const void* pool;      // [P, page_tokens, dl + d_r]
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  float* part_acc;
+  float* part_ml;
+  float* o_lat;          // [B, H, dl]
+  float* lse;            // [B, H] or nullptr
+  int32_t B, H, dl, d_r, page_tokens, max_pages;
+  int32_t n_splits, pages_per_split;
+  float scale_log2;      // sm_scale * log2(e)
+};
+
+// True when the MFMA kernel covers this shape (bf16 only).
+bool decode_mfma_supported(const tpla_shape_t& sh);
+int launch_decode_mfma(const DecodeArgs& a, hipStream_t st);
+int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st);
+int launch_decode_merge(const DecodeArgs& a, hipStream_t st);
+
+struct TransformArgs {
+  int32_t d_c, dtype, mode, inverse;
+  const float* signs;
+  const float* U;
+};
+int launch_transform_axis(const TransformArgs& t, const void* src, void* dst, int64_t n_outer,
+                          int64_t n_inner, hipStream_t st);
+struct ShardPools {
+  void* p[TPLA_MAX_G];
+};
+int launch_transform_paged(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
+                           const ShardPools& pools, const int32_t* page_ids, int64_t n_pages,
+                           hipStream_t st);
+int launch_write_mla_cache(const tpla_shape_t& sh, const void* c_raw, const void* k_pe,
+                           const int32_t* slot_mapping, int64_t T, float rms_eps, void* mla_pool,
+                           hipStream_t st);
+
+struct MuFactors {
+  float v[TPLA_MAX_G];
+};
+int launch_absorb_query(const tpla_shape_t& sh, const void* q_nope, const void* W_UK_t,
+                        const MuFactors& mu, void* q_lat, hipStream_t st);
+int launch_combine_shards(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
+                          hipStream_t st);
+
+// ---- small device helpers -------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return (float)x; }
+__device__ __forceinline__ float load_as_f32(const float* p) { return *p; }
+__device__ __forceinline__ float load_as_f32(const bf16_t* p) { return (float)*p; }
+__device__ __forceinline__ void store_from_f32(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_from_f32(bf16_t* p, float v) { *p = (bf16_t)v; }
+
+}  // namespace tpla

@@ -1,0 +1,83 @@
+"""Device buffers and call sequencing for one TPLA decode layer-step.
+
+Only marshalling: torch allocates device memory and provides the stream;
+every arithmetic step runs inside libtpla (see include/tpla.h).
+"""
+import math
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(dtype):
+    return torch.float32 if dtype in ("f32", B.TPLA_F32) else torch.bfloat16
+
+
+def to_device(stored, dtype, device="cuda"):
+    """Storage array (float32, or uint16 bf16 bit patterns) -> device tensor."""
+    a = np.ascontiguousarray(stored)
+    if dtype == "f32":
+        return torch.from_numpy(a).to(device)
+    return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def from_device_bits(t):
+    """Device tensor -> storage array (float32, or uint16 bit patterns for bf16)."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def make_shape(w):
+    """TplaShape of a workloads.Workload."""
+    return B.TplaShape(w.B, w.H, w.d_c, w.g, w.d_r, w.d_n, w.d_v, w.page_tokens,
+                       B.TPLA_F32 if w.dtype == "f32" else B.TPLA_BF16, w.sm_scale)
+
+
+class DecodeStep:
+    """Buffers for absorb -> g x decode_shard -> combine on one GPU."""
+
+    def __init__(self, shape, max_pages_per_seq, n_splits=0, device="cuda"):
+        self.shape = shape
+        self.max_pages = int(max_pages_per_seq)
+        self.n_splits = int(n_splits)
+        st = torch.float32 if shape.dtype == B.TPLA_F32 else torch.bfloat16
+        g, Bn, H, dl = shape.g, shape.B, shape.H, shape.d_c // shape.g
+        self.q_lat = torch.empty((g, Bn, H, dl), dtype=st, device=device)
+        self.o_lat = torch.empty((g, Bn, H, dl), dtype=torch.float32, device=device)
+        self.lse = torch.empty((g, Bn, H), dtype=torch.float32, device=device)
+        self.o = torch.empty((Bn, H, shape.d_v), dtype=torch.float32, device=device)
+        self.ws_bytes = B.tpla_workspace_bytes(shape, self.max_pages, self.n_splits)
+        if self.ws_bytes == 0:
+            raise B.TplaError(-2, B.tpla_last_error())
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+
+    def absorb(self, q_nope, W_UK_t, mu=None):
+        B.tpla_absorb_query(self.shape, q_nope, W_UK_t, mu, self.q_lat)
+
+    def decode(self, i, q_pe, shard_pool, block_table, seq_lens):
+        B.tpla_decode_shard(self.shape, self.q_lat[i], q_pe, shard_pool, block_table, self.max_pages,
+                            seq_lens, self.n_splits, self.workspace, self.ws_bytes,
+                            self.o_lat[i], self.lse[i])
+
+    def combine(self, W_UV_t):
+        B.tpla_combine_shards(self.shape, self.o_lat, W_UV_t, self.o)
+
+    def run(self, q_nope, q_pe, W_UK_t, W_UV_t, shard_pools, block_table, seq_lens, mu=None):
+        self.absorb(q_nope, W_UK_t, mu)
+        for i in range(self.shape.g):
+            self.decode(i, q_pe, shard_pools[i], block_table, seq_lens)
+        self.combine(W_UV_t)
+        return self.o
+
+
+def transform_weights(shape, mode, signs, U, W_UK, W_UV):
+    """W_UK [H,d_n,d_c] -> W_UK U (last axis); W_UV [H,d_c,d_v] -> U^T W_UV (middle axis)."""
+    W_UK_t = torch.empty_like(W_UK)
+    W_UV_t = torch.empty_like(W_UV)
+    H, d_n, d_c = W_UK.shape
+    B.tpla_transform_latent(shape, mode, 0, signs, U, W_UK, W_UK_t, H * d_n, 1)
+    B.tpla_transform_latent(shape, mode, 0, signs, U, W_UV, W_UV_t, H, W_UV.shape[2])
+    return W_UK_t, W_UV_t

@@ -1,0 +1,79 @@
+"""Helpers shared by the GPU parity tests (not collected by pytest)."""
+import numpy as np
+import torch
+
+import paper_2508_15881_amd as tp
+from paper_2508_15881_amd import pipeline as pl
+from paper_2508_15881_amd import workloads as wl
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}   # max|x - r| / max|r| per output tensor
+
+
+def rel_err(x, r):
+    x = np.asarray(x, dtype=np.float64)
+    r = np.asarray(r, dtype=np.float64)
+    assert x.shape == r.shape, (x.shape, r.shape)
+    den = np.max(np.abs(r))
+    return float(np.max(np.abs(x - r)) / (den if den > 0 else 1.0))
+
+
+def build_shard_problem(w, lens, seed_model=None, permute=True, slack_pages=3, poison=True, rng_extra=0):
+    """Seeded inputs of one shard's decode at widths of workload `w` with the
+    given sequence lengths: queries, a paged pool holding the shard's rows and
+    the page table.  Returns host arrays (storage form) and float64 copies."""
+    lens = np.asarray(lens, dtype=np.int64)
+    Bn = len(lens)
+    w = wl.scaled(w, B=Bn)
+    r = np.random.default_rng([w.seed, 77, rng_extra])
+    q_lat = wl.to_storage(r.standard_normal((Bn, w.H, w.dl)) * 0.35, w.dtype)
+    q_pe = wl.to_storage(r.standard_normal((Bn, w.H, w.d_r)), w.dtype)
+    pt = w.page_tokens
+    pages = (lens + pt - 1) // pt
+    n_used = int(pages.sum())
+    n_pool = max(1, n_used + slack_pages)
+    order = r.permutation(n_pool) if permute else np.arange(n_pool)
+    max_pages = max(1, int(pages.max()))
+    bt = np.zeros((Bn, max_pages), dtype=np.int32)
+    width = w.dl + w.d_r
+    pool = wl.nan_fill((n_pool, pt, width), w.dtype) if poison else wl.to_storage(np.zeros((n_pool, pt, width)), w.dtype)
+    rows64, k = [], 0
+    for b in range(Bn):
+        n = int(pages[b])
+        bt[b, :n] = order[k:k + n]
+        k += n
+        c, kp = wl.draw_sequence(w, b, int(lens[b]), width=w.dl)
+        rows = np.concatenate([c, kp], axis=1)
+        wl.place_rows(pool, bt[b, :n], rows)
+        rows64.append(wl.as_f64(rows, w.dtype))
+    return {"w": w, "q_lat": q_lat, "q_pe": q_pe, "pool": pool, "bt": bt, "lens": lens.astype(np.int32),
+            "max_pages": max_pages, "rows64": rows64}
+
+
+def run_decode_shard(prob, n_splits=0):
+    w = prob["w"]
+    shape = pl.make_shape(w)
+    dev = "cuda"
+    q_lat = pl.to_device(prob["q_lat"], w.dtype)
+    q_pe = pl.to_device(prob["q_pe"], w.dtype)
+    pool = pl.to_device(prob["pool"], w.dtype)
+    bt = torch.from_numpy(prob["bt"]).to(dev)
+    lens = torch.from_numpy(prob["lens"]).to(dev)
+    # host-side sanity before any launch: ids inside the pool, lengths inside the table
+    assert prob["bt"].min() >= 0 and prob["bt"].max() < prob["pool"].shape[0]
+    assert int(prob["lens"].max()) <= prob["max_pages"] * w.page_tokens
+    ws_bytes = tp.tpla_workspace_bytes(shape, prob["max_pages"], n_splits)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    o = torch.full((w.B, w.H, w.dl), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((w.B, w.H), float("nan"), dtype=torch.float32, device=dev)
+    tp.tpla_decode_shard(shape, q_lat, q_pe, pool, bt, prob["max_pages"], lens, n_splits, ws, ws_bytes, o, lse)
+    torch.cuda.synchronize()
+    return o.cpu().numpy(), lse.cpu().numpy()
+
+
+def oracle_decode_shard(prob):
+    from oracle import tpla_oracle as orc
+    w = prob["w"]
+    c = [r[:, :w.dl] for r in prob["rows64"]]
+    k = [r[:, w.dl:] for r in prob["rows64"]]
+    return orc.shard_attention(wl.as_f64(prob["q_lat"], w.dtype), wl.as_f64(prob["q_pe"], w.dtype), c, k, w.sm_scale)

@@ -1,0 +1,336 @@
+"""GPU parity: every C-ABI entry point against the float64 oracle on the same
+seeded inputs.  Tolerances: bit-exact for paging / copies, max|x-r|/max|r| <=
+1e-5 (float storage) or 1e-2 (bf16 storage, float accumulation) otherwise."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2508_15881_amd as tp
+from paper_2508_15881_amd import pipeline as pl
+from paper_2508_15881_amd import workloads as wl
+from oracle import tpla_oracle as orc
+from gpu_common import TOL, build_shard_problem, oracle_decode_shard, rel_err, run_decode_shard
+
+pytestmark = pytest.mark.gpu
+
+DSV3 = wl.CONFIGS["dsv3_4k"]
+KIMI = wl.CONFIGS["kimi_32k"]
+RAGGED = wl.CONFIGS["ragged_g4"]
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------ decode_shard
+MFMA_CASES = [
+    ("dsv3_g2_H64", DSV3, [1, 63, 64, 65, 700, 2049, 0, 31]),
+    ("kimi_g2_H32", KIMI, [129, 1000, 5, 64]),
+    ("ragged_g4_H64", RAGGED, [3000, 17, 256, 4097]),
+    ("mla_g1_H64", wl.scaled(DSV3, g=1), [333, 64, 1025]),
+    ("dsv3_g2_H128", wl.scaled(DSV3, H=128), [500, 130]),
+    ("dsv3_g2_H16", wl.scaled(DSV3, H=16), [500, 130]),
+]
+
+
+@pytest.mark.parametrize("name,w,lens", MFMA_CASES, ids=[c[0] for c in MFMA_CASES])
+@pytest.mark.parametrize("n_splits", [0, 1, 3])
+def test_decode_shard_bf16_matches_oracle(name, w, lens, n_splits):
+    _say(f"decode_shard bf16 {name} lens={lens} n_splits={n_splits}")
+    prob = build_shard_problem(w, lens)
+    o, lse = run_decode_shard(prob, n_splits)
+    ro, rl = oracle_decode_shard(prob)
+    nz = np.asarray(lens) > 0
+    assert rel_err(o, ro) <= TOL["bf16"]
+    assert np.max(np.abs(lse[nz] - rl[nz])) <= 1e-2
+    assert np.all(o[~nz] == 0) and np.all(np.isneginf(lse[~nz]))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decode_shard_generic_shapes(dtype):
+    # widths the matrix-core kernel does not cover: generic kernel, both storage types
+    w = wl.Workload("odd", B=3, H=5, d_c=80, g=2, d_r=24, d_n=16, d_v=16, dtype=dtype, seed=11)
+    for n_splits in (0, 1, 2):
+        _say(f"decode_shard generic {dtype} n_splits={n_splits}")
+        prob = build_shard_problem(w, [200, 0, 65])
+        o, lse = run_decode_shard(prob, n_splits)
+        ro, rl = oracle_decode_shard(prob)
+        assert rel_err(o, ro) <= TOL[dtype]
+        assert np.max(np.abs(lse[[0, 2]] - rl[[0, 2]])) <= TOL[dtype] * 10
+        assert np.all(o[1] == 0) and np.all(np.isneginf(lse[1]))
+
+
+def test_decode_shard_paging_is_bit_invariant():
+    lens = [700, 65, 1, 2048]
+    _say("decode_shard paging invariance")
+    a = build_shard_problem(DSV3, lens, permute=True, slack_pages=5, poison=True)
+    b = build_shard_problem(DSV3, lens, permute=False, slack_pages=0, poison=False)
+    for n_splits in (1, 4):
+        oa, la = run_decode_shard(a, n_splits)
+        ob, lb = run_decode_shard(b, n_splits)
+        assert np.array_equal(oa, ob) and np.array_equal(la, lb)
+        oa2, la2 = run_decode_shard(a, n_splits)
+        assert np.array_equal(oa, oa2) and np.array_equal(la, la2)     # reproducible bits
+    assert np.all(np.isfinite(oa))                                     # NaN tails / spare pages never leak
+
+
+def test_decode_shard_softmax_properties_at_long_context():
+    # one long sequence (spans many tiles and splits): weights sum to one and
+    # the output stays inside the rows' column range
+    prob = build_shard_problem(DSV3, [20000, 8191])
+    w = prob["w"]
+    o, lse = run_decode_shard(prob, 0)
+    ro, rl = oracle_decode_shard(prob)
+    assert rel_err(o, ro) <= TOL["bf16"]
+    assert np.max(np.abs(lse - rl)) <= 1e-2
+    for b in range(2):
+        lat = prob["rows64"][b][:, :w.dl]
+        assert np.all(o[b] <= lat.max(axis=0) + 1e-3) and np.all(o[b] >= lat.min(axis=0) - 1e-3)
+
+
+# ------------------------------------------------------------ tiny config, whole path
+def _full_problem(w):
+    m = wl.draw_model_side(w)
+    c64, k64, cs, ks = [], [], [], []
+    for b in range(w.B):
+        c, k = wl.draw_sequence(w, b, int(m["seq_lens"][b]), heavy=m["heavy"])
+        cs.append(c); ks.append(k)
+        c64.append(wl.as_f64(c, w.dtype)); k64.append(wl.as_f64(k, w.dtype))
+    pool = wl.nan_fill((m["n_pool_pages"], w.page_tokens, w.d_c + w.d_r), w.dtype)
+    for b in range(w.B):
+        n = (int(m["seq_lens"][b]) + w.page_tokens - 1) // w.page_tokens
+        wl.place_rows(pool, m["block_table"][b, :n], np.concatenate([cs[b], ks[b]], axis=1))
+    return m, pool, c64, k64
+
+
+def _run_full(w, m, mla_pool_np, mode, signs_np, U_np, mu, g=None):
+    g = w.g if g is None else g
+    wg = wl.scaled(w, g=g)
+    shape = pl.make_shape(wg)
+    dev = "cuda"
+    W_UK = pl.to_device(m["W_UK"], w.dtype); W_UV = pl.to_device(m["W_UV"], w.dtype)
+    q_nope = pl.to_device(m["q_nope"], w.dtype); q_pe = pl.to_device(m["q_pe"], w.dtype)
+    signs = None if signs_np is None else torch.from_numpy(signs_np).to(dev)
+    U = None if U_np is None else torch.from_numpy(np.ascontiguousarray(U_np, dtype=np.float32)).to(dev)
+    W_UK_t, W_UV_t = pl.transform_weights(shape, mode, signs, U, W_UK, W_UV)
+    mla_pool = pl.to_device(mla_pool_np, w.dtype)
+    P = mla_pool.shape[0]
+    pools = [torch.full((P, w.page_tokens, wg.dl + w.d_r), float("nan"), dtype=pl.torch_dtype(w.dtype), device=dev)
+             for _ in range(g)]
+    used = np.unique(np.concatenate([m["block_table"][b, :(int(m["seq_lens"][b]) + w.page_tokens - 1) // w.page_tokens]
+                                     for b in range(w.B)])).astype(np.int32)
+    page_ids = torch.from_numpy(used).to(dev)
+    tp.tpla_transform_latent_paged(shape, mode, signs, U, mla_pool, pools, page_ids, len(used))
+    step = pl.DecodeStep(shape, m["max_pages"])
+    bt = torch.from_numpy(m["block_table"]).to(dev); lens = torch.from_numpy(m["seq_lens"]).to(dev)
+    o = step.run(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt, lens, mu)
+    torch.cuda.synchronize()
+    return {"o": o.cpu().numpy(), "O_lat": step.o_lat.cpu().numpy(), "lse": step.lse.cpu().numpy(),
+            "Q_lat": wl.as_f64(pl.from_device_bits(step.q_lat), w.dtype)}
+
+
+@pytest.mark.parametrize("mode", ["identity", "hadamard", "dense"])
+def test_tiny_config_whole_path_fp32(mode):
+    w = wl.CONFIGS["tiny"]
+    _say(f"tiny config whole path, U={mode}")
+    m, pool, c64, k64 = _full_problem(w)
+    args = (wl.as_f64(m["q_nope"], "f32"), wl.as_f64(m["q_pe"], "f32"), wl.as_f64(m["W_UK"], "f32"),
+            wl.as_f64(m["W_UV"], "f32"), c64, k64)
+    if mode == "identity":
+        U64, code, signs, Unp = None, tp.TPLA_U_IDENTITY, None, None
+    elif mode == "hadamard":
+        U64, code, signs, Unp = orc.hadamard_U(w.d_c, m["signs"]), tp.TPLA_U_HADAMARD, m["signs"], None
+    else:
+        q, r = np.linalg.qr(np.random.default_rng(5).standard_normal((w.d_c, w.d_c)))
+        U64 = (q * np.sign(np.diag(r))).astype(np.float32).astype(np.float64)
+        code, signs, Unp = tp.TPLA_U_DENSE, None, U64
+    mu = [2.0, 2.0]
+    ref = orc.tpla_decode(*args, 2, w.sm_scale, U=U64, mu=mu)
+    got = _run_full(w, m, pool, code, signs, Unp, mu)
+    for key in ("Q_lat", "O_lat", "o"):
+        assert rel_err(got[key], ref[key]) <= TOL["f32"], key
+    assert np.max(np.abs(got["lse"] - ref["lse"])) <= 1e-5
+    # one slice: TPLA is MLA, whatever U is
+    got1 = _run_full(w, m, pool, code, signs, Unp, None, g=1)
+    mla = orc.mla_naive(*args, w.sm_scale)
+    assert rel_err(got1["o"], mla) <= TOL["f32"]
+
+
+# ------------------------------------------------------------ transform
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", ["hadamard", "dense", "identity"])
+def test_transform_latent_weights(dtype, mode):
+    _say(f"transform_latent {dtype} {mode}")
+    d_c, H, d_n, d_v = 128, 3, 8, 24
+    rng = np.random.default_rng(21)
+    shape = tp.TplaShape(1, H, d_c, 2, 16, d_n, d_v, 64, tp.TPLA_F32 if dtype == "f32" else tp.TPLA_BF16, 1.0)
+    W_UK = wl.to_storage(rng.standard_normal((H, d_n, d_c)), dtype)
+    W_UV = wl.to_storage(rng.standard_normal((H, d_c, d_v)), dtype)
+    signs_np = rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=d_c)
+    if mode == "hadamard":
+        U64, code, signs, U = orc.hadamard_U(d_c, signs_np), tp.TPLA_U_HADAMARD, torch.from_numpy(signs_np).cuda(), None
+    elif mode == "dense":
+        q, r = np.linalg.qr(rng.standard_normal((d_c, d_c)))
+        U64 = (q * np.sign(np.diag(r))).astype(np.float32).astype(np.float64)
+        code, signs, U = tp.TPLA_U_DENSE, None, torch.from_numpy(U64.astype(np.float32)).cuda()
+    else:
+        U64, code, signs, U = np.eye(d_c), tp.TPLA_U_IDENTITY, None, None
+    a, b = pl.transform_weights(shape, code, signs, U, pl.to_device(W_UK, dtype), pl.to_device(W_UV, dtype))
+    ra, rb = orc.reparameterize_weights(wl.as_f64(W_UK, dtype), wl.as_f64(W_UV, dtype), U64)
+    ga = wl.as_f64(pl.from_device_bits(a), dtype); gb = wl.as_f64(pl.from_device_bits(b), dtype)
+    if mode == "identity":
+        assert np.array_equal(ga, ra) and np.array_equal(gb, rb)
+    else:
+        tol = 1e-5 if dtype == "f32" else 2.0 ** -8
+        assert rel_err(ga, ra) <= tol and rel_err(gb, rb) <= tol
+    # inverse undoes the transform (U U^T = I)
+    back = torch.empty_like(a)
+    tp.tpla_transform_latent(shape, code, 1, signs, U, a, back, H * d_n, 1)
+    torch.cuda.synchronize()
+    assert rel_err(wl.as_f64(pl.from_device_bits(back), dtype), wl.as_f64(W_UK, dtype)) <= (1e-5 if dtype == "f32" else 2e-2)
+
+
+@pytest.mark.parametrize("dtype,d_c,g", [("bf16", 512, 2), ("bf16", 512, 4), ("f32", 64, 2), ("bf16", 96, 2)])
+def test_transform_latent_paged(dtype, d_c, g):
+    _say(f"transform_latent_paged {dtype} d_c={d_c} g={g}")
+    d_r, pt, P = 64 if d_c == 512 else 16, 64, 7
+    rng = np.random.default_rng(31)
+    shape = tp.TplaShape(1, 16, d_c, g, d_r, 8, 8, pt, tp.TPLA_F32 if dtype == "f32" else tp.TPLA_BF16, 1.0)
+    pool_np = wl.to_storage(rng.standard_normal((P, pt, d_c + d_r)), dtype)
+    pool = pl.to_device(pool_np, dtype)
+    ids_np = np.array([5, 0, 3], dtype=np.int32)
+    ids = torch.from_numpy(ids_np).cuda()
+    dl = d_c // g
+    pow2 = (d_c & (d_c - 1)) == 0
+    modes = [("identity", tp.TPLA_U_IDENTITY, None)]
+    if pow2:
+        modes.append(("hadamard", tp.TPLA_U_HADAMARD, rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=d_c)))
+    for name, code, signs_np in modes:
+        outs = [torch.zeros((P, pt, dl + d_r), dtype=pl.torch_dtype(dtype), device="cuda") for _ in range(g)]
+        signs = None if signs_np is None else torch.from_numpy(signs_np).cuda()
+        tp.tpla_transform_latent_paged(shape, code, signs, None, pool, outs, ids, len(ids_np))
+        torch.cuda.synchronize()
+        src64 = wl.as_f64(pool_np, dtype)
+        U64 = np.eye(d_c) if name == "identity" else orc.hadamard_U(d_c, signs_np)
+        for i in range(g):
+            got_bits = pl.from_device_bits(outs[i])
+            got = wl.as_f64(got_bits, dtype)
+            untouched = np.setdiff1d(np.arange(P), ids_np)
+            assert np.all(got[untouched] == 0)                                  # only listed pages are written
+            assert np.array_equal(got_bits[ids_np][:, :, dl:], pool_np[ids_np][:, :, d_c:])   # k_pe copied bit-exactly
+            ref = orc.transform_latent(src64[ids_np][:, :, :d_c], U64)[:, :, i * dl:(i + 1) * dl]
+            lat = got[ids_np][:, :, :dl]
+            if name == "identity":
+                assert np.array_equal(lat, ref)
+            elif dtype == "f32":
+                assert rel_err(lat, ref) <= 1e-5
+            else:
+                # one rounding of the float64 result; float butterflies may land on
+                # the other side of a tie for a tiny fraction of elements (1 ulp)
+                rr = orc.round_to_bf16(ref)
+                diff = lat != rr
+                assert diff.mean() <= 1e-3
+                assert np.all(np.abs(lat - rr)[diff] <= np.abs(rr[diff]) * 2.0 ** -7 + 1e-30)
+
+
+def test_write_mla_cache():
+    _say("write_mla_cache")
+    for dtype in ("f32", "bf16"):
+        d_c, d_r, pt, P, T = 512, 64, 64, 5, 150
+        rng = np.random.default_rng(41)
+        shape = tp.TplaShape(1, 16, d_c, 2, d_r, 8, 8, pt, tp.TPLA_F32 if dtype == "f32" else tp.TPLA_BF16, 1.0)
+        c = wl.to_storage(rng.standard_normal((T, d_c)) * np.exp(rng.uniform(-2, 2, size=(T, 1))), dtype)
+        k = wl.to_storage(rng.standard_normal((T, d_r)), dtype)
+        slots_np = rng.permutation(P * pt)[:T].astype(np.int32)
+        slots_np[7] = -1                                     # skipped token
+        pool = torch.zeros((P, pt, d_c + d_r), dtype=pl.torch_dtype(dtype), device="cuda")
+        for eps in (1e-6, -1.0):
+            pool.zero_()
+            tp.tpla_write_mla_cache(shape, pl.to_device(c, dtype), pl.to_device(k, dtype),
+                                    torch.from_numpy(slots_np).cuda(), T, eps, pool)
+            torch.cuda.synchronize()
+            got = wl.as_f64(pl.from_device_bits(pool), dtype).reshape(P * pt, d_c + d_r)
+            c64, k64 = wl.as_f64(c, dtype), wl.as_f64(k, dtype)
+            ref = orc.mla_cache_rows(c64, k64, eps) if eps >= 0 else np.concatenate([c64, k64], axis=1)
+            keep = slots_np >= 0
+            assert np.array_equal(got[slots_np[keep]][:, d_c:], ref[keep][:, d_c:])
+            tol = 1e-6 if dtype == "f32" else 2.0 ** -8
+            assert np.all(np.abs(got[slots_np[keep]][:, :d_c] - ref[keep][:, :d_c]) <= tol * np.abs(ref[keep][:, :d_c]) + 1e-30)
+            written = np.zeros(P * pt, dtype=bool); written[slots_np[keep]] = True
+            assert np.all(got[~written] == 0)
+
+
+# ------------------------------------------------------------ absorb / combine
+@pytest.mark.parametrize("dtype,Bn,H,g", [("bf16", 5, 64, 2), ("bf16", 17, 32, 4), ("f32", 3, 4, 2)])
+def test_absorb_and_combine(dtype, Bn, H, g):
+    _say(f"absorb/combine {dtype} B={Bn} H={H} g={g}")
+    d_c, d_n, d_v, d_r = (512, 128, 128, 64) if dtype == "bf16" else (64, 32, 32, 16)
+    rng = np.random.default_rng(51)
+    shape = tp.TplaShape(Bn, H, d_c, g, d_r, d_n, d_v, 64, tp.TPLA_F32 if dtype == "f32" else tp.TPLA_BF16, 1.0)
+    q = wl.to_storage(rng.standard_normal((Bn, H, d_n)), dtype)
+    Wk = wl.to_storage(rng.standard_normal((H, d_n, d_c)) * 0.05, dtype)
+    Wv = wl.to_storage(rng.standard_normal((H, d_c, d_v)) * 0.05, dtype)
+    mu = list(rng.uniform(0.5, 2.5, size=g))
+    dl = d_c // g
+    q_lat = torch.empty((g, Bn, H, dl), dtype=pl.torch_dtype(dtype), device="cuda")
+    tp.tpla_absorb_query(shape, pl.to_device(q, dtype), pl.to_device(Wk, dtype), mu, q_lat)
+    ref = orc.absorb_query(wl.as_f64(q, dtype), wl.as_f64(Wk, dtype), g, np.asarray(mu, dtype=np.float32).astype(np.float64))
+    torch.cuda.synchronize()
+    assert rel_err(wl.as_f64(pl.from_device_bits(q_lat), dtype), ref) <= (1e-5 if dtype == "f32" else 2.0 ** -8)
+    o_lat_np = rng.standard_normal((g, Bn, H, dl)).astype(np.float32)
+    o = torch.empty((Bn, H, d_v), dtype=torch.float32, device="cuda")
+    tp.tpla_combine_shards(shape, torch.from_numpy(o_lat_np).cuda(), pl.to_device(Wv, dtype), o)
+    torch.cuda.synchronize()
+    assert rel_err(o.cpu().numpy(), orc.combine_shards(o_lat_np.astype(np.float64), wl.as_f64(Wv, dtype))) <= 1e-5
+
+
+# ------------------------------------------------------------ whole path, bf16, model-shaped
+@pytest.mark.parametrize("name,lens", [("dsv3_4k", [300, 1100, 64]), ("kimi_32k", [257, 900]), ("ragged_g4", [1500, 70, 640])])
+def test_whole_path_bf16_scaled_configs(name, lens):
+    w0 = wl.CONFIGS[name]
+    _say(f"whole path bf16 {name} lens={lens}")
+    w = wl.scaled(w0, B=len(lens), context=0, ragged=())
+    m = wl.draw_model_side(wl.scaled(w, context=max(lens)))
+    m["seq_lens"] = np.asarray(lens, dtype=np.int32)
+    # rebuild the page table for the ragged lengths (permuted pool with spare pages)
+    r = np.random.default_rng([w.seed, 5])
+    pages = (np.asarray(lens) + 63) // 64
+    P = int(pages.sum()) + 4
+    order = r.permutation(P)
+    bt = np.zeros((w.B, int(pages.max())), dtype=np.int32); k = 0
+    for b in range(w.B):
+        bt[b, :pages[b]] = order[k:k + pages[b]]; k += pages[b]
+    m["block_table"], m["max_pages"], m["n_pool_pages"] = bt, int(pages.max()), P
+    dev = "cuda"
+    shape = pl.make_shape(w)
+    c64, k64 = [], []
+    mla_pool = torch.full((P, 64, w.d_c + w.d_r), float("nan"), dtype=torch.bfloat16, device=dev)
+    for b in range(w.B):
+        c, kp = wl.draw_sequence(w, b, lens[b], heavy=m["heavy"])
+        slots = torch.from_numpy(wl.slot_mapping(bt[b, :pages[b]], lens[b], 64)).to(dev)
+        eps = 1e-6 if w.rms_prefill else -1.0
+        tp.tpla_write_mla_cache(shape, pl.to_device(c, "bf16"), pl.to_device(kp, "bf16"), slots, lens[b], eps, mla_pool)
+        cc = wl.as_f64(c, "bf16")
+        # the cache stores bf16: the oracle rounds where the data is stored
+        c64.append(orc.round_to_bf16(orc.rms_norm_unit(cc, eps)) if w.rms_prefill else cc)
+        k64.append(wl.as_f64(kp, "bf16"))
+    hadamard = w.transform == "hadamard"
+    signs_np = m["signs"] if hadamard else None
+    U64 = orc.hadamard_U(w.d_c, signs_np) if hadamard else None
+    code = tp.TPLA_U_HADAMARD if hadamard else tp.TPLA_U_IDENTITY
+    signs = torch.from_numpy(signs_np).to(dev) if hadamard else None
+    W_UK_t, W_UV_t = pl.transform_weights(shape, code, signs, None, pl.to_device(m["W_UK"], "bf16"), pl.to_device(m["W_UV"], "bf16"))
+    pools = [torch.full((P, 64, w.dl + w.d_r), float("nan"), dtype=torch.bfloat16, device=dev) for _ in range(w.g)]
+    used = torch.from_numpy(np.unique(np.concatenate([bt[b, :pages[b]] for b in range(w.B)])).astype(np.int32)).to(dev)
+    tp.tpla_transform_latent_paged(shape, code, signs, None, mla_pool, pools, used, used.numel())
+    step = pl.DecodeStep(shape, m["max_pages"])
+    mu = [float(w.g)] * w.g
+    o = step.run(pl.to_device(m["q_nope"], "bf16"), pl.to_device(m["q_pe"], "bf16"), W_UK_t, W_UV_t, pools,
+                 torch.from_numpy(bt).to(dev), torch.from_numpy(m["seq_lens"]).to(dev), mu)
+    torch.cuda.synchronize()
+    ref = orc.tpla_decode(wl.as_f64(m["q_nope"], "bf16"), wl.as_f64(m["q_pe"], "bf16"), wl.as_f64(m["W_UK"], "bf16"),
+                          wl.as_f64(m["W_UV"], "bf16"), c64, k64, w.g, w.sm_scale, U=U64, mu=mu)
+    assert rel_err(wl.as_f64(pl.from_device_bits(step.q_lat), "bf16"), ref["Q_lat"]) <= TOL["bf16"]
+    assert rel_err(step.o_lat.cpu().numpy(), ref["O_lat"]) <= TOL["bf16"]
+    assert rel_err(o.cpu().numpy(), ref["o"]) <= TOL["bf16"]
+    assert np.max(np.abs(step.lse.cpu().numpy() - ref["lse"])) <= 2e-2
