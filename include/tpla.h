@@ -171,6 +171,20 @@ int tpla_decode_shard(const tpla_shape_t* shape,
 int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t,
                         float* o, void* stream);
 
+/*
+ * Measurement aid for the split kernel of tpla_decode_shard (the pass over
+ * the cache of Sec. 4.5's memory-bound decode).  After
+ * tpla_profile_enable(n) with n > 0, each tpla_decode_shard call on this
+ * thread brackets that kernel -- not the merge that follows it -- with a pair
+ * of HIP events on the call's stream, for at most n calls.
+ * tpla_profile_collect waits for the recorded events, writes the elapsed
+ * milliseconds of each bracketed kernel to the HOST array ms (capacity
+ * entries), stores the count in *n_records and starts over.
+ * tpla_profile_enable(0) switches the recording off and frees the events.
+ */
+int tpla_profile_enable(int32_t max_records);
+int tpla_profile_collect(float* ms, int32_t capacity, int32_t* n_records);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,7 @@ TPLA_MAX_G = 8
 EXPORTS = (
     "tpla_last_error", "tpla_version", "tpla_transform_latent", "tpla_transform_latent_paged",
     "tpla_write_mla_cache", "tpla_absorb_query", "tpla_workspace_bytes", "tpla_decode_shard",
-    "tpla_combine_shards",
+    "tpla_combine_shards", "tpla_profile_enable", "tpla_profile_collect",
 )
 
 
@@ -77,6 +77,10 @@ def load_library():
     lib.tpla_decode_shard.argtypes = [shp, vp, vp, vp, vp, i32, vp, i32, vp, ctypes.c_size_t, vp, vp, vp]
     lib.tpla_combine_shards.restype = ctypes.c_int
     lib.tpla_combine_shards.argtypes = [shp, vp, vp, vp, vp]
+    lib.tpla_profile_enable.restype = ctypes.c_int
+    lib.tpla_profile_enable.argtypes = [i32]
+    lib.tpla_profile_collect.restype = ctypes.c_int
+    lib.tpla_profile_collect.argtypes = [fp, i32, ctypes.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -163,3 +167,15 @@ def tpla_decode_shard(shape, q_lat_i, q_pe, shard_pool, block_table, max_pages_p
 def tpla_combine_shards(shape, o_lat, W_UV_t, o, stream=None):
     _check(load_library().tpla_combine_shards(
         ctypes.byref(shape), _ptr(o_lat), _ptr(W_UV_t), _ptr(o), _stream(stream)))
+
+
+def tpla_profile_enable(max_records):
+    _check(load_library().tpla_profile_enable(max_records))
+
+
+def tpla_profile_collect(capacity):
+    """Elapsed milliseconds of every bracketed split kernel since the last collect."""
+    buf = (ctypes.c_float * max(1, capacity))()
+    n = ctypes.c_int32(0)
+    _check(load_library().tpla_profile_collect(buf, capacity, ctypes.byref(n)))
+    return [buf[i] for i in range(n.value)]

@@ -37,6 +37,20 @@ int device_cu_count() {
   return cached[dev];
 }
 
+// ---- optional event bracketing of the split kernel -------------------------
+struct ProfileState {
+  hipEvent_t* ev = nullptr;   // 2 * cap events
+  int cap = 0;
+  int used = 0;
+};
+static thread_local ProfileState g_prof;
+
+static void profile_mark(hipStream_t st, bool start) {
+  if (g_prof.cap == 0 || g_prof.used >= g_prof.cap) return;
+  (void)hipEventRecord(g_prof.ev[2 * g_prof.used + (start ? 0 : 1)], st);
+  if (!start) ++g_prof.used;
+}
+
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static int check_dtype(const tpla_shape_t* sh) {
@@ -239,10 +253,12 @@ int tpla_decode_shard(const tpla_shape_t* shape, const void* q_lat_i, const void
   a.scale_log2 = shape->sm_scale * 1.4426950408889634f;
 
   hipStream_t st = (hipStream_t)stream;
+  profile_mark(st, true);
   if (shape->dtype == TPLA_BF16 && decode_mfma_supported(*shape))
     rc = launch_decode_mfma(a, st);
   else
     rc = launch_decode_generic(a, shape->dtype, st);
+  profile_mark(st, false);
   if (rc) return rc;
   return launch_decode_merge(a, st);
 }
@@ -255,6 +271,40 @@ int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const voi
   if (!aligned16(o_lat) || !aligned16(W_UV_t) || !aligned16(o))
     return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
   return launch_combine_shards(*shape, o_lat, W_UV_t, o, (hipStream_t)stream);
+}
+
+int tpla_profile_enable(int32_t max_records) {
+  if (max_records < 0 || max_records > (1 << 20)) return fail(TPLA_ERR_SHAPE, "max_records=%d", max_records);
+  if (g_prof.ev) {
+    for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    delete[] g_prof.ev;
+    g_prof = ProfileState();
+  }
+  if (max_records == 0) return TPLA_OK;
+  g_prof.ev = new hipEvent_t[2 * (size_t)max_records];
+  for (int i = 0; i < 2 * max_records; ++i) {
+    if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
+      delete[] g_prof.ev;
+      g_prof = ProfileState();
+      return fail(TPLA_ERR_HIP, "hipEventCreate failed");
+    }
+  }
+  g_prof.cap = max_records;
+  return TPLA_OK;
+}
+
+int tpla_profile_collect(float* ms, int32_t capacity, int32_t* n_records) {
+  if (!ms || !n_records) return fail(TPLA_ERR_NULL, "ms/n_records is NULL");
+  int n = g_prof.used < capacity ? g_prof.used : capacity;
+  for (int i = 0; i < n; ++i) {
+    if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess ||
+        hipEventElapsedTime(&ms[i], g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess)
+      return fail(TPLA_ERR_HIP, "event %d could not be read", i);
+  }
+  *n_records = n;
+  g_prof.used = 0;
+  return TPLA_OK;
 }
 
 #pragma GCC visibility pop
