@@ -82,11 +82,18 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages, int32_t n_split
   SplitPlan p;
   int32_t n = n_splits_req;
   if (n <= 0) {
-    // Aim for about three resident workgroups per compute unit, but keep a
-    // chunk at least 4 pages long so the partial results stay a small
-    // fraction of the cache bytes read.
-    const int slots = device_cu_count() * 3;
-    n = (slots + sh.B - 1) / sh.B;
+    // One resident workgroup per slot and no second round: with B * n at most
+    // the number of workgroups the chip holds at once, every chunk runs
+    // concurrently and chunks are equal (this assumes sequences of similar
+    // length; pass n_splits for a ragged batch).  A chunk keeps at least 4
+    // pages so the partial results stay a small fraction of the bytes read.
+    int per_cu = 4;
+    if (sh.dtype == TPLA_BF16 && decode_mfma_supported(sh)) {
+      per_cu = decode_mfma_blocks_per_cu(sh);
+      if (per_cu <= 0) per_cu = 2;
+    }
+    const int slots = device_cu_count() * per_cu;
+    n = slots / sh.B;
     const int32_t cap = (max_pages + 3) / 4;
     if (n > cap) n = cap;
     if (n < 1) n = 1;

@@ -27,6 +27,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 #define TPLA_LDS(p) ((__attribute__((address_space(3))) s16x4*)(p))
 
 constexpr int PAGE_TOKENS = 64;
+constexpr float LAZY = 8.0f;   // log2 units: the softmax reference lags the running maximum by at most this
 
 // 16-byte pieces of a tile are stored at a swizzled position so that both
 // the row-wise reads (16 tokens x 16 B at one column) and the transposing
@@ -78,14 +79,20 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
   auto fetch = [&](int t) {
     const int T = p0 * TPP + t;
     const int page = bt[T / TPP];
-    const u32x4* src = pool + (size_t)page * (PAGE_TOKENS * RC) + (size_t)(T % TPP) * TC;
+    const u32x4* src = pool + (size_t)page * (PAGE_TOKENS * RC) + (size_t)(T % TPP) * TC + tid;
     const int valid = t_end - (t_begin + t * TOK);   // rows >= valid are not read
+    if (valid >= TOK) {
 #pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      if (st_tok[j] < valid)
-        pre[j] = __builtin_nontemporal_load(src + tid + j * NT);
-      else
-        pre[j] = u32x4{0u, 0u, 0u, 0u};
+      for (int j = 0; j < CPT; ++j)
+        if ((j + 1) * NT <= TC || st_tok[j] < TOK) pre[j] = __builtin_nontemporal_load(src + j * NT);
+    } else {
+#pragma unroll
+      for (int j = 0; j < CPT; ++j) {
+        if (st_tok[j] < valid)
+          pre[j] = __builtin_nontemporal_load(src + j * NT);
+        else
+          pre[j] = u32x4{0u, 0u, 0u, 0u};
+      }
     }
   };
 
@@ -147,34 +154,43 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
     }
 
     // ---- online softmax (lane = one head; tokens 16*tb + 4*q4 + i) ----------
+    // The reference m_run of the exponentials is only moved when some score
+    // exceeds it by more than LAZY (weights stay <= 2^LAZY, harmless in
+    // float), so the accumulator rescale is off the common path.
     const int valid = t_end - (t_begin + t * TOK);
-    float mx = -INFINITY;
+    if (valid < TOK) {
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (16 * tb + 4 * q4 + i >= valid) sacc[tb][i] = -INFINITY;
+    }
+    float mx = sacc[0][0];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float v = sacc[tb][i] * a.scale_log2;
-        if (16 * tb + 4 * q4 + i >= valid) v = -INFINITY;
-        sacc[tb][i] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      for (int i = 0; i < 4; ++i) mx = fmaxf(mx, sacc[tb][i]);
+    mx *= a.scale_log2;
+    if (__any(mx > m_run + LAZY)) {
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int d = 0; d < DB; ++d) acc[d] *= alpha;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float p = __builtin_amdgcn_exp2f(sacc[tb][i] - m_new);
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[tb][i], a.scale_log2, -m_run));
         sacc[tb][i] = p;
         psum += p;
       }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int d = 0; d < DB; ++d) acc[d] *= alpha;
+    l_run += psum;
 
     // ---- output: O^T += V^T P^T ----------------------------------------------
 #pragma unroll
@@ -217,39 +233,76 @@ bool decode_mfma_supported(const tpla_shape_t& sh) {
   return sh.H == 16 || sh.H == 32 || sh.H == 64 || sh.H == 128;
 }
 
+// Kernel entry, its LDS size and how many of its workgroups fit on one
+// compute unit (0 when the runtime cannot tell, e.g. without a device).
+struct KernelInfo {
+  void (*fn)(DecodeArgs) = nullptr;
+  size_t smem = 0;
+  int threads = 0;
+  int blocks_per_cu = 0;
+  bool ready = false;
+};
+
 template <int DL, int NW>
-static int launch_one(const DecodeArgs& a, hipStream_t st) {
+static int kernel_info(KernelInfo** out) {
   constexpr int TOK = 32;
-  constexpr size_t smem = 2u * TOK * ((DL + 64) / 8) * 16;
-  auto kern = decode_mfma_kernel<DL, 64, NW, TOK>;
-  static bool attr_set = false;   // dynamic LDS above the 64 KiB default needs opting in
-  if (smem > 64 * 1024 && !attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-      return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", smem);
-    attr_set = true;
+  static KernelInfo info;
+  if (!info.ready) {
+    info.fn = decode_mfma_kernel<DL, 64, NW, TOK>;
+    info.smem = 2u * TOK * ((DL + 64) / 8) * 16;
+    info.threads = NW * 64;
+    // dynamic LDS above the 64 KiB default needs opting in
+    if (info.smem > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)info.smem) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", info.smem);
+    }
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(info.fn), info.threads,
+                                                     info.smem) != hipSuccess) {
+      (void)hipGetLastError();
+      n = 0;
+    }
+    info.blocks_per_cu = n;
+    info.ready = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.n_splits)), dim3(NW * 64), smem, st, a);
-  return check_launch("decode_mfma_kernel");
+  *out = &info;
+  return TPLA_OK;
 }
 
 template <int DL>
-static int launch_dl(const DecodeArgs& a, hipStream_t st) {
-  switch (a.H) {
-    case 16: return launch_one<DL, 1>(a, st);
-    case 32: return launch_one<DL, 2>(a, st);
-    case 64: return launch_one<DL, 4>(a, st);
-    case 128: return launch_one<DL, 8>(a, st);
+static int kernel_info_dl(int H, KernelInfo** out) {
+  switch (H) {
+    case 16: return kernel_info<DL, 1>(out);
+    case 32: return kernel_info<DL, 2>(out);
+    case 64: return kernel_info<DL, 4>(out);
+    case 128: return kernel_info<DL, 8>(out);
   }
-  return fail(TPLA_ERR_UNSUPPORTED, "H=%d", a.H);
+  return fail(TPLA_ERR_UNSUPPORTED, "H=%d", H);
+}
+
+static int kernel_info_for(int dl, int H, KernelInfo** out) {
+  switch (dl) {
+    case 128: return kernel_info_dl<128>(H, out);
+    case 256: return kernel_info_dl<256>(H, out);
+    case 512: return kernel_info_dl<512>(H, out);
+  }
+  return fail(TPLA_ERR_UNSUPPORTED, "d_c/g=%d", dl);
+}
+
+int decode_mfma_blocks_per_cu(const tpla_shape_t& sh) {
+  KernelInfo* k = nullptr;
+  if (kernel_info_for(sh.d_c / sh.g, sh.H, &k) != TPLA_OK) return 0;
+  return k->blocks_per_cu;
 }
 
 int launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
-  switch (a.dl) {
-    case 128: return launch_dl<128>(a, st);
-    case 256: return launch_dl<256>(a, st);
-    case 512: return launch_dl<512>(a, st);
-  }
-  return fail(TPLA_ERR_UNSUPPORTED, "d_c/g=%d", a.dl);
+  KernelInfo* k = nullptr;
+  const int rc = kernel_info_for(a.dl, a.H, &k);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k->fn, dim3((unsigned)(a.B * a.n_splits)), dim3(k->threads), k->smem, st, a);
+  return check_launch("decode_mfma_kernel");
 }
 
 }  // namespace tpla

@@ -44,6 +44,9 @@ struct DecodeArgs {
 
 // True when the MFMA kernel covers this shape (bf16 only).
 bool decode_mfma_supported(const tpla_shape_t& sh);
+// Workgroups of the matrix-core kernel for this shape that fit on one compute
+// unit (0 = unknown).
+int decode_mfma_blocks_per_cu(const tpla_shape_t& sh);
 int launch_decode_mfma(const DecodeArgs& a, hipStream_t st);
 int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st);
 int launch_decode_merge(const DecodeArgs& a, hipStream_t st);
