@@ -26,7 +26,7 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
     "-I", INCLUDE, "-I", CSRC,
-]
+] + os.environ.get("TPLA_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def _run(cmd):

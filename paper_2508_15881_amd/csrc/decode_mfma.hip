@@ -2,54 +2,94 @@
 //
 // One workgroup = one (sequence, split).  It walks its pages in tiles of TOK
 // tokens.  A tile (TOK rows of d_c/g + d_r bf16, contiguous inside a page)
-// is fetched with 128-bit loads into registers one tile ahead, then written
-// to LDS, where all heads share it.  Wave w owns heads [16w, 16w+16):
+// goes straight from global memory into a ring of NSTAGE LDS buffers with
+// 128-bit direct-to-LDS loads, two tiles ahead of the one being consumed, and
+// is shared there by all heads.  Wave w owns heads [16w, 16w+16):
 //   S^T[tok, head] = K[tok, :] . Q[head, :]      MFMA 16x16x32, M = tokens, N = heads
-//   online softmax per head (one head per lane column, 16-lane DPP-free
-//   layout: a lane only ever sees its own head)
+//   online softmax per head (a lane only ever sees one head)
 //   O^T[dim, head] += V^T[dim, tok] . P^T[tok, head]   M = latent dims, N = heads
 // The latent prefix of a row is both key and value, so the same LDS tile is
 // read row-wise for the scores and through the transposing LDS read for the
 // output.  The S^T accumulator layout is already the B-operand layout of the
 // second product once the token order inside a 32-token step is permuted
 // identically for V^T, so P never leaves registers.
+//
+// LDS reads of the tiles are issued from inline assembly with hand-placed
+// lgkmcnt waits: the compiler would otherwise make every LDS read wait for
+// all outstanding direct-to-LDS loads, which would serialise the prefetch.
+#include <utility>
 #include "tpla_internal.h"
 
 namespace tpla {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-#define TPLA_LDS(p) ((__attribute__((address_space(3))) s16x4*)(p))
 
 constexpr int PAGE_TOKENS = 64;
 constexpr float LAZY = 8.0f;   // log2 units: the softmax reference lags the running maximum by at most this
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// Compile-time loop: f receives std::integral_constant<int, i>, so i can feed
+// instruction immediates.
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
+
+// s_waitcnt immediate that only waits on the vector-memory counter.
+__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+template <int OFF>
+__device__ __forceinline__ void lds_read_b128(bf16x8& dst, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+// Transposing read: lane j of each 16-lane group points at 4 bf16 of row j/4,
+// columns 4*(j%4)..; lane i receives column i of those 4 rows.
+template <int OFF>
+__device__ __forceinline__ void lds_read_tr_b64(u32x2& dst, unsigned addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+// Waits until at most N LDS operations of this wave are outstanding; the
+// operands are tied so that their consumers cannot be scheduled before it.
+template <int N>
+__device__ __forceinline__ void lds_wait(bf16x8& a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
 
 // 16-byte pieces of a tile are stored at a swizzled position so that both
 // the row-wise reads (16 tokens x 16 B at one column) and the transposing
 // reads (16 tokens x 32 B at one column) spread over all LDS banks: piece c
 // of token `tok` lives at piece index tok * RC + (c ^ ((tok >> 1) & 7)).
-__device__ __forceinline__ int swz(int tok, int c, int RC) { return tok * RC + (c ^ ((tok >> 1) & 7)); }
+// The direct-to-LDS load writes lane l of an instruction at base + 16 l, so
+// the swizzle is applied to the global address each lane fetches from.
 
-template <int DL, int DR, int NW, int TOK>
+template <int DL, int DR, int NW, int TOK, int NSTAGE>
 __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
   constexpr int RC = (DL + DR) / 8;      // 16-byte pieces per row
   constexpr int KS = (DL + DR) / 32;     // k-steps of the score product
   constexpr int DB = DL / 16;            // 16-wide blocks of latent dims
   constexpr int TB = TOK / 16;           // 16-token blocks per tile
   constexpr int S2 = TOK / 32;           // 32-token k-steps of the output product
-  constexpr int NT = NW * 64;
   constexpr int TC = TOK * RC;           // pieces per tile
-  constexpr int CPT = (TC + NT - 1) / NT;
+  constexpr int NI = TC / 64;            // direct-to-LDS instructions per tile
+  constexpr int CPT = (NI + NW - 1) / NW;   // of which each wave issues this many
   constexpr int TPP = PAGE_TOKENS / TOK; // tiles per page
+  constexpr int TILE_BYTES = TC * 16;
   static_assert(RC % 8 == 0, "row must be a multiple of 64 elements");
-  static_assert(TOK % 32 == 0 && PAGE_TOKENS % TOK == 0, "tile size");
+  static_assert(TOK % 32 == 0 && PAGE_TOKENS % TOK == 0 && TC % 64 == 0, "tile size");
+  static_assert(NSTAGE == 3, "the wait counts below assume two tiles in flight");
 
-  extern __shared__ u32x4 smem[];        // 2 tiles
+  extern __shared__ u32x4 smem[];        // NSTAGE tiles
+  const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j16 = lane & 15, q4 = lane >> 4;
@@ -64,37 +104,76 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
   const int t_end = min(p1 * PAGE_TOKENS, L);
   const int ntiles = (t_end - t_begin + TOK - 1) / TOK;
   const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
-  const u32x4* pool = static_cast<const u32x4*>(a.pool);
+  const char* pool = static_cast<const char*>(a.pool);
 
-  // ---- staging bookkeeping: piece x = tid + j*NT of a tile -----------------
-  int st_tok[CPT], st_slot[CPT];
+  // ---- direct-to-LDS bookkeeping ---------------------------------------------
+  // Instruction k of a tile fills LDS pieces [64k, 64k+64).  This wave issues
+  // k = wave + j*NW; when NI is not a multiple of NW the surplus instruction
+  // repeats the wave's previous one (same data to the same place).
+  int ld_tok[CPT];          // token row of the piece this lane fetches
+  unsigned ld_goff[CPT];    // its byte offset inside the tile in global memory
+  int ld_k[CPT];
 #pragma unroll
   for (int j = 0; j < CPT; ++j) {
-    const int x = tid + j * NT;
-    const int tok = x / RC, c = x % RC;
-    st_tok[j] = (x < TC) ? tok : TOK;    // TOK = never valid
-    st_slot[j] = swz(tok, c, RC);
+    int k = wave + j * NW;
+    if (k >= NI) k -= NW;
+    const int x = k * 64 + lane;                 // LDS piece index
+    const int tok = x / RC, cs = x % RC;         // swizzled position -> source piece
+    ld_k[j] = k;
+    ld_tok[j] = tok;
+    ld_goff[j] = (unsigned)((tok * RC + (cs ^ ((tok >> 1) & 7))) * 16);
   }
-  u32x4 pre[CPT];
-  auto fetch = [&](int t) {
+  // Page ids of this chunk live in a register, 64 pages at a time (lane i
+  // holds page p0 + pg_base + i), and are read back with v_readlane: a memory
+  // load per tile would have to wait for every direct-to-LDS load before it.
+  int pg_base = 0;
+  int pg_reg = bt[min(p0 + lane, p1 - 1)];
+  asm volatile("" : "+v"(pg_reg));
+  auto issue = [&](int t) {
     const int T = p0 * TPP + t;
-    const int page = bt[T / TPP];
-    const u32x4* src = pool + (size_t)page * (PAGE_TOKENS * RC) + (size_t)(T % TPP) * TC + tid;
+    const int pg = t / TPP;                 // page of this chunk, uniform
+    if (pg - pg_base >= 64) {
+      pg_base += 64;
+      pg_reg = bt[min(p0 + pg_base + lane, p1 - 1)];
+      asm volatile("" : "+v"(pg_reg));      // the load's wait stays inside this branch
+    }
+    const int page = __builtin_amdgcn_readlane(pg_reg, pg - pg_base);
+    const char* src = pool + (size_t)page * (PAGE_TOKENS * RC * 16) + (size_t)(T % TPP) * TILE_BYTES;
     const int valid = t_end - (t_begin + t * TOK);   // rows >= valid are not read
-    if (valid >= TOK) {
+    char* dst = reinterpret_cast<char*>(smem) + (t % NSTAGE) * TILE_BYTES;
 #pragma unroll
-      for (int j = 0; j < CPT; ++j)
-        if ((j + 1) * NT <= TC || st_tok[j] < TOK) pre[j] = __builtin_nontemporal_load(src + j * NT);
-    } else {
-#pragma unroll
-      for (int j = 0; j < CPT; ++j) {
-        if (st_tok[j] < valid)
-          pre[j] = __builtin_nontemporal_load(src + j * NT);
-        else
-          pre[j] = u32x4{0u, 0u, 0u, 0u};
-      }
+    for (int j = 0; j < CPT; ++j) {
+      // every lane issues (the wait counts rely on it); rows past the end of
+      // the sequence fetch row 0 of the tile instead and are zeroed afterwards
+      const unsigned off = (ld_tok[j] < valid) ? ld_goff[j] : (ld_goff[j] % (RC * 16));
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + off),
+                                       (__attribute__((address_space(3))) void*)(dst + ld_k[j] * 1024),
+                                       16, 0, 2 /* streaming: do not keep in L2 */);
     }
   };
+
+  // ---- per-lane LDS byte offsets -------------------------------------------
+  // score product: token 16*tb + j16, piece 4*ks + q4
+  const int xk = (j16 >> 1) & 7;
+  unsigned k_off[2];
+  k_off[0] = (unsigned)((j16 * RC + ((q4) ^ xk)) * 16);
+  k_off[1] = (unsigned)((j16 * RC + ((4 | q4) ^ xk)) * 16);
+  // output product: token 4*q4 + (j16>>2) (+16), dims 16*db + 4*(j16&3) .. +4
+  const int v_tok = 4 * q4 + (j16 >> 2);
+  const int xv = (v_tok >> 1) & 7;
+  const int cb = (j16 & 3) >> 1;
+  unsigned v_off[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+    v_off[d] = (unsigned)((v_tok * RC + (((d << 1) | cb) ^ xv)) * 16 + (j16 & 1) * 8);
+
+  f32x4 acc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d) acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+
+  issue(0);
+  if (ntiles > 1) issue(1);
 
   // ---- this wave's 16 heads of the query, as B operands --------------------
   const int head = wave * 16 + j16;
@@ -108,56 +187,67 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
       qreg[ks] = (k0 < DL) ? *reinterpret_cast<const bf16x8*>(ql + k0)
                            : *reinterpret_cast<const bf16x8*>(qp + (k0 - DL));
     }
+    // complete these loads here: a wait left for their first use would sit
+    // inside the tile loop and drain the prefetched tiles on every iteration
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));
   }
 
-  // ---- per-lane LDS byte offsets -------------------------------------------
-  // score product: token 16*tb + j16, piece 4*ks + q4
-  const int xk = (j16 >> 1) & 7;
-  int k_off[2];
-  k_off[0] = (j16 * RC + ((q4) ^ xk)) * 16;
-  k_off[1] = (j16 * RC + ((4 | q4) ^ xk)) * 16;
-  // output product: token 4*q4 + (j16>>2) (+16), dims 16*db + 4*(j16&3) .. +4
-  const int v_tok = 4 * q4 + (j16 >> 2);
-  const int xv = (v_tok >> 1) & 7;
-  const int cb = (j16 & 3) >> 1;
-  int v_off[4];
-#pragma unroll
-  for (int d = 0; d < 4; ++d) v_off[d] = (v_tok * RC + (((d << 1) | cb) ^ xv)) * 16 + (j16 & 1) * 8;
 
-  f32x4 acc[DB];
-#pragma unroll
-  for (int d = 0; d < DB; ++d) acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
-
-  fetch(0);
   for (int t = 0; t < ntiles; ++t) {
-    u32x4* buf = smem + (t & 1) * TC;
-#pragma unroll
-    for (int j = 0; j < CPT; ++j)
-      if (st_tok[j] < TOK) buf[st_slot[j]] = pre[j];
-    if (t + 1 < ntiles) fetch(t + 1);
-    __syncthreads();
-    const char* tile = reinterpret_cast<const char*>(buf);
+    // tile t has landed once at most the loads of tile t+1 are outstanding
+    if (t + 1 < ntiles)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(CPT));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    // all waves: tile t visible, tile t-1 no longer read.  A bare barrier:
+    // __syncthreads() would add a fence that waits for the loads in flight.
+    __builtin_amdgcn_s_barrier();
+#ifndef TPLA_EXP_NOLOAD
+    if (t + 2 < ntiles) issue(t + 2);
+#endif
+    const unsigned tile = lds_base + (unsigned)((t % NSTAGE) * TILE_BYTES);
+    const int valid = t_end - (t_begin + t * TOK);
+    if (valid < TOK) {
+      // last, partial tile: clear the rows past the end of the sequence so
+      // that whatever the pool holds there can never reach the accumulators
+      u32x4* tl = smem + (t % NSTAGE) * TC;
+      for (int x = tid; x < TC; x += NW * 64)
+        if (x / RC >= valid) tl[x] = u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+    }
 
-    // ---- scores ------------------------------------------------------------
+#ifndef TPLA_EXP_NOCOMPUTE
+    // ---- scores: a ring of 4 K fragments ahead of the MFMAs -------------------
     f32x4 sacc[TB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) sacc[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-      for (int tb = 0; tb < TB; ++tb) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(
-            tile + k_off[ks & 1] + (ks >> 1) * 128 + tb * (16 * RC * 16));
-        sacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qreg[ks], sacc[tb], 0, 0, 0);
-      }
+    {
+      constexpr int NQ = KS * TB;          // MFMAs, in order (ks, tb)
+      bf16x8 kf[4];
+      const unsigned ka[2] = {tile + k_off[0], tile + k_off[1]};
+      static_for<4>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int ks = i / TB, tb = i % TB;
+        lds_read_b128<(ks >> 1) * 128 + tb * (16 * RC * 16)>(kf[i], ka[ks & 1]);
+      });
+      static_for<NQ>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int ks = i / TB, tb = i % TB;
+        constexpr int ahead = (NQ - 1 - i) < 3 ? (NQ - 1 - i) : 3;
+        lds_wait<ahead>(kf[i & 3]);
+        sacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i & 3], qreg[ks], sacc[tb], 0, 0, 0);
+        if constexpr (i + 4 < NQ) {
+          constexpr int ks2 = (i + 4) / TB, tb2 = (i + 4) % TB;
+          lds_read_b128<(ks2 >> 1) * 128 + tb2 * (16 * RC * 16)>(kf[i & 3], ka[ks2 & 1]);
+        }
+      });
     }
 
     // ---- online softmax (lane = one head; tokens 16*tb + 4*q4 + i) ----------
     // The reference m_run of the exponentials is only moved when some score
     // exceeds it by more than LAZY (weights stay <= 2^LAZY, harmless in
     // float), so the accumulator rescale is off the common path.
-    const int valid = t_end - (t_begin + t * TOK);
     if (valid < TOK) {
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb)
@@ -192,7 +282,7 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
       }
     l_run += psum;
 
-    // ---- output: O^T += V^T P^T ----------------------------------------------
+    // ---- output: O^T += V^T P^T, a ring of 4 V fragments ---------------------
 #pragma unroll
     for (int s2 = 0; s2 < S2; ++s2) {
       bf16x8 pb;
@@ -201,17 +291,29 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
         pb[i] = (bf16_t)sacc[2 * s2][i];
         pb[4 + i] = (bf16_t)sacc[2 * s2 + 1][i];
       }
+      u32x2 vlo[4], vhi[4];
+      unsigned va[4];
 #pragma unroll
-      for (int d = 0; d < DB; ++d) {
-        const char* pa = tile + v_off[d & 3] + (d >> 2) * 128 + s2 * (32 * RC * 16);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TPLA_LDS(pa));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TPLA_LDS(pa + 16 * RC * 16));
-        const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        acc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v8), pb, acc[d], 0, 0, 0);
-      }
+      for (int d = 0; d < 4; ++d) va[d] = tile + v_off[d] + (unsigned)(s2 * (32 * RC * 16));
+      static_for<4>([&](auto ic) {
+        constexpr int d = decltype(ic)::value;
+        lds_read_tr_b64<(d >> 2) * 128>(vlo[d], va[d & 3]);
+        lds_read_tr_b64<(d >> 2) * 128 + 16 * RC * 16>(vhi[d], va[d & 3]);
+      });
+      static_for<DB>([&](auto ic) {
+        constexpr int d = decltype(ic)::value;
+        constexpr int ahead = (DB - 1 - d) < 3 ? (DB - 1 - d) : 3;
+        lds_wait<2 * ahead>(vlo[d & 3], vhi[d & 3]);
+        const u32x4 v4 = {vlo[d & 3][0], vlo[d & 3][1], vhi[d & 3][0], vhi[d & 3][1]};
+        acc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v4), pb, acc[d], 0, 0, 0);
+        if constexpr (d + 4 < DB) {
+          constexpr int d2 = d + 4;
+          lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d & 3], va[d2 & 3]);
+          lds_read_tr_b64<(d2 >> 2) * 128 + 16 * RC * 16>(vhi[d & 3], va[d2 & 3]);
+        }
+      });
     }
-    // the next iteration writes the other buffer; the barrier at its top
-    // orders these reads before the write after that one
+  #endif
   }
 
   float l_tot = l_run + __shfl_xor(l_run, 16);
@@ -245,11 +347,11 @@ struct KernelInfo {
 
 template <int DL, int NW>
 static int kernel_info(KernelInfo** out) {
-  constexpr int TOK = 32;
+  constexpr int TOK = 32, NSTAGE = 3;
   static KernelInfo info;
   if (!info.ready) {
-    info.fn = decode_mfma_kernel<DL, 64, NW, TOK>;
-    info.smem = 2u * TOK * ((DL + 64) / 8) * 16;
+    info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE>;
+    info.smem = (size_t)NSTAGE * TOK * ((DL + 64) / 8) * 16;
     info.threads = NW * 64;
     // dynamic LDS above the 64 KiB default needs opting in
     if (info.smem > 64 * 1024 &&
