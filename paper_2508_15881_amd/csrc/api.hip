@@ -99,6 +99,7 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages, int32_t n_split
     if (n < 1) n = 1;
   }
   if (n > max_pages) n = max_pages;
+  if (n > 1024 && n_splits_req <= 0) n = 1024;   // the merge handles at most 1024 chunks per sequence
   if (n < 1) n = 1;
   p.pages_per_split = (max_pages + n - 1) / n;
   p.n_splits = (max_pages + p.pages_per_split - 1) / p.pages_per_split;
@@ -235,6 +236,8 @@ int tpla_decode_shard(const tpla_shape_t* shape, const void* q_lat_i, const void
   const size_t need = workspace_for(*shape, plan);
   if (workspace_bytes < need)
     return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  if (plan.n_splits > 1024)
+    return fail(TPLA_ERR_UNSUPPORTED, "n_splits=%d above 1024", plan.n_splits);
   if ((int64_t)shape->B * plan.n_splits > (int64_t)2147483647 / 4)
     return fail(TPLA_ERR_UNSUPPORTED, "B * n_splits too large");
 

@@ -103,8 +103,12 @@ __global__ void __launch_bounds__(GEN_THREADS) decode_generic_kernel(DecodeArgs 
 }
 
 // One workgroup = one (sequence, head): combines the non-empty splits in
-// ascending split order (fixed order => reproducible bits).
+// ascending split order (fixed order => reproducible bits).  Wave 0 turns the
+// (reference, weight-sum) pairs into one normalised factor per split; then
+// every thread sums its columns over the splits.
+constexpr int MERGE_MAX_SPLITS = 1024;
 __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
+  __shared__ float wgt[MERGE_MAX_SPLITS];
   const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
   const int L = a.seq_lens[b];
   const int n_pages = (L + a.page_tokens - 1) / a.page_tokens;
@@ -118,24 +122,43 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
     return;
   }
   const size_t item0 = ((size_t)b * a.n_splits) * a.H + h;
-  float M = -INFINITY;
-  for (int s = 0; s < cnt; ++s) M = fmaxf(M, a.part_ml[(item0 + (size_t)s * a.H) * 2]);
-  float lsum = 0.f;
-  for (int s = 0; s < cnt; ++s) {
-    const float* ml = a.part_ml + (item0 + (size_t)s * a.H) * 2;
-    lsum += ml[1] * exp2f(ml[0] - M);
-  }
-  const float inv = 1.0f / lsum;
-  for (int c = threadIdx.x; c < dl; c += blockDim.x) {
-    float v = 0.f;
-    for (int s = 0; s < cnt; ++s) {
-      const size_t item = item0 + (size_t)s * a.H;
-      v = fmaf(a.part_acc[item * dl + c], exp2f(a.part_ml[item * 2] - M), v);
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    float M = -INFINITY;
+    for (int s = lane; s < cnt; s += 64) M = fmaxf(M, a.part_ml[(item0 + (size_t)s * a.H) * 2]);
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) M = fmaxf(M, __shfl_xor(M, m));
+    float lsum = 0.f;
+    for (int s = lane; s < cnt; s += 64) {
+      const float* ml = a.part_ml + (item0 + (size_t)s * a.H) * 2;
+      const float e = exp2f(ml[0] - M);
+      wgt[s] = e;
+      lsum = fmaf(ml[1], e, lsum);
     }
-    out[c] = v * inv;
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) lsum += __shfl_xor(lsum, m);
+    const float inv = 1.0f / lsum;
+    for (int s = lane; s < cnt; s += 64) wgt[s] *= inv;
+    if (a.lse && lane == 0) a.lse[(size_t)b * a.H + h] = (M + log2f(lsum)) * 0.6931471805599453f;
   }
-  if (a.lse && threadIdx.x == 0)
-    a.lse[(size_t)b * a.H + h] = (M + log2f(lsum)) * 0.6931471805599453f;
+  __syncthreads();
+  if ((dl & 3) == 0) {
+    for (int c = threadIdx.x * 4; c < dl; c += blockDim.x * 4) {
+      float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+      for (int s = 0; s < cnt; ++s) {
+        const float4 p = *reinterpret_cast<const float4*>(a.part_acc + (item0 + (size_t)s * a.H) * dl + c);
+        const float w = wgt[s];
+        v0 = fmaf(p.x, w, v0); v1 = fmaf(p.y, w, v1); v2 = fmaf(p.z, w, v2); v3 = fmaf(p.w, w, v3);
+      }
+      *reinterpret_cast<float4*>(out + c) = make_float4(v0, v1, v2, v3);
+    }
+  } else {
+    for (int c = threadIdx.x; c < dl; c += blockDim.x) {
+      float v = 0.f;
+      for (int s = 0; s < cnt; ++s) v = fmaf(a.part_acc[(item0 + (size_t)s * a.H) * dl + c], wgt[s], v);
+      out[c] = v;
+    }
+  }
 }
 
 int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st) {
@@ -153,7 +176,8 @@ int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st) {
 }
 
 int launch_decode_merge(const DecodeArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(a.B * a.H)), dim3(128), 0, st, a);
+  const int threads = a.dl >= 512 ? 128 : 64;
+  hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(a.B * a.H)), dim3(threads), 0, st, a);
   return check_launch("decode_merge_kernel");
 }
 

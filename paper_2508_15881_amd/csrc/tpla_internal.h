@@ -83,4 +83,75 @@ __device__ __forceinline__ float load_as_f32(const bf16_t* p) { return (float)*p
 __device__ __forceinline__ void store_from_f32(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_from_f32(bf16_t* p, float v) { *p = (bf16_t)v; }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// 8 consecutive elements of a row, as floats.
+struct Vec8 {
+  float v[8];
+};
+__device__ __forceinline__ Vec8 load8(const bf16_t* p) {
+  const u32x4 raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  Vec8 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r.v[2 * i] = __uint_as_float(raw[i] << 16);
+    r.v[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+  }
+  return r;
+}
+__device__ __forceinline__ Vec8 load8(const float* p) {
+  const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  const u32x4 b = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p) + 1);
+  Vec8 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r.v[i] = __uint_as_float(a[i]);
+    r.v[4 + i] = __uint_as_float(b[i]);
+  }
+  return r;
+}
+__device__ __forceinline__ unsigned short f32_to_bf16_bits(float f) {
+  return __builtin_bit_cast(unsigned short, (bf16_t)f);
+}
+__device__ __forceinline__ void store8(bf16_t* p, const Vec8& r) {
+  u32x4 raw;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    raw[i] = (unsigned)f32_to_bf16_bits(r.v[2 * i]) | ((unsigned)f32_to_bf16_bits(r.v[2 * i + 1]) << 16);
+  __builtin_nontemporal_store(raw, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ void store8(float* p, const Vec8& r) {
+  u32x4 a, b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = __float_as_uint(r.v[i]);
+    b[i] = __float_as_uint(r.v[4 + i]);
+  }
+  __builtin_nontemporal_store(a, reinterpret_cast<u32x4*>(p));
+  __builtin_nontemporal_store(b, reinterpret_cast<u32x4*>(p) + 1);
+}
+
+// Plain (cached) variant of load8 for operands that are re-read.
+__device__ __forceinline__ Vec8 load8_cached(const bf16_t* p) {
+  const u32x4 raw = *reinterpret_cast<const u32x4*>(p);
+  Vec8 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r.v[2 * i] = __uint_as_float(raw[i] << 16);
+    r.v[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+  }
+  return r;
+}
+__device__ __forceinline__ Vec8 load8_cached(const float* p) {
+  const u32x4 a = *reinterpret_cast<const u32x4*>(p);
+  const u32x4 b = *(reinterpret_cast<const u32x4*>(p) + 1);
+  Vec8 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r.v[i] = __uint_as_float(a[i]);
+    r.v[4 + i] = __uint_as_float(b[i]);
+  }
+  return r;
+}
+
 }  // namespace tpla
