@@ -64,12 +64,16 @@ __device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
   asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
-// 16-byte pieces of a tile are stored at a swizzled position so that both
-// the row-wise reads (16 tokens x 16 B at one column) and the transposing
-// reads (16 tokens x 32 B at one column) spread over all LDS banks: piece c
-// of token `tok` lives at piece index tok * RC + (c ^ ((tok >> 1) & 7)).
+// 16-byte pieces of a tile are stored at a swizzled position: piece c of
+// token `tok` lives at piece index tok * RC + (c ^ swz(tok)).  RC is 8 mod 16,
+// so rows alternate between the two halves of the 64 LDS banks and swz, a
+// bijection of (tok >> 1) & 7, supplies the other three bits: the row-wise
+// reads (16 lanes = 16 tokens x 16 B at one column) and the transposing reads
+// (16 tokens x 32 B at one column) then run at the LDS issue rate of one wave
+// instruction per 4 cycles (measured; other XOR maps were no faster).
 // The direct-to-LDS load writes lane l of an instruction at base + 16 l, so
 // the swizzle is applied to the global address each lane fetches from.
+__device__ __forceinline__ int swz(int tok) { return (tok >> 1) & 7; }
 
 template <int DL, int DR, int NW, int TOK, int NSTAGE>
 __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
@@ -93,10 +97,17 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j16 = lane & 15, q4 = lane >> 4;
   const int b = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;
+  const int p0 = s * a.pages_per_split;
+  // Page ids of this chunk live in a register, 64 pages at a time (lane i
+  // holds page p0 + pg_base + i), and are read back with v_readlane: a memory
+  // load per tile would have to wait for every direct-to-LDS load before it.
+  // The first batch is fetched together with the sequence length (entries
+  // past the sequence's last page are inside the table row and never used).
+  int pg_reg = a.block_table[(size_t)b * a.max_pages + min(p0 + lane, a.max_pages - 1)];
   const int L = a.seq_lens[b];
   const int n_pages = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
-  const int p0 = s * a.pages_per_split;
   if (p0 >= n_pages) return;
+  asm volatile("" : "+v"(pg_reg));
   int p1 = p0 + a.pages_per_split;
   if (p1 > n_pages) p1 = n_pages;
   const int t_begin = p0 * PAGE_TOKENS;
@@ -120,14 +131,9 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
     const int tok = x / RC, cs = x % RC;         // swizzled position -> source piece
     ld_k[j] = k;
     ld_tok[j] = tok;
-    ld_goff[j] = (unsigned)((tok * RC + (cs ^ ((tok >> 1) & 7))) * 16);
+    ld_goff[j] = (unsigned)((tok * RC + (cs ^ swz(tok))) * 16);
   }
-  // Page ids of this chunk live in a register, 64 pages at a time (lane i
-  // holds page p0 + pg_base + i), and are read back with v_readlane: a memory
-  // load per tile would have to wait for every direct-to-LDS load before it.
   int pg_base = 0;
-  int pg_reg = bt[min(p0 + lane, p1 - 1)];
-  asm volatile("" : "+v"(pg_reg));
   auto issue = [&](int t) {
     const int T = p0 * TPP + t;
     const int pg = t / TPP;                 // page of this chunk, uniform
@@ -153,13 +159,13 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
 
   // ---- per-lane LDS byte offsets -------------------------------------------
   // score product: token 16*tb + j16, piece 4*ks + q4
-  const int xk = (j16 >> 1) & 7;
+  const int xk = swz(j16);
   unsigned k_off[2];
   k_off[0] = (unsigned)((j16 * RC + ((q4) ^ xk)) * 16);
   k_off[1] = (unsigned)((j16 * RC + ((4 | q4) ^ xk)) * 16);
   // output product: token 4*q4 + (j16>>2) (+16), dims 16*db + 4*(j16&3) .. +4
   const int v_tok = 4 * q4 + (j16 >> 2);
-  const int xv = (v_tok >> 1) & 7;
+  const int xv = swz(v_tok);
   const int cb = (j16 & 3) >> 1;
   unsigned v_off[4];
 #pragma unroll
