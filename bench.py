@@ -25,7 +25,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM traffic of one split-kernel launch measured with rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), bytes per
 # launch; see profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/decode_split_kernel_dsv3_32k_hbm_traffic.txt: 681.8 MB read + 33.8 MB written
+    "dsv3_32k": 715.6e6,
+}
 
 
 def cpu_baseline(w, model, budget_s=12.0):
@@ -69,8 +72,8 @@ def cpu_baseline(w, model, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="dsv3_32k")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -188,6 +191,8 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),
                      "launch_us": kern_avg_ms * 1e3, "launches": len(kern_ms),
+                     "launch_us_min": float(np.min(kern_ms)) * 1e3, "launch_us_median": float(np.median(kern_ms)) * 1e3,
+                     "launch_us_first10": float(np.mean(kern_ms[:10])) * 1e3, "launch_us_last10": float(np.mean(kern_ms[-10:])) * 1e3,
                      "algorithmic_bytes_per_launch": shard_bytes},
         "paper_context": "paper reports only ratios: TPLA vs MLA decode 1.79x (DeepSeek-V3) / 1.93x (Kimi-K2) at 32K, "
                          "2 GPUs of an unnamed model, BF16, FlashAttention-3, MoE removed (Sec. 5.4.1)",
