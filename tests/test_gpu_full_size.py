@@ -1,0 +1,94 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times (automatic split plan), on sampled outputs: the
+oracle recomputes whole sequences picked from the batch, every head of them."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2508_15881_amd as tp
+from paper_2508_15881_amd import pipeline as pl
+from paper_2508_15881_amd import workloads as wl
+from oracle import tpla_oracle as orc
+from gpu_common import TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_config(name, sample):
+    w = wl.CONFIGS[name]
+    print(f"full-size {name}: B={w.B} tokens~{w.B * (w.context or 26800)} sample={sample}", flush=True)
+    dev = "cuda"
+    shape = pl.make_shape(w)
+    m = wl.draw_model_side(w)
+    lens = m["seq_lens"]
+    pt = w.page_tokens
+    P = m["n_pool_pages"]
+    pages = (lens.astype(np.int64) + pt - 1) // pt
+    assert m["block_table"].max() < P and int(lens.max()) <= m["max_pages"] * pt
+    tdt = pl.torch_dtype(w.dtype)
+    mla_pool = torch.full((P, pt, w.d_c + w.d_r), float("nan"), dtype=tdt, device=dev)
+    eps = 1e-6 if w.rms_prefill else -1.0
+    kept = {}
+    for b in range(w.B):
+        L = int(lens[b])
+        c, k = wl.draw_sequence(w, b, L, heavy=m["heavy"])
+        slots = torch.from_numpy(wl.slot_mapping(m["block_table"][b, :pages[b]], L, pt)).to(dev)
+        tp.tpla_write_mla_cache(shape, pl.to_device(c, w.dtype), pl.to_device(k, w.dtype), slots, L, eps, mla_pool)
+        if b in sample:
+            kept[b] = (c, k)
+    torch.cuda.synchronize()
+    print("  cache written", flush=True)
+    hadamard = w.transform == "hadamard"
+    code = tp.TPLA_U_HADAMARD if hadamard else tp.TPLA_U_IDENTITY
+    signs = torch.from_numpy(m["signs"]).to(dev) if hadamard else None
+    W_UK_t, W_UV_t = pl.transform_weights(shape, code, signs, None, pl.to_device(m["W_UK"], w.dtype),
+                                          pl.to_device(m["W_UV"], w.dtype))
+    pools = [torch.full((P, pt, w.dl + w.d_r), float("nan"), dtype=tdt, device=dev) for _ in range(w.g)]
+    used_np = np.unique(np.concatenate([m["block_table"][b, :pages[b]] for b in range(w.B)])).astype(np.int32)
+    tp.tpla_transform_latent_paged(shape, code, signs, None, mla_pool, pools, torch.from_numpy(used_np).to(dev), len(used_np))
+    del mla_pool
+    step = pl.DecodeStep(shape, m["max_pages"], 0)
+    mu = [float(w.g)] * w.g
+    o = step.run(pl.to_device(m["q_nope"], w.dtype), pl.to_device(m["q_pe"], w.dtype), W_UK_t, W_UV_t, pools,
+                 torch.from_numpy(m["block_table"]).to(dev), torch.from_numpy(lens).to(dev), mu)
+    torch.cuda.synchronize()
+    print("  step done", flush=True)
+    o = o.cpu().numpy(); o_lat = step.o_lat.cpu().numpy(); lse = step.lse.cpu().numpy()
+    assert np.all(np.isfinite(o)) and np.all(np.isfinite(o_lat)) and np.all(np.isfinite(lse))
+    U64 = orc.hadamard_U(w.d_c, m["signs"]) if hadamard else None
+    q_nope, q_pe = wl.as_f64(m["q_nope"], w.dtype), wl.as_f64(m["q_pe"], w.dtype)
+    W_UK, W_UV = wl.as_f64(m["W_UK"], w.dtype), wl.as_f64(m["W_UV"], w.dtype)
+    for b in sample:
+        c, k = kept[b]
+        c64 = wl.as_f64(c, w.dtype)
+        if w.rms_prefill:
+            c64 = orc.round_to_bf16(orc.rms_norm_unit(c64, eps))   # the cache stores bf16
+        ref = orc.tpla_decode(q_nope[b:b + 1], q_pe[b:b + 1], W_UK, W_UV, [c64], [wl.as_f64(k, w.dtype)],
+                              w.g, w.sm_scale, U=U64, mu=mu)
+        assert rel_err(o_lat[:, b:b + 1], ref["O_lat"]) <= TOL[w.dtype], (name, b)
+        assert rel_err(o[b:b + 1], ref["o"]) <= TOL[w.dtype], (name, b)
+        assert np.max(np.abs(lse[:, b:b + 1] - ref["lse"])) <= 2e-2, (name, b)
+        print(f"  sequence {b} (L={int(lens[b])}) ok", flush=True)
+
+
+@pytest.mark.timeout(300)
+def test_full_size_dsv3_4k():
+    _run_config("dsv3_4k", [0, 9, 15])
+
+
+@pytest.mark.timeout(300)
+def test_full_size_dsv3_32k():
+    _run_config("dsv3_32k", [0, 17, 31])
+
+
+@pytest.mark.timeout(400)
+def test_full_size_kimi_32k():
+    _run_config("kimi_32k", [3, 63])
+
+
+@pytest.mark.timeout(600)
+def test_full_size_ragged_g4():
+    w = wl.CONFIGS["ragged_g4"]
+    lens = wl.draw_model_side(w)["seq_lens"]
+    order = np.argsort(lens)
+    _run_config("ragged_g4", [int(order[0]), int(order[len(order) // 2])])
