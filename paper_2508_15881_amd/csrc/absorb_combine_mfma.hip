@@ -1,0 +1,223 @@
+// Matrix-core versions of the two per-head contractions around the decode
+// (bf16 weights): absorb  q_lat = mu * (q_nope @ W_UK')   (Sec. 3.3 / 4 / 4.2)
+//                 combine o = sum_i o_lat_i @ W_UV'[slice i]   (Sec. 4)
+// Both are X[b, k] @ W[k, j] per head with W row-major (j contiguous), while
+// the MFMA B operand wants 8 consecutive k per lane: the weight slab goes
+// through LDS and comes back through the transposing read, which hands lane j
+// the 4 rows of column j.  The float o_lat is split into bf16 hi + lo parts
+// (two MFMAs) so the combine keeps float accuracy.
+#include "tpla_internal.h"
+
+namespace tpla {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+#define TPLA_LDS4(p) ((__attribute__((address_space(3))) s16x4*)(p))
+
+// LDS slab [rows][16 * PPR bytes] of 16-byte pieces; piece p of row r sits at
+// p ^ wswz(r).  A transposing read touches rows {0..3, 8..11, 16..19, 24..27}
+// (+4) of a 32-row step at one 32-byte column: wswz spreads those 16 rows
+// over the 8 bank groups, two rows each.
+__device__ __forceinline__ int wswz(int r) { return ((r & 3) | (((r >> 3) & 1) << 2)) << 1; }
+
+// Same for 8-piece (128-byte) rows, where the row parity already selects the
+// bank half: the remaining two bits come from row bits 1 and 3.
+__device__ __forceinline__ int wswz8(int r) { return (((r >> 1) & 1) | (((r >> 3) & 1) << 1)) << 1; }
+
+// B fragment (32 k-rows x 16 columns) of MFMA 16x16x32 from the slab.
+// rows k0..k0+31, 16-byte piece pair (2*cb, 2*cb+1) of a PPR-piece row.
+template <int PPR>
+__device__ __forceinline__ bf16x8 read_b_frag(const char* slab, int k0, int cb, int j16, int q4) {
+  const int r0 = k0 + 8 * q4 + (j16 >> 2);
+  const int p = 2 * cb + ((j16 & 3) >> 1);
+  const int byte = (j16 & 1) * 8;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      TPLA_LDS4(slab + (r0 * PPR + (p ^ wswz(r0))) * 16 + byte));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      TPLA_LDS4(slab + ((r0 + 4) * PPR + (p ^ wswz(r0 + 4))) * 16 + byte));
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// ---------------------------------------------------------------------------
+// absorb: grid (H, d_c / 128); 4 waves, wave w owns columns 32w..32w+31 of the
+// slab; LDS slab = W_UK'[h][0..d_n)[c0..c0+128).
+constexpr int AQ_COLS = 128;
+__global__ void __launch_bounds__(256) absorb_query_mfma_kernel(const bf16_t* __restrict__ q_nope,
+                                                                const bf16_t* __restrict__ W, MuFactors mu,
+                                                                bf16_t* __restrict__ q_lat, int B, int H,
+                                                                int d_n, int d_c, int g) {
+  extern __shared__ u32x4 slab4[];
+  char* slab = reinterpret_cast<char*>(slab4);
+  constexpr int PPR = AQ_COLS / 8;   // 16 pieces per row
+  const int h = blockIdx.x, c0 = blockIdx.y * AQ_COLS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j16 = lane & 15, q4 = lane >> 4;
+  const bf16_t* Wh = W + (size_t)h * d_n * d_c + c0;
+  for (int x = tid; x < d_n * PPR; x += 256) {
+    const int r = x / PPR, p = x % PPR;
+    slab4[r * PPR + (p ^ wswz(r))] = *reinterpret_cast<const u32x4*>(Wh + (size_t)r * d_c + 8 * p);
+  }
+  __syncthreads();
+  const int dl = d_c / g;
+  const int KS = d_n / 32;
+  for (int mb = 0; mb < (B + 15) / 16; ++mb) {
+    const int b = 16 * mb + j16;
+    const bf16_t* qrow = q_nope + ((size_t)min(b, B - 1) * H + h) * d_n + 8 * q4;
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(qrow + 32 * ks);
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const bf16x8 bf = read_b_frag<PPR>(slab, 32 * ks, 2 * wave + cb, j16, q4);
+        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bf, acc[cb], 0, 0, 0);
+      }
+    }
+    // acc[cb][i]: sequence 16 mb + 4 q4 + i, column c0 + 32 wave + 16 cb + j16
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      const int col = c0 + 32 * wave + 16 * cb + j16;
+      const int sl = col / dl, c = col - sl * dl;
+      const float m = mu.v[sl];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int bb = 16 * mb + 4 * q4 + i;
+        if (bb < B) q_lat[(((size_t)sl * B + bb) * H + h) * dl + c] = (bf16_t)(acc[cb][i] * m);
+      }
+    }
+  }
+}
+
+bool absorb_mfma_supported(const tpla_shape_t& sh) {
+  return sh.dtype == TPLA_BF16 && sh.d_n % 32 == 0 && sh.d_n <= 256 && sh.d_c % AQ_COLS == 0 &&
+         (sh.d_c / sh.g) % 16 == 0 && sh.d_c / AQ_COLS <= 65535;
+}
+
+int launch_absorb_query_mfma(const tpla_shape_t& sh, const void* q_nope, const void* W_UK_t,
+                             const MuFactors& mu, void* q_lat, hipStream_t st) {
+  const size_t smem = (size_t)sh.d_n * AQ_COLS * 2;
+  hipLaunchKernelGGL(absorb_query_mfma_kernel, dim3((unsigned)sh.H, (unsigned)(sh.d_c / AQ_COLS)), dim3(256),
+                     smem, st, static_cast<const bf16_t*>(q_nope), static_cast<const bf16_t*>(W_UK_t), mu,
+                     static_cast<bf16_t*>(q_lat), sh.B, sh.H, sh.d_n, sh.d_c, sh.g);
+  return check_launch("absorb_query_mfma_kernel");
+}
+
+// ---------------------------------------------------------------------------
+// combine: grid (H, d_v / 64).  The latent axis is walked in chunks of CK_ROWS
+// rows staged in LDS; inside a chunk wave w owns rows 128w..128w+127 (so every
+// o_lat element is fetched and split into hi/lo by exactly one wave) and all
+// 64 columns; the four waves' partial sums meet in LDS at the end.
+constexpr int CB_COLS = 64;
+constexpr int CK_ROWS = 512;
+__global__ void __launch_bounds__(256) combine_shards_mfma_kernel(const float* __restrict__ o_lat,
+                                                                  const bf16_t* __restrict__ W,
+                                                                  float* __restrict__ o, int B, int H,
+                                                                  int d_c, int d_v, int g) {
+  extern __shared__ u32x4 slab4[];
+  char* slab = reinterpret_cast<char*>(slab4);
+  constexpr int PPR = CB_COLS / 8;   // 8 pieces per row
+  constexpr int WK = CK_ROWS / 4;    // rows per wave and chunk
+  const int h = blockIdx.x, c0 = blockIdx.y * CB_COLS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j16 = lane & 15, q4 = lane >> 4;
+  const int dl = d_c / g;
+  const int n_mb = (B + 15) / 16;
+  for (int mb0 = 0; mb0 < n_mb; mb0 += 2) {
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) acc[m][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kc = 0; kc < d_c; kc += CK_ROWS) {
+      // this lane's o_lat pieces of the chunk: issued before the weights are staged
+      float4 xa[WK / 32][2][2];
+#pragma unroll
+      for (int ks = 0; ks < WK / 32; ++ks) {
+        const int k = kc + WK * wave + 32 * ks + 8 * q4;
+        const int sl = k / dl, c = k - sl * dl;
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+          const int b = min(16 * (mb0 + m) + j16, B - 1);
+          const float* src = o_lat + (((size_t)sl * B + b) * H + h) * dl + c;
+          xa[ks][m][0] = *reinterpret_cast<const float4*>(src);
+          xa[ks][m][1] = *reinterpret_cast<const float4*>(src + 4);
+        }
+      }
+      __syncthreads();
+      const bf16_t* Wh = W + ((size_t)h * d_c + kc) * d_v + c0;
+      for (int x = tid; x < CK_ROWS * PPR; x += 256) {
+        const int r = x / PPR, p = x % PPR;
+        slab4[r * PPR + (p ^ wswz8(r))] = *reinterpret_cast<const u32x4*>(Wh + (size_t)r * d_v + 8 * p);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int ks = 0; ks < WK / 32; ++ks) {
+        bf16x8 ah[2], al[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+          const float xs[8] = {xa[ks][m][0].x, xa[ks][m][0].y, xa[ks][m][0].z, xa[ks][m][0].w,
+                               xa[ks][m][1].x, xa[ks][m][1].y, xa[ks][m][1].z, xa[ks][m][1].w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const bf16_t hi16 = (bf16_t)xs[e];
+            ah[m][e] = hi16;
+            al[m][e] = (bf16_t)(xs[e] - (float)hi16);
+          }
+        }
+        const int r0 = WK * wave + 32 * ks + 8 * q4 + (j16 >> 2);
+        const int byte = (j16 & 1) * 8;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) {
+          const int p = 2 * cb + ((j16 & 3) >> 1);
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              TPLA_LDS4(slab + (r0 * PPR + (p ^ wswz8(r0))) * 16 + byte));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              TPLA_LDS4(slab + ((r0 + 4) * PPR + (p ^ wswz8(r0 + 4))) * 16 + byte));
+          const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 bf = __builtin_bit_cast(bf16x8, v8);
+#pragma unroll
+          for (int m = 0; m < 2; ++m) {
+            acc[m][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[m], bf, acc[m][cb], 0, 0, 0);
+            acc[m][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[m], bf, acc[m][cb], 0, 0, 0);
+          }
+        }
+      }
+    }
+    // sum the four waves' partial tiles through LDS; wave w finishes column block w
+    __syncthreads();
+    f32x4* red = reinterpret_cast<f32x4*>(slab);     // [wave][m][cb][lane]
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) red[((wave * 2 + m) * 4 + cb) * 64 + lane] = acc[m][cb];
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+      f32x4 t = red[((0 * 2 + m) * 4 + wave) * 64 + lane];
+#pragma unroll
+      for (int w2 = 1; w2 < 4; ++w2) t += red[((w2 * 2 + m) * 4 + wave) * 64 + lane];
+      // t[i]: sequence 16 (mb0 + m) + 4 q4 + i, column c0 + 16 wave + j16
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int bb = 16 * (mb0 + m) + 4 * q4 + i;
+        if (bb < B) o[((size_t)bb * H + h) * d_v + c0 + 16 * wave + j16] = t[i];
+      }
+    }
+  }
+}
+
+bool combine_mfma_supported(const tpla_shape_t& sh) {
+  return sh.dtype == TPLA_BF16 && sh.d_v % CB_COLS == 0 && sh.d_c % CK_ROWS == 0 && (sh.d_c / sh.g) % 32 == 0 &&
+         sh.d_v / CB_COLS <= 65535;
+}
+
+int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
+                               hipStream_t st) {
+  const size_t smem = (size_t)CK_ROWS * CB_COLS * 2;
+  hipLaunchKernelGGL(combine_shards_mfma_kernel, dim3((unsigned)sh.H, (unsigned)(sh.d_v / CB_COLS)), dim3(256),
+                     smem, st, o_lat, static_cast<const bf16_t*>(W_UV_t), o, sh.B, sh.H, sh.d_c, sh.d_v, sh.g);
+  return check_launch("combine_shards_mfma_kernel");
+}
+
+}  // namespace tpla

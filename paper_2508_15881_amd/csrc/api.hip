@@ -84,9 +84,12 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages, int32_t n_split
   if (n <= 0) {
     // One resident workgroup per slot and no second round: with B * n at most
     // the number of workgroups the chip holds at once, every chunk runs
-    // concurrently and chunks are equal (this assumes sequences of similar
-    // length; pass n_splits for a ragged batch).  A chunk keeps at least 4
-    // pages so the partial results stay a small fraction of the bytes read.
+    // concurrently and chunks are equal.  That only balances when sequences
+    // have similar lengths, so it is used while a chunk stays within 64
+    // pages; beyond that (long tables: long or ragged batches) chunks are 32
+    // pages and the hardware dispatcher balances the many small workgroups.
+    // A chunk keeps at least 4 pages so the partial results stay a small
+    // fraction of the bytes read.
     int per_cu = 4;
     if (sh.dtype == TPLA_BF16 && decode_mfma_supported(sh)) {
       per_cu = decode_mfma_blocks_per_cu(sh);
@@ -94,6 +97,8 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages, int32_t n_split
     }
     const int slots = device_cu_count() * per_cu;
     n = slots / sh.B;
+    if (n < 1) n = 1;
+    if ((max_pages + n - 1) / n > 64) n = (max_pages + 31) / 32;
     const int32_t cap = (max_pages + 3) / 4;
     if (n > cap) n = cap;
     if (n < 1) n = 1;
@@ -204,6 +209,8 @@ int tpla_absorb_query(const tpla_shape_t* shape, const void* q_nope, const void*
       if (!isfinite(mu[i])) return fail(TPLA_ERR_SHAPE, "mu[%d] is not finite", i);
       m.v[i] = mu[i];
     }
+  if (absorb_mfma_supported(*shape))
+    return launch_absorb_query_mfma(*shape, q_nope, W_UK_t, m, q_lat, (hipStream_t)stream);
   return launch_absorb_query(*shape, q_nope, W_UK_t, m, q_lat, (hipStream_t)stream);
 }
 
@@ -280,6 +287,8 @@ int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const voi
   if (!o_lat || !W_UV_t || !o) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
   if (!aligned16(o_lat) || !aligned16(W_UV_t) || !aligned16(o))
     return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  if (combine_mfma_supported(*shape))
+    return launch_combine_shards_mfma(*shape, o_lat, W_UV_t, o, (hipStream_t)stream);
   return launch_combine_shards(*shape, o_lat, W_UV_t, o, (hipStream_t)stream);
 }
 

@@ -75,6 +75,13 @@ int launch_absorb_query(const tpla_shape_t& sh, const void* q_nope, const void* 
                         const MuFactors& mu, void* q_lat, hipStream_t st);
 int launch_combine_shards(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
                           hipStream_t st);
+// Matrix-core variants (bf16 weights, widths that tile): see absorb_combine_mfma.hip.
+bool absorb_mfma_supported(const tpla_shape_t& sh);
+int launch_absorb_query_mfma(const tpla_shape_t& sh, const void* q_nope, const void* W_UK_t,
+                             const MuFactors& mu, void* q_lat, hipStream_t st);
+bool combine_mfma_supported(const tpla_shape_t& sh);
+int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
+                               hipStream_t st);
 
 // ---- small device helpers -------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(bf16_t x) { return (float)x; }
