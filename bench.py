@@ -25,7 +25,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM traffic of one split-kernel launch measured with rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), bytes per
 # launch; see profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC = {
+MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC_ONE_SLICE = {
     # profiles/decode_split_kernel_dsv3_32k_hbm_traffic.txt: 681.8 MB read + 33.8 MB written
     "dsv3_32k": 715.6e6,
 }
@@ -130,7 +131,6 @@ def main():
         t_tr.append(ev0.elapsed_time(ev1))
     esz = 4 if w.dtype == "f32" else 2
     tr_bytes = len(used_np) * pt * ((w.d_c + w.d_r) + w.g * (w.dl + w.d_r)) * esz
-    del mla_pool
 
     q_nope = pl.to_device(model["q_nope"], w.dtype)
     q_pe = pl.to_device(model["q_pe"], w.dtype)
@@ -144,21 +144,34 @@ def main():
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps, split kernel bracketed by HIP events ----
-    tp.tpla_profile_enable(args.steps * w.g)
+    # (all g slices share one decode launch: one bracket per step)
+    tp.tpla_profile_enable(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step.run(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt, lens, mu)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kern_ms = tp.tpla_profile_collect(args.steps * w.g)
+    kern_ms = tp.tpla_profile_collect(args.steps)
+
+    # one device's share: the same kernel launched for one slice at a time
+    n_one = min(args.steps, 200)
+    tp.tpla_profile_enable(n_one * w.g)
+    for _ in range(n_one):
+        for i in range(w.g):
+            step.decode(i, q_pe, pools[i], bt, lens)
+    torch.cuda.synchronize()
+    one_ms = tp.tpla_profile_collect(n_one * w.g)
     tp.tpla_profile_enable(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     shard_bytes = wl.algorithmic_bytes_per_shard(w, lens_np)
     value = w.g * shard_bytes / (ms_per_step * 1e-3) / 1e9
     kern_avg_ms = float(np.mean(kern_ms))
-    achieved = shard_bytes / (kern_avg_ms * 1e-3) / 1e9
+    launch_bytes = w.g * shard_bytes
+    achieved = launch_bytes / (kern_avg_ms * 1e-3) / 1e9
+    one_avg_ms = float(np.mean(one_ms))
+    one_achieved = shard_bytes / (one_avg_ms * 1e-3) / 1e9
 
     # stage breakdown (untimed region, events on torch's current stream = the launch stream)
     def timed(fn, reps=20):
@@ -170,7 +183,26 @@ def main():
         return ev0.elapsed_time(ev1) / reps * 1e3
     us_absorb = timed(lambda: step.absorb(q_nope, W_UK_t, mu))
     us_decode = timed(lambda: step.decode(0, q_pe, pools[0], bt, lens))
+    us_decode_all = timed(lambda: step.decode_all(q_pe, pools, bt, lens))
     us_combine = timed(lambda: step.combine(W_UV_t))
+
+    # MLA under head-split tensor parallelism, one device's share: the same H heads
+    # over the unsliced 576-wide cache (the MLA pool is exactly the g = 1 layout).
+    # Its time against one TPLA slice is this box's counterpart of the paper's ratio.
+    w1 = wl.scaled(w, g=1)
+    shape1 = pl.make_shape(w1)
+    step1 = pl.DecodeStep(shape1, model["max_pages"], 0)
+    step1.absorb(q_nope, W_UK_t, None)
+    n_mla = min(args.steps, 100)
+    for _ in range(3):
+        step1.decode(0, q_pe, mla_pool, bt, lens)
+    tp.tpla_profile_enable(n_mla)
+    for _ in range(n_mla):
+        step1.decode(0, q_pe, mla_pool, bt, lens)
+    torch.cuda.synchronize()
+    mla_ms = float(np.mean(tp.tpla_profile_collect(n_mla)))
+    tp.tpla_profile_enable(0)
+    mla_bytes = wl.algorithmic_bytes_per_shard(w1, lens_np)
 
     out = {
         "metric": "latent-KV decode GB/s and % HBM roofline; µs per layer-step at 32K ctx",
@@ -180,20 +212,29 @@ def main():
         "config": {"workload": w.name, "B": w.B, "H": w.H, "d_c": w.d_c, "g": w.g, "d_r": w.d_r,
                    "context": int(lens_np.max()), "tokens": int(lens_np.sum()), "page_tokens": pt,
                    "transform": w.transform, "n_splits": args.n_splits,
-                   "step": "absorb + g x (split decode + merge) + combine, all g slices on one GPU"},
+                   "step": "absorb + decode of all g slices (one split launch + one merge) + combine, on one GPU"},
         "us_per_layer_step": ms_per_step * 1e3,
         "pct_hbm_roofline_step": 100.0 * value / HBM_PEAK_GBS,
-        "stages_us": {"absorb": us_absorb, "decode_shard(one slice, split+merge)": us_decode,
-                      "combine": us_combine,
+        "stages_us": {"absorb": us_absorb, "decode_shards(all slices, split+merge)": us_decode_all,
+                      "decode_shard(one slice, split+merge)": us_decode, "combine": us_combine,
                       "one_device_share": us_absorb / w.g + us_decode + us_combine},
         "transform": {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9},
-        "roofline": {"bound": "hbm", "kernel": "decode split kernel (tpla_decode_shard)",
+        "roofline": {"bound": "hbm", "kernel": "decode split kernel, all g slices in one launch (tpla_decode_shards)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),
                      "launch_us": kern_avg_ms * 1e3, "launches": len(kern_ms),
                      "launch_us_min": float(np.min(kern_ms)) * 1e3, "launch_us_median": float(np.median(kern_ms)) * 1e3,
                      "launch_us_first10": float(np.mean(kern_ms[:10])) * 1e3, "launch_us_last10": float(np.mean(kern_ms[-10:])) * 1e3,
-                     "algorithmic_bytes_per_launch": shard_bytes},
+                     "algorithmic_bytes_per_launch": launch_bytes},
+        "roofline_one_slice": {"bound": "hbm", "kernel": "decode split kernel, one slice per launch (tpla_decode_shard)",
+                               "achieved": one_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": one_achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_ONE_SLICE.get(w.name),
+                               "launch_us": one_avg_ms * 1e3, "launches": len(one_ms),
+                               "algorithmic_bytes_per_launch": shard_bytes},
+        "mla_tp_reference": {"what": "same kernel, g=1: H heads over the unsliced (d_c + d_r)-wide cache = one device of MLA with head-split TP",
+                             "launch_us": mla_ms * 1e3, "GB/s": mla_bytes / (mla_ms * 1e-3) / 1e9,
+                             "time_ratio_mla_over_tpla_slice": mla_ms / one_avg_ms,
+                             "bytes_ratio": mla_bytes / shard_bytes},
         "paper_context": "paper reports only ratios: TPLA vs MLA decode 1.79x (DeepSeek-V3) / 1.93x (Kimi-K2) at 32K, "
                          "2 GPUs of an unnamed model, BF16, FlashAttention-3, MoE removed (Sec. 5.4.1)",
     }

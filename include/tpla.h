@@ -162,6 +162,26 @@ int tpla_decode_shard(const tpla_shape_t* shape,
                       float* o_lat_i, float* lse_i, void* stream);
 
 /*
+ * All g slices in one launch: the same computation as g calls of
+ * tpla_decode_shard (slice i: q_lat[i], shard_pools[i] -> o_lat[i], lse[i];
+ * q_pe, block_table and seq_lens are shared, Sec. 4.2), which is how one GPU
+ * stands in for the g devices of Sec. 4 -- the chunks of all slices fill the
+ * chip together, so each can be longer and fewer partial results are
+ * written.  q_lat [g,B,H,d_c/g]; shard_pools: HOST array of g device
+ * pointers; o_lat float [g,B,H,d_c/g]; lse float [g,B,H] or NULL; workspace
+ * of tpla_workspace_bytes_all() bytes.  Results are bit-reproducible for
+ * fixed arguments; they may differ from tpla_decode_shard's in the last bits
+ * because the automatic split count differs.
+ */
+size_t tpla_workspace_bytes_all(const tpla_shape_t* shape, int32_t max_pages_per_seq, int32_t n_splits);
+int tpla_decode_shards(const tpla_shape_t* shape,
+                       const void* q_lat, const void* q_pe, const void* const* shard_pools,
+                       const int32_t* block_table, int32_t max_pages_per_seq,
+                       const int32_t* seq_lens, int32_t n_splits,
+                       void* workspace, size_t workspace_bytes,
+                       float* o_lat, float* lse, void* stream);
+
+/*
  * Value up-projection of every slice and the sum over slices that the
  * all-reduce of Sec. 4 performs (W_UV kept separate from W_O, Sec. 3.3):
  *     o[b, h, :] = sum_i o_lat[i, b, h, :] @ W_UV_t[h, i d_c/g : (i+1) d_c/g, :]

@@ -18,7 +18,8 @@ TPLA_MAX_G = 8
 EXPORTS = (
     "tpla_last_error", "tpla_version", "tpla_transform_latent", "tpla_transform_latent_paged",
     "tpla_write_mla_cache", "tpla_absorb_query", "tpla_workspace_bytes", "tpla_decode_shard",
-    "tpla_combine_shards", "tpla_profile_enable", "tpla_profile_collect",
+    "tpla_combine_shards", "tpla_profile_enable", "tpla_profile_collect", "tpla_workspace_bytes_all",
+    "tpla_decode_shards",
 )
 
 
@@ -75,6 +76,10 @@ def load_library():
     lib.tpla_workspace_bytes.argtypes = [shp, i32, i32]
     lib.tpla_decode_shard.restype = ctypes.c_int
     lib.tpla_decode_shard.argtypes = [shp, vp, vp, vp, vp, i32, vp, i32, vp, ctypes.c_size_t, vp, vp, vp]
+    lib.tpla_workspace_bytes_all.restype = ctypes.c_size_t
+    lib.tpla_workspace_bytes_all.argtypes = [shp, i32, i32]
+    lib.tpla_decode_shards.restype = ctypes.c_int
+    lib.tpla_decode_shards.argtypes = [shp, vp, vp, ctypes.POINTER(vp), vp, i32, vp, i32, vp, ctypes.c_size_t, vp, vp, vp]
     lib.tpla_combine_shards.restype = ctypes.c_int
     lib.tpla_combine_shards.argtypes = [shp, vp, vp, vp, vp]
     lib.tpla_profile_enable.restype = ctypes.c_int
@@ -162,6 +167,23 @@ def tpla_decode_shard(shape, q_lat_i, q_pe, shard_pool, block_table, max_pages_p
         ctypes.byref(shape), _ptr(q_lat_i), _ptr(q_pe), _ptr(shard_pool), _ptr(block_table),
         max_pages_per_seq, _ptr(seq_lens), n_splits, _ptr(workspace), workspace_bytes,
         _ptr(o_lat_i), _ptr(lse_i), _stream(stream)))
+
+
+def tpla_workspace_bytes_all(shape, max_pages_per_seq, n_splits):
+    return int(load_library().tpla_workspace_bytes_all(ctypes.byref(shape), max_pages_per_seq, n_splits))
+
+
+def tpla_decode_shards(shape, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
+                       n_splits, workspace, workspace_bytes, o_lat, lse, stream=None):
+    if shard_pools is None:
+        arr = None
+    else:
+        arr = (ctypes.c_void_p * max(TPLA_MAX_G, len(shard_pools)))()
+        for i, p in enumerate(shard_pools):
+            arr[i] = _ptr(p)
+    _check(load_library().tpla_decode_shards(
+        ctypes.byref(shape), _ptr(q_lat), _ptr(q_pe), arr, _ptr(block_table), max_pages_per_seq,
+        _ptr(seq_lens), n_splits, _ptr(workspace), workspace_bytes, _ptr(o_lat), _ptr(lse), _stream(stream)))
 
 
 def tpla_combine_shards(shape, o_lat, W_UV_t, o, stream=None):

@@ -78,7 +78,7 @@ static int check_shape(const tpla_shape_t* sh) {
   return TPLA_OK;
 }
 
-SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages, int32_t n_splits_req) {
+SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_pages, int32_t n_splits_req) {
   SplitPlan p;
   int32_t n = n_splits_req;
   if (n <= 0) {
@@ -96,7 +96,7 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages, int32_t n_split
       if (per_cu <= 0) per_cu = 2;
     }
     const int slots = device_cu_count() * per_cu;
-    n = slots / sh.B;
+    n = slots / (sh.B * n_shards);
     if (n < 1) n = 1;
     if ((max_pages + n - 1) / n > 64) n = (max_pages + 31) / 32;
     const int32_t cap = (max_pages + 3) / 4;
@@ -111,9 +111,72 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages, int32_t n_split
   return p;
 }
 
-static size_t workspace_for(const tpla_shape_t& sh, const SplitPlan& p) {
+static size_t workspace_for(const tpla_shape_t& sh, int n_shards, const SplitPlan& p) {
   const size_t dl = (size_t)(sh.d_c / sh.g);
-  return (size_t)sh.B * p.n_splits * sh.H * (dl + 2) * sizeof(float);
+  return (size_t)n_shards * sh.B * p.n_splits * sh.H * (dl + 2) * sizeof(float);
+}
+
+// Validation, planning and launches shared by the one-slice and the
+// all-slices entry points.
+static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_lat, const void* q_pe,
+                         const void* const* pools, const int32_t* block_table, int32_t max_pages_per_seq,
+                         const int32_t* seq_lens, int32_t n_splits, void* workspace,
+                         size_t workspace_bytes, float* o_lat, float* lse, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q_lat || !q_pe || !pools || !block_table || !seq_lens || !workspace || !o_lat)
+    return fail(TPLA_ERR_NULL, "a required pointer is NULL");
+  if (max_pages_per_seq < 1 || n_splits < 0)
+    return fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_splits=%d", max_pages_per_seq, n_splits);
+  if ((int64_t)max_pages_per_seq * shape->page_tokens > (int64_t)2147483647)
+    return fail(TPLA_ERR_SHAPE, "max_pages_per_seq * page_tokens overflows int32");
+  for (int i = 0; i < n_shards; ++i) {
+    if (!pools[i]) return fail(TPLA_ERR_NULL, "cache pool %d is NULL", i);
+    if (!aligned16(pools[i])) return fail(TPLA_ERR_ALIGN, "cache pool %d is not 16-byte aligned", i);
+  }
+  if (!aligned16(q_lat) || !aligned16(q_pe) || !aligned16(block_table) || !aligned16(seq_lens) ||
+      !aligned16(workspace) || !aligned16(o_lat) || !aligned16(lse))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  const SplitPlan plan = plan_splits(*shape, n_shards, max_pages_per_seq, n_splits);
+  const size_t need = workspace_for(*shape, n_shards, plan);
+  if (workspace_bytes < need)
+    return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  if (plan.n_splits > 1024)
+    return fail(TPLA_ERR_UNSUPPORTED, "n_splits=%d above 1024", plan.n_splits);
+  if ((int64_t)n_shards * shape->B * plan.n_splits > (int64_t)2147483647 / 4)
+    return fail(TPLA_ERR_UNSUPPORTED, "n_shards * B * n_splits too large");
+
+  DecodeArgs a;
+  const int dl = shape->d_c / shape->g;
+  a.q_lat = q_lat;
+  a.q_pe = q_pe;
+  for (int i = 0; i < TPLA_MAX_G; ++i) a.pools[i] = i < n_shards ? pools[i] : nullptr;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.part_acc = static_cast<float*>(workspace);
+  a.part_ml = a.part_acc + (size_t)n_shards * shape->B * plan.n_splits * shape->H * dl;
+  a.o_lat = o_lat;
+  a.lse = lse;
+  a.n_shards = n_shards;
+  a.B = shape->B;
+  a.H = shape->H;
+  a.dl = dl;
+  a.d_r = shape->d_r;
+  a.page_tokens = shape->page_tokens;
+  a.max_pages = max_pages_per_seq;
+  a.n_splits = plan.n_splits;
+  a.pages_per_split = plan.pages_per_split;
+  a.scale_log2 = shape->sm_scale * 1.4426950408889634f;
+
+  hipStream_t st = (hipStream_t)stream;
+  profile_mark(st, true);
+  if (shape->dtype == TPLA_BF16 && decode_mfma_supported(*shape))
+    rc = launch_decode_mfma(a, st);
+  else
+    rc = launch_decode_generic(a, shape->dtype, st);
+  profile_mark(st, false);
+  if (rc) return rc;
+  return launch_decode_merge(a, st);
 }
 
 }  // namespace tpla
@@ -220,7 +283,16 @@ size_t tpla_workspace_bytes(const tpla_shape_t* shape, int32_t max_pages_per_seq
     fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_splits=%d", max_pages_per_seq, n_splits);
     return 0;
   }
-  return workspace_for(*shape, plan_splits(*shape, max_pages_per_seq, n_splits));
+  return workspace_for(*shape, 1, plan_splits(*shape, 1, max_pages_per_seq, n_splits));
+}
+
+size_t tpla_workspace_bytes_all(const tpla_shape_t* shape, int32_t max_pages_per_seq, int32_t n_splits) {
+  if (check_shape(shape) != TPLA_OK) return 0;
+  if (max_pages_per_seq < 1 || n_splits < 0) {
+    fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_splits=%d", max_pages_per_seq, n_splits);
+    return 0;
+  }
+  return workspace_for(*shape, shape->g, plan_splits(*shape, shape->g, max_pages_per_seq, n_splits));
 }
 
 int tpla_decode_shard(const tpla_shape_t* shape, const void* q_lat_i, const void* q_pe,
@@ -228,56 +300,21 @@ int tpla_decode_shard(const tpla_shape_t* shape, const void* q_lat_i, const void
                       int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t n_splits,
                       void* workspace, size_t workspace_bytes, float* o_lat_i, float* lse_i,
                       void* stream) {
+  const void* pools[1] = {shard_pool};
+  if (shape && !shard_pool) return fail(TPLA_ERR_NULL, "a required pointer is NULL");
+  return decode_common(shape, 1, q_lat_i, q_pe, pools, block_table, max_pages_per_seq, seq_lens, n_splits,
+                       workspace, workspace_bytes, o_lat_i, lse_i, stream);
+}
+
+int tpla_decode_shards(const tpla_shape_t* shape, const void* q_lat, const void* q_pe,
+                       const void* const* shard_pools, const int32_t* block_table,
+                       int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t n_splits,
+                       void* workspace, size_t workspace_bytes, float* o_lat, float* lse,
+                       void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
-  if (!q_lat_i || !q_pe || !shard_pool || !block_table || !seq_lens || !workspace || !o_lat_i)
-    return fail(TPLA_ERR_NULL, "a required pointer is NULL");
-  if (max_pages_per_seq < 1 || n_splits < 0)
-    return fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_splits=%d", max_pages_per_seq, n_splits);
-  if ((int64_t)max_pages_per_seq * shape->page_tokens > (int64_t)2147483647)
-    return fail(TPLA_ERR_SHAPE, "max_pages_per_seq * page_tokens overflows int32");
-  if (!aligned16(q_lat_i) || !aligned16(q_pe) || !aligned16(shard_pool) || !aligned16(block_table) ||
-      !aligned16(seq_lens) || !aligned16(workspace) || !aligned16(o_lat_i) || !aligned16(lse_i))
-    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
-  const SplitPlan plan = plan_splits(*shape, max_pages_per_seq, n_splits);
-  const size_t need = workspace_for(*shape, plan);
-  if (workspace_bytes < need)
-    return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
-  if (plan.n_splits > 1024)
-    return fail(TPLA_ERR_UNSUPPORTED, "n_splits=%d above 1024", plan.n_splits);
-  if ((int64_t)shape->B * plan.n_splits > (int64_t)2147483647 / 4)
-    return fail(TPLA_ERR_UNSUPPORTED, "B * n_splits too large");
-
-  DecodeArgs a;
-  const int dl = shape->d_c / shape->g;
-  a.q_lat = q_lat_i;
-  a.q_pe = q_pe;
-  a.pool = shard_pool;
-  a.block_table = block_table;
-  a.seq_lens = seq_lens;
-  a.part_acc = static_cast<float*>(workspace);
-  a.part_ml = a.part_acc + (size_t)shape->B * plan.n_splits * shape->H * dl;
-  a.o_lat = o_lat_i;
-  a.lse = lse_i;
-  a.B = shape->B;
-  a.H = shape->H;
-  a.dl = dl;
-  a.d_r = shape->d_r;
-  a.page_tokens = shape->page_tokens;
-  a.max_pages = max_pages_per_seq;
-  a.n_splits = plan.n_splits;
-  a.pages_per_split = plan.pages_per_split;
-  a.scale_log2 = shape->sm_scale * 1.4426950408889634f;
-
-  hipStream_t st = (hipStream_t)stream;
-  profile_mark(st, true);
-  if (shape->dtype == TPLA_BF16 && decode_mfma_supported(*shape))
-    rc = launch_decode_mfma(a, st);
-  else
-    rc = launch_decode_generic(a, shape->dtype, st);
-  profile_mark(st, false);
-  if (rc) return rc;
-  return launch_decode_merge(a, st);
+  return decode_common(shape, shape->g, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
+                       n_splits, workspace, workspace_bytes, o_lat, lse, stream);
 }
 
 int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t, float* o,

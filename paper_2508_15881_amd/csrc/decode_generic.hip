@@ -20,7 +20,8 @@ __global__ void __launch_bounds__(GEN_THREADS) decode_generic_kernel(DecodeArgs 
   float* p = smem + w;              // [GEN_THREADS]
   float* red = p + GEN_THREADS;     // [GEN_THREADS]
   const int tid = threadIdx.x;
-  const int b = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;
+  const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
+  const int shard = vb / a.B, b = vb % a.B;
   const int h = blockIdx.y;
   const int L = a.seq_lens[b];
   const int pt = a.page_tokens;
@@ -32,13 +33,13 @@ __global__ void __launch_bounds__(GEN_THREADS) decode_generic_kernel(DecodeArgs 
   const int t_begin = p0 * pt;
   const int t_end = min(p1 * pt, L);
 
-  const T* ql = static_cast<const T*>(a.q_lat) + ((size_t)b * a.H + h) * dl;
+  const T* ql = static_cast<const T*>(a.q_lat) + ((size_t)vb * a.H + h) * dl;
   const T* qp = static_cast<const T*>(a.q_pe) + ((size_t)b * a.H + h) * dr;
   for (int i = tid; i < dl; i += GEN_THREADS) q[i] = load_as_f32(ql + i);
   for (int i = tid; i < dr; i += GEN_THREADS) q[dl + i] = load_as_f32(qp + i);
   __syncthreads();
 
-  const T* pool = static_cast<const T*>(a.pool);
+  const T* pool = static_cast<const T*>(a.pools[shard]);
   const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
   float acc[GEN_MAX_COLS];
 #pragma unroll
@@ -90,7 +91,7 @@ __global__ void __launch_bounds__(GEN_THREADS) decode_generic_kernel(DecodeArgs 
     }
     __syncthreads();
   }
-  const size_t item = ((size_t)b * a.n_splits + s) * a.H + h;
+  const size_t item = ((size_t)vb * a.n_splits + s) * a.H + h;
 #pragma unroll
   for (int c = 0; c < GEN_MAX_COLS; ++c) {
     const int col = tid + c * GEN_THREADS;
@@ -109,19 +110,20 @@ __global__ void __launch_bounds__(GEN_THREADS) decode_generic_kernel(DecodeArgs 
 constexpr int MERGE_MAX_SPLITS = 1024;
 __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
   __shared__ float wgt[MERGE_MAX_SPLITS];
-  const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
+  const int vb = blockIdx.x / a.H, h = blockIdx.x % a.H;   // vb = slice * B + sequence
+  const int b = vb % a.B;
   const int L = a.seq_lens[b];
   const int n_pages = (L + a.page_tokens - 1) / a.page_tokens;
   int cnt = (n_pages + a.pages_per_split - 1) / a.pages_per_split;
   if (cnt > a.n_splits) cnt = a.n_splits;
   const int dl = a.dl;
-  float* out = a.o_lat + ((size_t)b * a.H + h) * dl;
+  float* out = a.o_lat + ((size_t)vb * a.H + h) * dl;
   if (cnt == 0) {
     for (int c = threadIdx.x; c < dl; c += blockDim.x) out[c] = 0.f;
-    if (a.lse && threadIdx.x == 0) a.lse[(size_t)b * a.H + h] = -INFINITY;
+    if (a.lse && threadIdx.x == 0) a.lse[(size_t)vb * a.H + h] = -INFINITY;
     return;
   }
-  const size_t item0 = ((size_t)b * a.n_splits) * a.H + h;
+  const size_t item0 = ((size_t)vb * a.n_splits) * a.H + h;
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
     float M = -INFINITY;
@@ -139,7 +141,7 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
     for (int m = 32; m > 0; m >>= 1) lsum += __shfl_xor(lsum, m);
     const float inv = 1.0f / lsum;
     for (int s = lane; s < cnt; s += 64) wgt[s] *= inv;
-    if (a.lse && lane == 0) a.lse[(size_t)b * a.H + h] = (M + log2f(lsum)) * 0.6931471805599453f;
+    if (a.lse && lane == 0) a.lse[(size_t)vb * a.H + h] = (M + log2f(lsum)) * 0.6931471805599453f;
   }
   __syncthreads();
   if ((dl & 3) == 0) {
@@ -167,7 +169,7 @@ int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st) {
   const size_t smem = (size_t)(a.dl + a.d_r + 2 * GEN_THREADS) * sizeof(float);
   if (smem > 64 * 1024) return fail(TPLA_ERR_UNSUPPORTED, "row too wide for the generic kernel");
   if (a.H > 65535) return fail(TPLA_ERR_UNSUPPORTED, "H above 65535");
-  dim3 grid((unsigned)(a.B * a.n_splits), (unsigned)a.H);
+  dim3 grid((unsigned)(a.n_shards * a.B * a.n_splits), (unsigned)a.H);
   if (dtype == TPLA_F32)
     hipLaunchKernelGGL(decode_generic_kernel<float>, grid, dim3(GEN_THREADS), smem, st, a);
   else
@@ -177,7 +179,7 @@ int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st) {
 
 int launch_decode_merge(const DecodeArgs& a, hipStream_t st) {
   const int threads = a.dl >= 512 ? 128 : 64;
-  hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(a.B * a.H)), dim3(threads), 0, st, a);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3((unsigned)(a.n_shards * a.B * a.H)), dim3(threads), 0, st, a);
   return check_launch("decode_merge_kernel");
 }
 

@@ -96,7 +96,8 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j16 = lane & 15, q4 = lane >> 4;
-  const int b = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;
+  const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
+  const int shard = vb / a.B, b = vb % a.B;
   const int p0 = s * a.pages_per_split;
   // Page ids of this chunk live in a register, 64 pages at a time (lane i
   // holds page p0 + pg_base + i), and are read back with v_readlane: a memory
@@ -114,7 +115,7 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
   const int t_end = min(p1 * PAGE_TOKENS, L);
   const int ntiles = (t_end - t_begin + TOK - 1) / TOK;
   const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
-  const char* pool = static_cast<const char*>(a.pool);
+  const char* pool = static_cast<const char*>(a.pools[shard]);
 
   // ---- direct-to-LDS bookkeeping ---------------------------------------------
   // Instruction k of a tile fills LDS pieces [64k, 64k+64).  This wave issues
@@ -184,7 +185,7 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
   const int head = wave * 16 + j16;
   bf16x8 qreg[KS];
   {
-    const bf16_t* ql = static_cast<const bf16_t*>(a.q_lat) + ((size_t)b * a.H + head) * DL;
+    const bf16_t* ql = static_cast<const bf16_t*>(a.q_lat) + ((size_t)vb * a.H + head) * DL;
     const bf16_t* qp = static_cast<const bf16_t*>(a.q_pe) + ((size_t)b * a.H + head) * DR;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -323,7 +324,7 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
 
   float l_tot = l_run + __shfl_xor(l_run, 16);
   l_tot += __shfl_xor(l_tot, 32);
-  const size_t item = ((size_t)b * a.n_splits + s) * a.H + head;
+  const size_t item = ((size_t)vb * a.n_splits + s) * a.H + head;
   float* pacc = a.part_acc + item * DL + 4 * q4;
 #ifndef TPLA_EXP_NOSTORE
 #pragma unroll
@@ -412,7 +413,7 @@ int launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
   KernelInfo* k = nullptr;
   const int rc = kernel_info_for(a.dl, a.H, &k);
   if (rc) return rc;
-  hipLaunchKernelGGL(k->fn, dim3((unsigned)(a.B * a.n_splits)), dim3(k->threads), k->smem, st, a);
+  hipLaunchKernelGGL(k->fn, dim3((unsigned)(a.n_shards * a.B * a.n_splits)), dim3(k->threads), k->smem, st, a);
   return check_launch("decode_mfma_kernel");
 }
 

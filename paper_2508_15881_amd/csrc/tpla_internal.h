@@ -23,20 +23,23 @@ struct SplitPlan {
   int32_t n_splits;
   int32_t pages_per_split;
 };
-SplitPlan plan_splits(const tpla_shape_t& sh, int32_t max_pages_per_seq, int32_t n_splits_req);
+SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_pages_per_seq, int32_t n_splits_req);
 
-// Partial results of one (sequence, split): acc [B, S, H, dl] floats, then
-// ml [B, S, H, 2] floats (running max in log2 units, sum of weights).
+// Partial results of one (slice, sequence, split): acc [n_shards, B, S, H, dl]
+// floats, then ml [n_shards, B, S, H, 2] floats (running max in log2 units, sum of weights).
+// Several latent slices can share one launch: slice i uses q_lat[i], pools[i],
+// the common q_pe / page table / lengths, and row i of every output.
 struct DecodeArgs {
-  const void* q_lat;     // [B, H, dl]
+  const void* q_lat;     // [n_shards, B, H, dl]
   const void* q_pe;      // [B, H, d_r]
-  const void* pool;      // [P, page_tokens, dl + d_r]
+  const void* pools[TPLA_MAX_G];   // each [P, page_tokens, dl + d_r]
   const int32_t* block_table;
   const int32_t* seq_lens;
   float* part_acc;
   float* part_ml;
-  float* o_lat;          // [B, H, dl]
-  float* lse;            // [B, H] or nullptr
+  float* o_lat;          // [n_shards, B, H, dl]
+  float* lse;            // [n_shards, B, H] or nullptr
+  int32_t n_shards;
   int32_t B, H, dl, d_r, page_tokens, max_pages;
   int32_t n_splits, pages_per_split;
   float scale_log2;      // sm_scale * log2(e)

@@ -49,7 +49,8 @@ class DecodeStep:
         self.o_lat = torch.empty((g, Bn, H, dl), dtype=torch.float32, device=device)
         self.lse = torch.empty((g, Bn, H), dtype=torch.float32, device=device)
         self.o = torch.empty((Bn, H, shape.d_v), dtype=torch.float32, device=device)
-        self.ws_bytes = B.tpla_workspace_bytes(shape, self.max_pages, self.n_splits)
+        self.ws_bytes = max(B.tpla_workspace_bytes(shape, self.max_pages, self.n_splits),
+                            B.tpla_workspace_bytes_all(shape, self.max_pages, self.n_splits))
         if self.ws_bytes == 0:
             raise B.TplaError(-2, B.tpla_last_error())
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
@@ -62,13 +63,24 @@ class DecodeStep:
                             seq_lens, self.n_splits, self.workspace, self.ws_bytes,
                             self.o_lat[i], self.lse[i])
 
+    def decode_all(self, q_pe, shard_pools, block_table, seq_lens):
+        """All g slices in one launch."""
+        B.tpla_decode_shards(self.shape, self.q_lat, q_pe, shard_pools, block_table, self.max_pages,
+                             seq_lens, self.n_splits, self.workspace, self.ws_bytes, self.o_lat, self.lse)
+
     def combine(self, W_UV_t):
         B.tpla_combine_shards(self.shape, self.o_lat, W_UV_t, self.o)
 
-    def run(self, q_nope, q_pe, W_UK_t, W_UV_t, shard_pools, block_table, seq_lens, mu=None):
+    def run(self, q_nope, q_pe, W_UK_t, W_UV_t, shard_pools, block_table, seq_lens, mu=None, fused=True):
+        """One decode layer-step.  fused: all slices in one decode launch (how one GPU
+        runs the whole step); otherwise one tpla_decode_shard call per slice (one
+        device's share at a time)."""
         self.absorb(q_nope, W_UK_t, mu)
-        for i in range(self.shape.g):
-            self.decode(i, q_pe, shard_pools[i], block_table, seq_lens)
+        if fused:
+            self.decode_all(q_pe, shard_pools, block_table, seq_lens)
+        else:
+            for i in range(self.shape.g):
+                self.decode(i, q_pe, shard_pools[i], block_table, seq_lens)
         self.combine(W_UV_t)
         return self.o
 

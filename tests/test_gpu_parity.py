@@ -88,6 +88,43 @@ def test_decode_shard_softmax_properties_at_long_context():
         assert np.all(o[b] <= lat.max(axis=0) + 1e-3) and np.all(o[b] >= lat.min(axis=0) - 1e-3)
 
 
+def test_decode_shards_equals_one_call_per_slice():
+    # all slices in one launch == g single-slice calls, bit for bit at equal split count
+    w = wl.scaled(DSV3, B=3)
+    lens = np.array([700, 65, 2048], dtype=np.int32)
+    _say("decode_shards vs decode_shard")
+    probs = [build_shard_problem(w, lens, rng_extra=i) for i in range(w.g)]
+    shape = pl.make_shape(w)
+    dev = "cuda"
+    q_lat = pl.to_device(np.stack([p["q_lat"] for p in probs]), "bf16")
+    q_pe = pl.to_device(probs[0]["q_pe"], "bf16")
+    pools = [pl.to_device(p["pool"], "bf16") for p in probs]
+    # the slices share one page table: reuse slice 0's table for every pool
+    for i in range(1, w.g):
+        pools[i] = pl.to_device(probs[0]["pool"][:, :, ::-1].copy(), "bf16")    # different contents, same paging
+    bt = torch.from_numpy(probs[0]["bt"]).to(dev); ln = torch.from_numpy(lens).to(dev)
+    mp = probs[0]["max_pages"]
+    for n_splits in (0, 4):
+        ws_b = tp.tpla_workspace_bytes_all(shape, mp, n_splits)
+        ws = torch.empty(ws_b, dtype=torch.uint8, device=dev)
+        o_all = torch.full((w.g, 3, w.H, w.dl), float("nan"), dtype=torch.float32, device=dev)
+        l_all = torch.full((w.g, 3, w.H), float("nan"), dtype=torch.float32, device=dev)
+        tp.tpla_decode_shards(shape, q_lat, q_pe, pools, bt, mp, ln, n_splits, ws, ws_b, o_all, l_all)
+        o_one = torch.empty_like(o_all); l_one = torch.empty_like(l_all)
+        ws1_b = tp.tpla_workspace_bytes(shape, mp, n_splits)
+        ws1 = torch.empty(ws1_b, dtype=torch.uint8, device=dev)
+        for i in range(w.g):
+            tp.tpla_decode_shard(shape, q_lat[i], q_pe, pools[i], bt, mp, ln, n_splits, ws1, ws1_b, o_one[i], l_one[i])
+        torch.cuda.synchronize()
+        if n_splits:
+            assert torch.equal(o_all, o_one) and torch.equal(l_all, l_one)
+        else:
+            assert rel_err(o_all.cpu().numpy(), o_one.cpu().numpy()) <= 1e-4
+    # and against the oracle for slice 0
+    ro, rl = oracle_decode_shard(probs[0])
+    assert rel_err(o_all[0].cpu().numpy(), ro) <= TOL["bf16"]
+
+
 # ------------------------------------------------------------ tiny config, whole path
 def _full_problem(w):
     m = wl.draw_model_side(w)
