@@ -80,40 +80,51 @@ static int check_shape(const tpla_shape_t* sh) {
 
 SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_pages, int32_t n_splits_req) {
   SplitPlan p;
+  p.balanced = 0;
+  p.n_wg = 0;
   int32_t n = n_splits_req;
+  if (n <= 0 && sh.dtype == TPLA_BF16 && decode_mfma_supported(sh)) {
+    // Automatic plan of the matrix-core kernel: exactly as many workgroups as
+    // the chip holds at once, each taking an equal share of all pages.
+    int per_cu = decode_mfma_blocks_per_cu(sh);
+    if (per_cu <= 0) per_cu = 2;
+    int n_wg = device_cu_count() * per_cu;
+    if (n_wg > 1024) n_wg = 1024;     // the merge handles at most 1024 partial results per sequence
+    const long long most = (long long)n_shards * sh.B * max_pages;
+    if (n_wg > most) n_wg = (int)most;
+    p.balanced = 1;
+    p.n_wg = n_wg;
+    p.n_splits = 1;
+    p.pages_per_split = max_pages;
+    return p;
+  }
   if (n <= 0) {
-    // One resident workgroup per slot and no second round: with B * n at most
-    // the number of workgroups the chip holds at once, every chunk runs
-    // concurrently and chunks are equal.  That only balances when sequences
-    // have similar lengths, so it is used while a chunk stays within 64
-    // pages; beyond that (long tables: long or ragged batches) chunks are 32
-    // pages and the hardware dispatcher balances the many small workgroups.
-    // A chunk keeps at least 4 pages so the partial results stay a small
-    // fraction of the bytes read.
-    int per_cu = 4;
-    if (sh.dtype == TPLA_BF16 && decode_mfma_supported(sh)) {
-      per_cu = decode_mfma_blocks_per_cu(sh);
-      if (per_cu <= 0) per_cu = 2;
-    }
-    const int slots = device_cu_count() * per_cu;
+    // Static chunks sized so that one round of workgroups covers the batch
+    // when sequences are equally long; at least 4 pages per chunk.
+    const int slots = device_cu_count() * 4;
     n = slots / (sh.B * n_shards);
-    if (n < 1) n = 1;
-    if ((max_pages + n - 1) / n > 64) n = (max_pages + 31) / 32;
     const int32_t cap = (max_pages + 3) / 4;
     if (n > cap) n = cap;
+    if (n > 1024) n = 1024;
     if (n < 1) n = 1;
   }
   if (n > max_pages) n = max_pages;
-  if (n > 1024 && n_splits_req <= 0) n = 1024;   // the merge handles at most 1024 chunks per sequence
   if (n < 1) n = 1;
   p.pages_per_split = (max_pages + n - 1) / n;
   p.n_splits = (max_pages + p.pages_per_split - 1) / p.pages_per_split;
   return p;
 }
 
+// Partial-result slots of a plan, and the workspace: acc [slots, H, dl] floats,
+// (reference, sum) [slots, H, 2] floats, then (balanced) the page-offset table.
+static size_t plan_slots(const tpla_shape_t& sh, int n_shards, const SplitPlan& p) {
+  return p.balanced ? (size_t)p.n_wg + (size_t)n_shards * sh.B : (size_t)n_shards * sh.B * p.n_splits;
+}
 static size_t workspace_for(const tpla_shape_t& sh, int n_shards, const SplitPlan& p) {
   const size_t dl = (size_t)(sh.d_c / sh.g);
-  return (size_t)n_shards * sh.B * p.n_splits * sh.H * (dl + 2) * sizeof(float);
+  size_t bytes = plan_slots(sh, n_shards, p) * sh.H * (dl + 2) * sizeof(float);
+  if (p.balanced) bytes += (((size_t)n_shards * sh.B + 1) * sizeof(int32_t) + 15) / 16 * 16;
+  return bytes;
 }
 
 // Validation, planning and launches shared by the one-slice and the
@@ -143,8 +154,9 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
     return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
   if (plan.n_splits > 1024)
     return fail(TPLA_ERR_UNSUPPORTED, "n_splits=%d above 1024", plan.n_splits);
-  if ((int64_t)n_shards * shape->B * plan.n_splits > (int64_t)2147483647 / 4)
-    return fail(TPLA_ERR_UNSUPPORTED, "n_shards * B * n_splits too large");
+  if ((int64_t)n_shards * shape->B * plan.n_splits > (int64_t)2147483647 / 4 ||
+      (int64_t)n_shards * shape->B * max_pages_per_seq > (int64_t)2147483647 / 2)
+    return fail(TPLA_ERR_UNSUPPORTED, "n_shards * B * n_splits (or * max_pages_per_seq) too large");
 
   DecodeArgs a;
   const int dl = shape->d_c / shape->g;
@@ -154,7 +166,11 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
   a.block_table = block_table;
   a.seq_lens = seq_lens;
   a.part_acc = static_cast<float*>(workspace);
-  a.part_ml = a.part_acc + (size_t)n_shards * shape->B * plan.n_splits * shape->H * dl;
+  const size_t slots = plan_slots(*shape, n_shards, plan);
+  a.part_ml = a.part_acc + slots * shape->H * dl;
+  a.plan = reinterpret_cast<int32_t*>(a.part_ml + slots * shape->H * 2);
+  a.balanced = plan.balanced;
+  a.n_wg = plan.n_wg;
   a.o_lat = o_lat;
   a.lse = lse;
   a.n_shards = n_shards;

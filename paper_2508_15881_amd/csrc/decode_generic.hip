@@ -103,36 +103,60 @@ __global__ void __launch_bounds__(GEN_THREADS) decode_generic_kernel(DecodeArgs 
   }
 }
 
-// One workgroup = one (sequence, head): combines the non-empty splits in
-// ascending split order (fixed order => reproducible bits).  Wave 0 turns the
-// (reference, weight-sum) pairs into one normalised factor per split; then
-// every thread sums its columns over the splits.
+// One workgroup = one (slice, sequence, head): combines that sequence's
+// partial results in ascending order of the work items (fixed order =>
+// reproducible bits).  Wave 0 lists the contributing slots and turns their
+// (reference, weight-sum) pairs into one normalised factor each; then every
+// thread sums its columns over the slots.
 constexpr int MERGE_MAX_SPLITS = 1024;
 __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
   __shared__ float wgt[MERGE_MAX_SPLITS];
+  __shared__ int slot_of[MERGE_MAX_SPLITS];
+  __shared__ int cnt_sh;
   const int vb = blockIdx.x / a.H, h = blockIdx.x % a.H;   // vb = slice * B + sequence
   const int b = vb % a.B;
   const int L = a.seq_lens[b];
   const int n_pages = (L + a.page_tokens - 1) / a.page_tokens;
-  int cnt = (n_pages + a.pages_per_split - 1) / a.pages_per_split;
-  if (cnt > a.n_splits) cnt = a.n_splits;
   const int dl = a.dl;
   float* out = a.o_lat + ((size_t)vb * a.H + h) * dl;
-  if (cnt == 0) {
+  if (n_pages == 0) {
     for (int c = threadIdx.x; c < dl; c += blockDim.x) out[c] = 0.f;
     if (a.lse && threadIdx.x == 0) a.lse[(size_t)vb * a.H + h] = -INFINITY;
     return;
   }
-  const size_t item0 = ((size_t)vb * a.n_splits) * a.H + h;
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
+    int cnt;
+    if (!a.balanced) {
+      cnt = (n_pages + a.pages_per_split - 1) / a.pages_per_split;
+      if (cnt > a.n_splits) cnt = a.n_splits;
+      for (int s = lane; s < cnt; s += 64) slot_of[s] = vb * a.n_splits + s;
+    } else {
+      // workgroups whose page range [w T / W, (w+1) T / W) meets [c0, c0 + n_pages)
+      const int n_v = a.n_shards * a.B;
+      const long long T = a.plan[n_v], W = a.n_wg;
+      const long long c0 = a.plan[vb], c1 = c0 + n_pages;
+      long long w0 = c0 * W / T;
+      while (w0 + 1 < W && (w0 + 1) * T / W <= c0) ++w0;
+      while (w0 > 0 && w0 * T / W > c0) --w0;
+      cnt = 0;
+      for (long long w = w0; w < W && w * T / W < c1; ++w) {
+        const long long lo = max(w * T / W, c0), hi = min((w + 1) * T / W, c1);
+        if (hi > lo) {
+          if (lane == 0) slot_of[cnt] = (int)w + vb;
+          ++cnt;
+        }
+      }
+    }
+    if (lane == 0) cnt_sh = cnt;
+    __builtin_amdgcn_wave_barrier();
     float M = -INFINITY;
-    for (int s = lane; s < cnt; s += 64) M = fmaxf(M, a.part_ml[(item0 + (size_t)s * a.H) * 2]);
+    for (int s = lane; s < cnt; s += 64) M = fmaxf(M, a.part_ml[((size_t)slot_of[s] * a.H + h) * 2]);
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) M = fmaxf(M, __shfl_xor(M, m));
     float lsum = 0.f;
     for (int s = lane; s < cnt; s += 64) {
-      const float* ml = a.part_ml + (item0 + (size_t)s * a.H) * 2;
+      const float* ml = a.part_ml + ((size_t)slot_of[s] * a.H + h) * 2;
       const float e = exp2f(ml[0] - M);
       wgt[s] = e;
       lsum = fmaf(ml[1], e, lsum);
@@ -144,11 +168,12 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
     if (a.lse && lane == 0) a.lse[(size_t)vb * a.H + h] = (M + log2f(lsum)) * 0.6931471805599453f;
   }
   __syncthreads();
+  const int cnt = cnt_sh;
   if ((dl & 3) == 0) {
     for (int c = threadIdx.x * 4; c < dl; c += blockDim.x * 4) {
       float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
       for (int s = 0; s < cnt; ++s) {
-        const float4 p = *reinterpret_cast<const float4*>(a.part_acc + (item0 + (size_t)s * a.H) * dl + c);
+        const float4 p = *reinterpret_cast<const float4*>(a.part_acc + ((size_t)slot_of[s] * a.H + h) * dl + c);
         const float w = wgt[s];
         v0 = fmaf(p.x, w, v0); v1 = fmaf(p.y, w, v1); v2 = fmaf(p.z, w, v2); v3 = fmaf(p.w, w, v3);
       }
@@ -157,7 +182,7 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
   } else {
     for (int c = threadIdx.x; c < dl; c += blockDim.x) {
       float v = 0.f;
-      for (int s = 0; s < cnt; ++s) v = fmaf(a.part_acc[(item0 + (size_t)s * a.H) * dl + c], wgt[s], v);
+      for (int s = 0; s < cnt; ++s) v = fmaf(a.part_acc[((size_t)slot_of[s] * a.H + h) * dl + c], wgt[s], v);
       out[c] = v;
     }
   }

@@ -75,8 +75,12 @@ __device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
 // the swizzle is applied to the global address each lane fetches from.
 __device__ __forceinline__ int swz(int tok) { return (tok >> 1) & 7; }
 
+// One work item: pages [p0, p1) of sequence b of slice `shard` (L tokens in
+// the sequence, p1 <= its page count); the partial result goes to slot
+// `slot` of the workspace.  Called by every thread of the workgroup.
 template <int DL, int DR, int NW, int TOK, int NSTAGE>
-__global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
+__device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, int shard, int b, int L,
+                                            int p0, int p1, size_t slot) {
   constexpr int RC = (DL + DR) / 8;      // 16-byte pieces per row
   constexpr int KS = (DL + DR) / 32;     // k-steps of the score product
   constexpr int DB = DL / 16;            // 16-wide blocks of latent dims
@@ -91,31 +95,23 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
   static_assert(TOK % 32 == 0 && PAGE_TOKENS % TOK == 0 && TC % 64 == 0, "tile size");
   static_assert(NSTAGE == 3, "the wait counts below assume two tiles in flight");
 
-  extern __shared__ u32x4 smem[];        // NSTAGE tiles
   const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j16 = lane & 15, q4 = lane >> 4;
-  const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
-  const int shard = vb / a.B, b = vb % a.B;
-  const int p0 = s * a.pages_per_split;
+  const int vb = shard * a.B + b;
   // Page ids of this chunk live in a register, 64 pages at a time (lane i
   // holds page p0 + pg_base + i), and are read back with v_readlane: a memory
   // load per tile would have to wait for every direct-to-LDS load before it.
-  // The first batch is fetched together with the sequence length (entries
-  // past the sequence's last page are inside the table row and never used).
-  int pg_reg = a.block_table[(size_t)b * a.max_pages + min(p0 + lane, a.max_pages - 1)];
-  const int L = a.seq_lens[b];
-  const int n_pages = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
-  if (p0 >= n_pages) return;
+  int pg_reg = a.block_table[(size_t)b * a.max_pages + min(p0 + lane, p1 - 1)];
   asm volatile("" : "+v"(pg_reg));
-  int p1 = p0 + a.pages_per_split;
-  if (p1 > n_pages) p1 = n_pages;
   const int t_begin = p0 * PAGE_TOKENS;
   const int t_end = min(p1 * PAGE_TOKENS, L);
   const int ntiles = (t_end - t_begin + TOK - 1) / TOK;
   const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
   const char* pool = static_cast<const char*>(a.pools[shard]);
+  // the ring restarts at buffer 0: nobody may still be reading the previous item's tiles
+  __syncthreads();
 
   // ---- direct-to-LDS bookkeeping ---------------------------------------------
   // Instruction k of a tile fills LDS pieces [64k, 64k+64).  This wave issues
@@ -324,7 +320,7 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
 
   float l_tot = l_run + __shfl_xor(l_run, 16);
   l_tot += __shfl_xor(l_tot, 32);
-  const size_t item = ((size_t)vb * a.n_splits + s) * a.H + head;
+  const size_t item = slot * a.H + head;
   float* pacc = a.part_acc + item * DL + 4 * q4;
 #ifndef TPLA_EXP_NOSTORE
 #pragma unroll
@@ -338,6 +334,75 @@ __global__ void __launch_bounds__(NW * 64) decode_mfma_kernel(DecodeArgs a) {
   }
 }
 
+// Static chunks: workgroup = (slice, sequence, chunk s), pages [s*pps, (s+1)*pps).
+// Waves per SIMD the register allocation must allow: two 4-wave workgroups
+// (or one 8-wave workgroup) per compute unit need 2; a 512-wide slice only
+// fits one workgroup per compute unit in LDS, so it keeps the full budget.
+template <int DL, int NW>
+constexpr int waves_per_simd() { return DL >= 512 ? (NW >= 8 ? 2 : 1) : (NW >= 4 ? 2 : 1); }
+
+template <int DL, int DR, int NW, int TOK, int NSTAGE>
+__global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mfma_kernel(DecodeArgs a) {
+  extern __shared__ u32x4 smem[];        // NSTAGE tiles
+  const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
+  const int shard = vb / a.B, b = vb % a.B;
+  const int L = a.seq_lens[b];
+  const int n_pages = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
+  const int p0 = s * a.pages_per_split;
+  if (p0 >= n_pages) return;
+  const int p1 = min(p0 + a.pages_per_split, n_pages);
+  decode_item<DL, DR, NW, TOK, NSTAGE>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
+}
+
+// Balanced ranges: the pages of all (slice, sequence) pairs are laid end to
+// end (T pages) and workgroup w of W takes [w T / W, (w+1) T / W), whatever
+// sequences that covers; every (workgroup, sequence) overlap is one work item
+// whose partial result goes to slot w + v (v = slice * B + sequence; strictly
+// increasing along the items, hence unique).  Workgroup 0 also publishes the
+// page offsets of the sequences for the merge.
+template <int DL, int DR, int NW, int TOK, int NSTAGE>
+__global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mfma_balanced_kernel(DecodeArgs a) {
+  extern __shared__ u32x4 smem[];
+  const int lane = threadIdx.x & 63;
+  const int n_v = a.n_shards * a.B;
+  const int w = blockIdx.x, W = gridDim.x;
+  // every wave scans the lengths by itself (no LDS, no barrier)
+  int total = 0;
+  for (int v0 = 0; v0 < n_v; v0 += 64) {
+    const int v = v0 + lane;
+    int pg = (v < n_v) ? (a.seq_lens[v % a.B] + PAGE_TOKENS - 1) / PAGE_TOKENS : 0;
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) pg += __shfl_xor(pg, m);
+    total += pg;
+  }
+  const int start = (int)((long long)w * total / W), end = (int)((long long)(w + 1) * total / W);
+  int base = 0;
+  for (int v0 = 0; v0 < n_v; v0 += 64) {
+    const int v = v0 + lane;
+    const int L = (v < n_v) ? a.seq_lens[v % a.B] : 0;
+    const int pg = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
+    int incl = pg;                               // inclusive prefix sum over the wave
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(incl, d);
+      if (lane >= d) incl += o;
+    }
+    const int excl = base + incl - pg;
+    if (w == 0 && v < n_v && threadIdx.x < 64) a.plan[v] = excl;
+    unsigned long long hit = __ballot(pg > 0 && excl < end && excl + pg > start);
+    while (hit) {
+      const int src = __builtin_ctzll(hit);
+      hit &= hit - 1;
+      const int e = __shfl(excl, src), n = __shfl(pg, src), Ls = __shfl(L, src);
+      const int vs = v0 + src;
+      const int p0 = max(start, e) - e, p1 = min(end, e + n) - e;
+      decode_item<DL, DR, NW, TOK, NSTAGE>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
+    }
+    base += __shfl(incl, 63);
+  }
+  if (w == 0 && threadIdx.x == 0) a.plan[n_v] = total;
+}
+
 bool decode_mfma_supported(const tpla_shape_t& sh) {
   if (sh.dtype != TPLA_BF16 || sh.page_tokens != PAGE_TOKENS || sh.d_r != 64) return false;
   const int dl = sh.d_c / sh.g;
@@ -349,6 +414,7 @@ bool decode_mfma_supported(const tpla_shape_t& sh) {
 // compute unit (0 when the runtime cannot tell, e.g. without a device).
 struct KernelInfo {
   void (*fn)(DecodeArgs) = nullptr;
+  void (*fn_balanced)(DecodeArgs) = nullptr;
   size_t smem = 0;
   int threads = 0;
   int blocks_per_cu = 0;
@@ -361,17 +427,20 @@ static int kernel_info(KernelInfo** out) {
   static KernelInfo info;
   if (!info.ready) {
     info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE>;
+    info.fn_balanced = decode_mfma_balanced_kernel<DL, 64, NW, TOK, NSTAGE>;
     info.smem = (size_t)NSTAGE * TOK * ((DL + 64) / 8) * 16;
     info.threads = NW * 64;
     // dynamic LDS above the 64 KiB default needs opting in
     if (info.smem > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)info.smem) != hipSuccess) {
+        (hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)info.smem) != hipSuccess ||
+         hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn_balanced),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)info.smem) != hipSuccess)) {
       (void)hipGetLastError();
       return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", info.smem);
     }
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(info.fn), info.threads,
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(info.fn_balanced), info.threads,
                                                      info.smem) != hipSuccess) {
       (void)hipGetLastError();
       n = 0;
@@ -413,7 +482,10 @@ int launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
   KernelInfo* k = nullptr;
   const int rc = kernel_info_for(a.dl, a.H, &k);
   if (rc) return rc;
-  hipLaunchKernelGGL(k->fn, dim3((unsigned)(a.n_shards * a.B * a.n_splits)), dim3(k->threads), k->smem, st, a);
+  if (a.balanced)
+    hipLaunchKernelGGL(k->fn_balanced, dim3((unsigned)a.n_wg), dim3(k->threads), k->smem, st, a);
+  else
+    hipLaunchKernelGGL(k->fn, dim3((unsigned)(a.n_shards * a.B * a.n_splits)), dim3(k->threads), k->smem, st, a);
   return check_launch("decode_mfma_kernel");
 }
 

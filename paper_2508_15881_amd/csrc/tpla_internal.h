@@ -19,9 +19,13 @@ typedef __bf16 bf16_t;
 // Split plan of the decode: the sequence axis of every sequence is cut into
 // chunks of pages_per_split pages; chunk s of sequence b is non-empty when
 // s * pages_per_split < ceil(seq_lens[b] / page_tokens).
+// Balanced mode instead lays all pages end to end and gives each of n_wg
+// workgroups an equal range (see decode_mfma_balanced_kernel).
 struct SplitPlan {
-  int32_t n_splits;
-  int32_t pages_per_split;
+  int32_t balanced;
+  int32_t n_wg;              // balanced: workgroups; partial slots = n_wg + n_shards * B
+  int32_t n_splits;          // static
+  int32_t pages_per_split;   // static
 };
 SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_pages_per_seq, int32_t n_splits_req);
 
@@ -42,6 +46,8 @@ struct DecodeArgs {
   int32_t n_shards;
   int32_t B, H, dl, d_r, page_tokens, max_pages;
   int32_t n_splits, pages_per_split;
+  int32_t balanced, n_wg;
+  int32_t* plan;         // balanced: [n_shards * B + 1] first page of every sequence, then the total
   float scale_log2;      // sm_scale * log2(e)
 };
 
