@@ -25,9 +25,12 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM traffic of one split-kernel launch measured with rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), bytes per
 # launch; see profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/decode_split_kernel_dsv3_32k_hbm_traffic.txt: 1361.2 MB read + 33.8 MB written
+    "dsv3_32k": 1395.0e6,
+}
 MEASURED_TRAFFIC_ONE_SLICE = {
-    # profiles/decode_split_kernel_dsv3_32k_hbm_traffic.txt: 681.8 MB read + 33.8 MB written
+    # same counters on a one-slice launch with 16 chunks per sequence: 681.8 MB read + 33.8 MB written
     "dsv3_32k": 715.6e6,
 }
 
@@ -78,6 +81,9 @@ def main():
     ap.add_argument("--workload", default="dsv3_32k")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="only the timed steps: no one-slice loop, stage timings or MLA reference "
+                         "(keeps every launch of the decode kernel in a profile identical)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (all g latent slices are computed on it and "
@@ -155,13 +161,15 @@ def main():
     kern_ms = tp.tpla_profile_collect(args.steps)
 
     # one device's share: the same kernel launched for one slice at a time
-    n_one = min(args.steps, 200)
-    tp.tpla_profile_enable(n_one * w.g)
-    for _ in range(n_one):
-        for i in range(w.g):
-            step.decode(i, q_pe, pools[i], bt, lens)
-    torch.cuda.synchronize()
-    one_ms = tp.tpla_profile_collect(n_one * w.g)
+    n_one = 0 if args.skip_extras else min(args.steps, 200)
+    one_ms = [float("nan")]
+    if n_one:
+        tp.tpla_profile_enable(n_one * w.g)
+        for _ in range(n_one):
+            for i in range(w.g):
+                step.decode(i, q_pe, pools[i], bt, lens)
+        torch.cuda.synchronize()
+        one_ms = tp.tpla_profile_collect(n_one * w.g)
     tp.tpla_profile_enable(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -175,6 +183,8 @@ def main():
 
     # stage breakdown (untimed region, events on torch's current stream = the launch stream)
     def timed(fn, reps=20):
+        if args.skip_extras:
+            return float("nan")
         fn(); torch.cuda.synchronize()
         ev0.record()
         for _ in range(reps):
@@ -193,15 +203,17 @@ def main():
     shape1 = pl.make_shape(w1)
     step1 = pl.DecodeStep(shape1, model["max_pages"], 0)
     step1.absorb(q_nope, W_UK_t, None)
-    n_mla = min(args.steps, 100)
-    for _ in range(3):
-        step1.decode(0, q_pe, mla_pool, bt, lens)
-    tp.tpla_profile_enable(n_mla)
-    for _ in range(n_mla):
-        step1.decode(0, q_pe, mla_pool, bt, lens)
-    torch.cuda.synchronize()
-    mla_ms = float(np.mean(tp.tpla_profile_collect(n_mla)))
-    tp.tpla_profile_enable(0)
+    n_mla = 0 if args.skip_extras else min(args.steps, 100)
+    mla_ms = float("nan")
+    if n_mla:
+        for _ in range(3):
+            step1.decode(0, q_pe, mla_pool, bt, lens)
+        tp.tpla_profile_enable(n_mla)
+        for _ in range(n_mla):
+            step1.decode(0, q_pe, mla_pool, bt, lens)
+        torch.cuda.synchronize()
+        mla_ms = float(np.mean(tp.tpla_profile_collect(n_mla)))
+        tp.tpla_profile_enable(0)
     mla_bytes = wl.algorithmic_bytes_per_shard(w1, lens_np)
 
     out = {
@@ -240,7 +252,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, model)
-    print(json.dumps(out))
+    print(json.dumps(out).replace("NaN", "null"))
 
 
 if __name__ == "__main__":

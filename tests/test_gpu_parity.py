@@ -60,12 +60,32 @@ def test_decode_shard_generic_shapes(dtype):
         assert np.all(o[1] == 0) and np.all(np.isneginf(lse[1]))
 
 
+def test_decode_shard_many_short_sequences():
+    # more sequences than workgroups' page ranges can separate: the automatic plan
+    # gives a workgroup pieces of several sequences, and sequences several workgroups
+    w = wl.scaled(RAGGED, H=16)
+    rng = np.random.default_rng(99)
+    lens = rng.integers(0, 400, size=700)
+    lens[::97] = 0
+    lens[5] = 9000                       # one long sequence among the short ones
+    _say(f"decode_shard many short sequences B={len(lens)} tokens={int(lens.sum())}")
+    prob = build_shard_problem(w, lens)
+    o, lse = run_decode_shard(prob, 0)
+    ro, rl = oracle_decode_shard(prob)
+    nz = lens > 0
+    assert rel_err(o, ro) <= TOL["bf16"]
+    assert np.max(np.abs(lse[nz] - rl[nz])) <= 1e-2
+    assert np.all(o[~nz] == 0) and np.all(np.isneginf(lse[~nz]))
+    o2, lse2 = run_decode_shard(prob, 0)
+    assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
+
+
 def test_decode_shard_paging_is_bit_invariant():
     lens = [700, 65, 1, 2048]
     _say("decode_shard paging invariance")
     a = build_shard_problem(DSV3, lens, permute=True, slack_pages=5, poison=True)
     b = build_shard_problem(DSV3, lens, permute=False, slack_pages=0, poison=False)
-    for n_splits in (1, 4):
+    for n_splits in (0, 1, 4):
         oa, la = run_decode_shard(a, n_splits)
         ob, lb = run_decode_shard(b, n_splits)
         assert np.array_equal(oa, ob) and np.array_equal(la, lb)
