@@ -87,58 +87,125 @@ int launch_transform_axis(const TransformArgs& t, const void* src, void* dst, in
 // Streaming pass over MLA pages: row = [latent d_c | k_pe d_r].  LPR = d_c/8
 // lanes cooperate on one row (LPR a power of two <= 64).  After the transform
 // lane l holds elements 8l..8l+7 of c U, which belong to slice (8l)/dl.
+// Value of lane (l ^ M) without going through LDS: DPP for M < 16, the
+// row / half swaps of gfx950 above that.
+template <int M>
+__device__ __forceinline__ float lane_xor(float v, int lane) {
+  const int x = __float_as_int(v);
+  if constexpr (M == 1) return __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  if constexpr (M == 2) return __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  if constexpr (M == 4) {
+    // rotations by 4 and 12 inside a row of 16: one of them is lane l + 4, the other l - 4
+    const int a = __builtin_amdgcn_update_dpp(x, x, 0x124, 0xF, 0xF, false);   // row_ror:4  -> lane (l - 4) & 15
+    const int b = __builtin_amdgcn_update_dpp(x, x, 0x12C, 0xF, 0xF, false);   // row_ror:12 -> lane (l + 4) & 15
+    return __int_as_float((lane & 4) ? a : b);
+  }
+  if constexpr (M == 8) return __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x128, 0xF, 0xF, false));  // row_ror:8
+  if constexpr (M == 16) {
+    // swaps rows 1,3 of the first operand with rows 0,2 of the second
+    const auto r = __builtin_amdgcn_permlane16_swap((unsigned)x, (unsigned)x, false, false);
+    return __int_as_float((int)((lane & 16) ? r[0] : r[1]));
+  }
+  if constexpr (M == 32) {
+    // swaps the upper half of the first operand with the lower half of the second
+    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
+    return __int_as_float((int)((lane & 32) ? r[0] : r[1]));
+  }
+  return v;
+}
+
+constexpr int FWHT_ROWS_MAX = 4;
+template <int M>
+__device__ __forceinline__ void fwht_lane_stage(Vec8* x, int n_rows_here, int l, int lane, int lpr) {
+  if (M >= lpr) return;
+  const float sg = (l & M) ? -1.0f : 1.0f;
+#pragma unroll
+  for (int r = 0; r < FWHT_ROWS_MAX; ++r)
+    if (r < n_rows_here)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[r].v[i] = fmaf(x[r].v[i], sg, lane_xor<M>(x[r].v[i], lane));
+}
+
+constexpr int FWHT_ROWS = FWHT_ROWS_MAX;   // rows per lane group: their loads and butterflies are independent
 template <typename T, bool HADAMARD>
 __global__ void __launch_bounds__(256) transform_paged_fwht_kernel(
     TransformArgs t, const T* __restrict__ mla_pool, ShardPools pools, const int32_t* __restrict__ page_ids,
     int64_t n_rows, int page_tokens, int d_r, int g) {
   const int d_c = t.d_c, dl = d_c / g;
   const int lpr = d_c / 8;
-  const int rows_per_block = 256 / lpr;
+  const int rows_per_block = (256 / lpr) * FWHT_ROWS;
   const int sub = threadIdx.x / lpr, l = threadIdx.x % lpr;
-  const int64_t row = (int64_t)blockIdx.x * rows_per_block + sub;
-  if (row >= n_rows) return;
-  const int64_t pg = row / page_tokens;
-  const int slot = (int)(row % page_tokens);
-  const int64_t page = page_ids ? (int64_t)page_ids[pg] : pg;
-  const size_t in_row = ((size_t)page * page_tokens + slot) * (size_t)(d_c + d_r);
-  const size_t out_row = ((size_t)page * page_tokens + slot) * (size_t)(dl + d_r);
-
-  Vec8 x = load8(mla_pool + in_row + 8 * l);
+  // 32-bit row arithmetic (n_rows < 2^31 is checked by the caller); one
+  // division per lane group, the following rows step through the page
+  const unsigned row0 = blockIdx.x * (unsigned)rows_per_block + (unsigned)sub * FWHT_ROWS;
+  const unsigned last = (unsigned)(n_rows - 1);
+  const unsigned base_row = min(row0, last);
+  const unsigned pg0 = base_row / (unsigned)page_tokens;
+  const unsigned slot0 = base_row - pg0 * (unsigned)page_tokens;
+  // rows past the end redo the last row (same values to the same place), so
+  // every lane takes part in the lane exchanges
+  size_t in_row[FWHT_ROWS], out_row[FWHT_ROWS];
+  Vec8 x[FWHT_ROWS], kpe[FWHT_ROWS];
+  const bool has_kpe = 8 * l < d_r;          // d_r <= d_c for this kernel: one piece per lane at most
+#pragma unroll
+  for (int r = 0; r < FWHT_ROWS; ++r) {
+    unsigned pg = pg0, slot = slot0;
+    if (row0 + r <= last) {
+      slot += r;
+      if (slot >= (unsigned)page_tokens) { slot -= page_tokens; pg += 1; }   // FWHT_ROWS <= page_tokens
+    }
+    const size_t page = page_ids ? (size_t)page_ids[pg] : (size_t)pg;
+    const size_t tok = page * page_tokens + slot;
+    in_row[r] = tok * (size_t)(d_c + d_r);
+    out_row[r] = tok * (size_t)(dl + d_r);
+    x[r] = load8(mla_pool + in_row[r] + 8 * l);
+    if (has_kpe) kpe[r] = load8(mla_pool + in_row[r] + d_c + 8 * l);
+  }
   if (HADAMARD) {
     if (t.signs) {
+      float sg[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) x.v[i] *= t.signs[8 * l + i];
+      for (int i = 0; i < 8; ++i) sg[i] = t.signs[8 * l + i];
+#pragma unroll
+      for (int r = 0; r < FWHT_ROWS; ++r)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[r].v[i] *= sg[i];
     }
     // strides 1, 2, 4 inside the lane
 #pragma unroll
-    for (int h = 1; h < 8; h <<= 1)
+    for (int r = 0; r < FWHT_ROWS; ++r)
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        if (!(i & h)) {
-          const float u = x.v[i], v = x.v[i | h];
-          x.v[i] = u + v;
-          x.v[i | h] = u - v;
-        }
-    // strides 8 .. d_c/2 across lanes: partner lane l ^ m
-    for (int m = 1; m < lpr; m <<= 1) {
-      const bool upper = (l & m) != 0;
+      for (int h = 1; h < 8; h <<= 1)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float other = __shfl_xor(x.v[i], m);
-        x.v[i] = upper ? (other - x.v[i]) : (x.v[i] + other);
-      }
-    }
+        for (int i = 0; i < 8; ++i)
+          if (!(i & h)) {
+            const float u = x[r].v[i], v = x[r].v[i | h];
+            x[r].v[i] = u + v;
+            x[r].v[i | h] = u - v;
+          }
+    // strides 8 .. d_c/2 across lanes: partner lane l ^ m, new = partner + (upper ? -own : own)
+    const int lane = threadIdx.x & 63;
+    fwht_lane_stage<1>(x, FWHT_ROWS, l, lane, lpr);
+    fwht_lane_stage<2>(x, FWHT_ROWS, l, lane, lpr);
+    fwht_lane_stage<4>(x, FWHT_ROWS, l, lane, lpr);
+    fwht_lane_stage<8>(x, FWHT_ROWS, l, lane, lpr);
+    fwht_lane_stage<16>(x, FWHT_ROWS, l, lane, lpr);
+    fwht_lane_stage<32>(x, FWHT_ROWS, l, lane, lpr);
     const float sc = 1.0f / sqrtf((float)d_c);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) x.v[i] *= sc;
+    for (int r = 0; r < FWHT_ROWS; ++r)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[r].v[i] *= sc;
   }
   const int col = 8 * l;
   const int shard = col / dl;
-  store8(static_cast<T*>(pools.p[shard]) + out_row + (col - shard * dl), x);
-  // replicate the RoPE key on every slice
-  for (int c = 8 * l; c < d_r; c += 8 * lpr) {
-    const Vec8 k = load8(mla_pool + in_row + d_c + c);
-    for (int i = 0; i < g; ++i) store8(static_cast<T*>(pools.p[i]) + out_row + dl + c, k);
+#pragma unroll
+  for (int r = 0; r < FWHT_ROWS; ++r) {
+    if (row0 + r > last) break;
+    store8(static_cast<T*>(pools.p[shard]) + out_row[r] + (col - shard * dl), x[r]);
+    // replicate the RoPE key on every slice
+    if (has_kpe)
+      for (int i = 0; i < g; ++i) store8(static_cast<T*>(pools.p[i]) + out_row[r] + dl + 8 * l, kpe[r]);
   }
 }
 
@@ -177,10 +244,11 @@ static int launch_paged_t(const TransformArgs& t, const tpla_shape_t& sh, const 
   const int64_t n_rows = n_pages * sh.page_tokens;
   const int lpr = sh.d_c / 8;
   const bool pow2 = (sh.d_c & (sh.d_c - 1)) == 0;
-  const bool fast = pow2 && lpr >= 1 && lpr <= 64 && (t.mode == TPLA_U_HADAMARD || t.mode == TPLA_U_IDENTITY);
+  const bool fast = pow2 && lpr >= 1 && lpr <= 64 && sh.d_r <= sh.d_c && sh.page_tokens >= FWHT_ROWS &&
+                    (t.mode == TPLA_U_HADAMARD || t.mode == TPLA_U_IDENTITY);
   const T* in = static_cast<const T*>(mla_pool);
   if (fast) {
-    const int rows_per_block = 256 / lpr;
+    const int rows_per_block = (256 / lpr) * FWHT_ROWS;
     const dim3 grid((unsigned)((n_rows + rows_per_block - 1) / rows_per_block));
     if (t.mode == TPLA_U_HADAMARD)
       hipLaunchKernelGGL((transform_paged_fwht_kernel<T, true>), grid, dim3(256), 0, st, t, in, pools,
