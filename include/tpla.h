@@ -120,6 +120,22 @@ int tpla_write_mla_cache(const tpla_shape_t* shape, const void* c_raw, const voi
                          void* mla_pool, void* stream);
 
 /*
+ * Decode-token cache append with the RMSNorm taken per slice (Sec. 4.1,
+ * RMSNorm slicing condition; alpha = 2 for a Hadamard basis and g = 2,
+ * Sec. 4.3.1): device i only holds slice x_i = c_t[b, i d_c/g : (i+1) d_c/g]
+ * of the new token's latent (U basis) and replaces the global mean square by
+ * alpha[i] * |x_i|^2 / d_c:
+ *     row slots[b] of shard_pools[i] = [ x_i / sqrt(alpha[i] |x_i|^2 / d_c + rms_eps)  ||  k_pe[b] ]
+ * c_t [B, d_c], k_pe [B, d_r] in shape->dtype; alpha: HOST array of g floats
+ * or NULL for all equal to g (balanced slices); slots int32 [B], row index
+ * page * page_tokens + offset, negative = skip; shard_pools: HOST array of g
+ * device pointers, each [P, page_tokens, d_c/g + d_r].
+ */
+int tpla_append_token_sliced(const tpla_shape_t* shape, const void* c_t, const void* k_pe,
+                             const float* alpha, float rms_eps, const int32_t* slots,
+                             void* const* shard_pools, void* stream);
+
+/*
  * Absorbed query (Sec. 3.3) cut into slices (Sec. 4) with the factor of the
  * softmax slicing condition folded in (Sec. 4.2):
  *     q_lat[i, b, h, :] = mu[i] * (q_nope[b, h, :] @ W_UK_t[h])[i d_c/g : (i+1) d_c/g]

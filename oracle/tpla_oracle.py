@@ -123,6 +123,30 @@ def mla_cache_rows(c_raw, k_pe, eps):
     return np.concatenate([rms_norm_unit(c_raw, eps), np.asarray(k_pe, dtype=F64)], axis=-1)
 
 
+def sliced_rms_rows(c_t, k_pe, g, alpha, eps):
+    """Cache rows of a decode token when every device normalises its own
+    latent slice (Sec. 4.1, RMSNorm slicing condition): with x_i the i-th of g
+    contiguous slices of c_t (already in the U basis), the global mean square
+    |c|^2 / d is replaced by alpha_i |x_i|^2 / d, so
+        row_i = [ x_i / sqrt(alpha_i |x_i|^2 / d + eps)  ||  k_pe ].
+    Returns a list of g arrays [..., d/g + d_r].  (The paper's last step also
+    writes this as sqrt(alpha/2) RMS(x_0); the two differ only in how eps is
+    scaled -- this oracle keeps eps unscaled, as in the line before it.)"""
+    c_t = np.asarray(c_t, dtype=F64)
+    k_pe = np.asarray(k_pe, dtype=F64)
+    d = c_t.shape[-1]
+    if d % g:
+        raise ValueError("d_c must be divisible by g")
+    alpha = np.full(g, F64(g)) if alpha is None else np.asarray(alpha, dtype=F64)
+    dl = d // g
+    rows = []
+    for i in range(g):
+        x = c_t[..., i * dl:(i + 1) * dl]
+        ms = alpha[i] * np.sum(x * x, axis=-1, keepdims=True) / F64(d) + F64(eps)
+        rows.append(np.concatenate([x / np.sqrt(ms), k_pe], axis=-1))
+    return rows
+
+
 # --------------------------------------------------------------------------
 # Softmax helpers
 # --------------------------------------------------------------------------

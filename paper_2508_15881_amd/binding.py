@@ -19,7 +19,7 @@ EXPORTS = (
     "tpla_last_error", "tpla_version", "tpla_transform_latent", "tpla_transform_latent_paged",
     "tpla_write_mla_cache", "tpla_absorb_query", "tpla_workspace_bytes", "tpla_decode_shard",
     "tpla_combine_shards", "tpla_profile_enable", "tpla_profile_collect", "tpla_workspace_bytes_all",
-    "tpla_decode_shards",
+    "tpla_decode_shards", "tpla_append_token_sliced",
 )
 
 
@@ -70,6 +70,8 @@ def load_library():
     lib.tpla_transform_latent_paged.argtypes = [shp, ctypes.c_int, vp, vp, vp, ctypes.POINTER(vp), vp, i64, vp]
     lib.tpla_write_mla_cache.restype = ctypes.c_int
     lib.tpla_write_mla_cache.argtypes = [shp, vp, vp, vp, i64, ctypes.c_float, vp, vp]
+    lib.tpla_append_token_sliced.restype = ctypes.c_int
+    lib.tpla_append_token_sliced.argtypes = [shp, vp, vp, fp, ctypes.c_float, vp, ctypes.POINTER(vp), vp]
     lib.tpla_absorb_query.restype = ctypes.c_int
     lib.tpla_absorb_query.argtypes = [shp, vp, vp, fp, vp, vp]
     lib.tpla_workspace_bytes.restype = ctypes.c_size_t
@@ -147,6 +149,20 @@ def tpla_write_mla_cache(shape, c_raw, k_pe, slot_mapping, T, rms_eps, mla_pool,
     _check(load_library().tpla_write_mla_cache(
         ctypes.byref(shape), _ptr(c_raw), _ptr(k_pe), _ptr(slot_mapping), T, rms_eps, _ptr(mla_pool),
         _stream(stream)))
+
+
+def tpla_append_token_sliced(shape, c_t, k_pe, alpha, rms_eps, slots, shard_pools, stream=None):
+    a_arr = None
+    if alpha is not None:
+        a_arr = (ctypes.c_float * max(TPLA_MAX_G, len(alpha)))(*[float(a) for a in alpha])
+    if shard_pools is None:
+        arr = None
+    else:
+        arr = (ctypes.c_void_p * max(TPLA_MAX_G, len(shard_pools)))()
+        for i, p in enumerate(shard_pools):
+            arr[i] = _ptr(p)
+    _check(load_library().tpla_append_token_sliced(
+        ctypes.byref(shape), _ptr(c_t), _ptr(k_pe), a_arr, rms_eps, _ptr(slots), arr, _stream(stream)))
 
 
 def tpla_absorb_query(shape, q_nope, W_UK_t, mu, q_lat, stream=None):

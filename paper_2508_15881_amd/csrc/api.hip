@@ -274,6 +274,32 @@ int tpla_write_mla_cache(const tpla_shape_t* shape, const void* c_raw, const voi
                                 (hipStream_t)stream);
 }
 
+int tpla_append_token_sliced(const tpla_shape_t* shape, const void* c_t, const void* k_pe,
+                             const float* alpha, float rms_eps, const int32_t* slots,
+                             void* const* shard_pools, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!c_t || !k_pe || !slots || !shard_pools) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
+  if (!(rms_eps >= 0.0f) || !isfinite(rms_eps)) return fail(TPLA_ERR_SHAPE, "rms_eps must be finite and >= 0");
+  ShardPools pools;
+  for (int i = 0; i < TPLA_MAX_G; ++i) pools.p[i] = nullptr;
+  MuFactors a;
+  for (int i = 0; i < TPLA_MAX_G; ++i) a.v[i] = (float)shape->g;
+  for (int i = 0; i < shape->g; ++i) {
+    if (!shard_pools[i]) return fail(TPLA_ERR_NULL, "shard_pools[%d] is NULL", i);
+    if (!aligned16(shard_pools[i])) return fail(TPLA_ERR_ALIGN, "shard_pools[%d] not 16-byte aligned", i);
+    pools.p[i] = shard_pools[i];
+    if (alpha) {
+      if (!(alpha[i] > 0.0f) || !isfinite(alpha[i])) return fail(TPLA_ERR_SHAPE, "alpha[%d] must be positive", i);
+      a.v[i] = alpha[i];
+    }
+  }
+  if (!aligned16(c_t) || !aligned16(k_pe) || !aligned16(slots))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  if (shape->B > 2147483647 / 2 || shape->g > 65535) return fail(TPLA_ERR_UNSUPPORTED, "grid too large");
+  return launch_append_token_sliced(*shape, c_t, k_pe, a, rms_eps, slots, pools, (hipStream_t)stream);
+}
+
 int tpla_absorb_query(const tpla_shape_t* shape, const void* q_nope, const void* W_UK_t,
                       const float* mu, void* q_lat, void* stream) {
   int rc = check_shape(shape);

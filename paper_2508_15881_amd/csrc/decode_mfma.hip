@@ -205,9 +205,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
     // all waves: tile t visible, tile t-1 no longer read.  A bare barrier:
     // __syncthreads() would add a fence that waits for the loads in flight.
     __builtin_amdgcn_s_barrier();
-#ifndef TPLA_EXP_NOLOAD
     if (t + 2 < ntiles) issue(t + 2);
-#endif
     const unsigned tile = lds_base + (unsigned)((t % NSTAGE) * TILE_BYTES);
     const int valid = t_end - (t_begin + t * TOK);
     if (valid < TOK) {
@@ -219,7 +217,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
       __syncthreads();
     }
 
-#ifndef TPLA_EXP_NOCOMPUTE
     // ---- scores: a ring of 4 K fragments ahead of the MFMAs -------------------
     f32x4 sacc[TB];
 #pragma unroll
@@ -315,19 +312,14 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
         }
       });
     }
-  #endif
-  }
+    }
 
   float l_tot = l_run + __shfl_xor(l_run, 16);
   l_tot += __shfl_xor(l_tot, 32);
   const size_t item = slot * a.H + head;
   float* pacc = a.part_acc + item * DL + 4 * q4;
-#ifndef TPLA_EXP_NOSTORE
 #pragma unroll
   for (int d = 0; d < DB; ++d) *reinterpret_cast<f32x4*>(pacc + 16 * d) = acc[d];
-#else
-  if (acc[0][0] == 1.2345f) *reinterpret_cast<f32x4*>(pacc) = acc[0];
-#endif
   if (q4 == 0) {
     a.part_ml[item * 2 + 0] = m_run;
     a.part_ml[item * 2 + 1] = l_tot;

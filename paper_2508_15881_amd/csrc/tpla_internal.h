@@ -77,6 +77,10 @@ int launch_write_mla_cache(const tpla_shape_t& sh, const void* c_raw, const void
                            const int32_t* slot_mapping, int64_t T, float rms_eps, void* mla_pool,
                            hipStream_t st);
 
+int launch_append_token_sliced(const tpla_shape_t& sh, const void* c_t, const void* k_pe,
+                               const struct MuFactors& alpha, float rms_eps, const int32_t* slots,
+                               const ShardPools& pools, hipStream_t st);
+
 struct MuFactors {
   float v[TPLA_MAX_G];
 };

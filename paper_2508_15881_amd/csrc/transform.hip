@@ -316,4 +316,43 @@ int launch_write_mla_cache(const tpla_shape_t& sh, const void* c_raw, const void
   return check_launch("write_mla_cache_kernel");
 }
 
+// ---------------------------------------------------------------------------
+// Decode-token append with per-slice RMSNorm: one wave per (sequence, slice).
+template <typename T>
+__global__ void __launch_bounds__(64) append_token_sliced_kernel(const T* __restrict__ c_t,
+                                                                 const T* __restrict__ k_pe,
+                                                                 MuFactors alpha, float rms_eps,
+                                                                 const int32_t* __restrict__ slots,
+                                                                 ShardPools pools, int d_c, int d_r, int g) {
+  const int b = blockIdx.x, i = blockIdx.y, lane = threadIdx.x;
+  const int slot = slots[b];
+  if (slot < 0) return;
+  const int dl = d_c / g;
+  const T* x = c_t + (size_t)b * d_c + (size_t)i * dl;
+  float ss = 0.f;
+  for (int k = lane; k < dl; k += 64) {
+    const float v = load_as_f32(x + k);
+    ss = fmaf(v, v, ss);
+  }
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) ss += __shfl_xor(ss, m);
+  const float scale = 1.0f / sqrtf(alpha.v[i] * ss / (float)d_c + rms_eps);
+  T* out = static_cast<T*>(pools.p[i]) + (size_t)slot * (size_t)(dl + d_r);
+  for (int k = lane; k < dl; k += 64) store_from_f32(out + k, load_as_f32(x + k) * scale);
+  for (int k = lane; k < d_r; k += 64) out[dl + k] = k_pe[(size_t)b * d_r + k];
+}
+
+int launch_append_token_sliced(const tpla_shape_t& sh, const void* c_t, const void* k_pe,
+                               const MuFactors& alpha, float rms_eps, const int32_t* slots,
+                               const ShardPools& pools, hipStream_t st) {
+  const dim3 grid((unsigned)sh.B, (unsigned)sh.g);
+  if (sh.dtype == TPLA_F32)
+    hipLaunchKernelGGL(append_token_sliced_kernel<float>, grid, dim3(64), 0, st, static_cast<const float*>(c_t),
+                       static_cast<const float*>(k_pe), alpha, rms_eps, slots, pools, sh.d_c, sh.d_r, sh.g);
+  else
+    hipLaunchKernelGGL(append_token_sliced_kernel<bf16_t>, grid, dim3(64), 0, st, static_cast<const bf16_t*>(c_t),
+                       static_cast<const bf16_t*>(k_pe), alpha, rms_eps, slots, pools, sh.d_c, sh.d_r, sh.g);
+  return check_launch("append_token_sliced_kernel");
+}
+
 }  // namespace tpla

@@ -87,6 +87,10 @@ def test_other_entry_points_argument_checks():
     assert _code(tp.tpla_transform_latent_paged, s, tp.TPLA_U_IDENTITY, None, None, A, [A, A], None, -1) == -2
     assert _code(tp.tpla_write_mla_cache, s, A, A, None, 5, 1e-6, A) == -1
     assert _code(tp.tpla_write_mla_cache, s, A, A, A, -5, 1e-6, A) == -2
+    assert _code(tp.tpla_append_token_sliced, s, A, A, None, 1e-6, None, [A, A]) == -1
+    assert _code(tp.tpla_append_token_sliced, s, A, A, [2.0, -1.0], 1e-6, A, [A, A]) == -2
+    assert _code(tp.tpla_append_token_sliced, s, A, A, None, -1.0, A, [A, A]) == -2
+    assert _code(tp.tpla_append_token_sliced, s, A, A, None, 1e-6, A, [A, A + 4]) == -3
     # empty work is accepted without a launch
     tp.tpla_transform_latent(s, tp.TPLA_U_IDENTITY, 0, None, None, A, A, 0, 1)
     tp.tpla_transform_latent_paged(s, tp.TPLA_U_IDENTITY, None, None, A, [A, A], None, 0)

@@ -317,6 +317,35 @@ def test_write_mla_cache():
             assert np.all(got[~written] == 0)
 
 
+def test_append_token_sliced():
+    _say("append_token_sliced")
+    for dtype, d_c, g, d_r in (("bf16", 512, 2, 64), ("bf16", 512, 4, 64), ("f32", 64, 2, 16)):
+        Bn, pt, P = 9, 64, 4
+        rng = np.random.default_rng(61)
+        shape = tp.TplaShape(Bn, 16, d_c, g, d_r, 8, 8, pt, tp.TPLA_F32 if dtype == "f32" else tp.TPLA_BF16, 1.0)
+        c = wl.to_storage(rng.standard_normal((Bn, d_c)) * np.exp(rng.uniform(-2, 2, size=(Bn, 1))), dtype)
+        k = wl.to_storage(rng.standard_normal((Bn, d_r)), dtype)
+        slots_np = rng.permutation(P * pt)[:Bn].astype(np.int32)
+        slots_np[3] = -1
+        dl = d_c // g
+        for alpha in (None, list(rng.uniform(1.0, 3.0, size=g))):
+            pools = [torch.zeros((P, pt, dl + d_r), dtype=pl.torch_dtype(dtype), device="cuda") for _ in range(g)]
+            tp.tpla_append_token_sliced(shape, pl.to_device(c, dtype), pl.to_device(k, dtype), alpha, 1e-6,
+                                        torch.from_numpy(slots_np).cuda(), pools)
+            torch.cuda.synchronize()
+            a64 = None if alpha is None else np.asarray(alpha, dtype=np.float32).astype(np.float64)
+            ref = orc.sliced_rms_rows(wl.as_f64(c, dtype), wl.as_f64(k, dtype), g, a64, 1e-6)
+            keep = slots_np >= 0
+            for i in range(g):
+                got = wl.as_f64(pl.from_device_bits(pools[i]), dtype).reshape(P * pt, dl + d_r)
+                assert np.array_equal(got[slots_np[keep]][:, dl:], ref[i][keep][:, dl:])       # k_pe bit-exact
+                tol = 1e-6 if dtype == "f32" else 2.0 ** -8
+                lat, r = got[slots_np[keep]][:, :dl], ref[i][keep][:, :dl]
+                assert np.all(np.abs(lat - r) <= tol * np.abs(r) + 1e-30)
+                written = np.zeros(P * pt, dtype=bool); written[slots_np[keep]] = True
+                assert np.all(got[~written] == 0)
+
+
 # ------------------------------------------------------------ absorb / combine
 @pytest.mark.parametrize("dtype,Bn,H,g", [("bf16", 5, 64, 2), ("bf16", 17, 32, 4), ("f32", 3, 4, 2)])
 def test_absorb_and_combine(dtype, Bn, H, g):

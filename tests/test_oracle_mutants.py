@@ -23,6 +23,7 @@ PIN_FUNCS = [
     pins.test_reparameterize_weights_layouts,
     pins.test_pca_closed_form_on_diagonal_covariance,
     pins.test_bf16_rounding_and_paging_helpers,
+    pins.test_sliced_rmsnorm_append,
 ]
 
 
@@ -140,7 +141,31 @@ def m_fractions_reciprocal(ev, g=2):
     return 1.0 / _orig["variance_fractions"](ev, g)
 
 
+def m_sliced_rms_local_mean(c_t, k_pe, g, alpha, eps):
+    # each slice normalised by its own mean square, without the alpha / g correction
+    return _orig["sliced_rms_rows"](c_t, k_pe, g, np.ones(g), eps)
+
+
+def m_sliced_rms_eps_scaled(c_t, k_pe, g, alpha, eps):
+    a = np.full(g, float(g)) if alpha is None else np.asarray(alpha, dtype=float)
+    d = np.asarray(c_t).shape[-1]
+    dl = d // g
+    c = np.asarray(c_t, dtype=float); k = np.asarray(k_pe, dtype=float)
+    return [np.concatenate([c[..., i * dl:(i + 1) * dl] /
+                            np.sqrt(a[i] / g * (np.sum(c[..., i * dl:(i + 1) * dl] ** 2, axis=-1, keepdims=True) / dl + eps)), k], axis=-1)
+            for i in range(g)]
+
+
+def m_sliced_rms_kpe_normalised(c_t, k_pe, g, alpha, eps):
+    rows = _orig["sliced_rms_rows"](c_t, k_pe, g, alpha, eps)
+    dl = np.asarray(c_t).shape[-1] // g
+    return [np.concatenate([r[..., :dl], r[..., dl:] * 0.5], axis=-1) for r in rows]
+
+
 MUTANTS = [
+    ("sliced_rms_rows", m_sliced_rms_local_mean),
+    ("sliced_rms_rows", m_sliced_rms_eps_scaled),
+    ("sliced_rms_rows", m_sliced_rms_kpe_normalised),
     ("sylvester_hadamard", m_hadamard_wrong_block),
     ("hadamard_U", m_hadamard_scale),
     ("hadamard_U", m_hadamard_signs_right),

@@ -97,6 +97,45 @@ def test_rmsnorm_textbook_values_and_prop1():
     assert np.allclose(row, [[3 / math.sqrt(12.5), 4 / math.sqrt(12.5), 7.0]])
 
 
+def test_sliced_rmsnorm_append():
+    gold = _golden("hadamard_worked_example.txt")
+    # Sec. 4.3.1: (100,0,0,0) H_4/2 = (50,50,50,50): both halves carry half the energy, so the
+    # sliced norm with alpha = 2 is the global one; RMS = 50, every normalised entry is 1
+    x = gold["vec_a"] @ orc.hadamard_U(4)
+    rows = orc.sliced_rms_rows(x, np.array([7.0]), 2, [2.0, 2.0], 0.0)
+    assert np.array_equal(rows[0], [1.0, 1.0, 7.0]) and np.array_equal(rows[1], [1.0, 1.0, 7.0])
+    # closed form with unequal halves: x = (3,4 | 0,5), alpha = (2, 2), eps = 0.5
+    rows = orc.sliced_rms_rows(np.array([3.0, 4.0, 0.0, 5.0]), np.zeros(0), 2, None, 0.5)
+    assert np.allclose(rows[0], np.array([3.0, 4.0]) / math.sqrt(2 * 25 / 4 + 0.5), rtol=1e-15)
+    assert np.allclose(rows[1], np.array([0.0, 5.0]) / math.sqrt(2 * 25 / 4 + 0.5), rtol=1e-15)
+    # eps is added to the estimated global mean square, not to the slice's own
+    rows = orc.sliced_rms_rows(np.array([3.0, 4.0, 0.0, 5.0]), np.zeros(0), 2, [1.5, 3.0], 0.5)
+    assert np.allclose(rows[0], np.array([3.0, 4.0]) / math.sqrt(1.5 * 25 / 4 + 0.5), rtol=1e-15)
+    assert np.allclose(rows[1], np.array([0.0, 5.0]) / math.sqrt(3.0 * 25 / 4 + 0.5), rtol=1e-15)
+    # equal-energy slices + alpha_i = g  ==  global RMSNorm (Condition 1 met exactly), any g
+    rng = np.random.default_rng(13)
+    for g in (2, 4):
+        c = rng.standard_normal((6, 32))
+        dl = 32 // g
+        e = np.sum(c[:, :dl] ** 2, axis=1, keepdims=True)
+        for i in range(1, g):
+            sl = c[:, i * dl:(i + 1) * dl]
+            sl *= np.sqrt(e / np.sum(sl ** 2, axis=1, keepdims=True))
+        rows = orc.sliced_rms_rows(c, np.zeros((6, 0)), g, None, 1e-6)
+        assert np.allclose(np.concatenate(rows, axis=1), orc.rms_norm_unit(c, 1e-6), rtol=1e-13)
+    # alpha as the reciprocal variance share (PCA reading): exact for a vector whose energy
+    # splits exactly in those shares
+    c = np.array([[2.0, 2.0, 1.0, 1.0]])            # |x_0|^2 = 8, |x_1|^2 = 2 -> shares 0.8 / 0.2
+    rows = orc.sliced_rms_rows(c, np.zeros((1, 0)), 2, [1 / 0.8, 1 / 0.2], 0.0)
+    assert np.allclose(np.concatenate(rows, axis=1), orc.rms_norm_unit(c, 0.0), rtol=1e-14)
+    # scale invariance at eps = 0, and the k_pe part is passed through untouched
+    c = rng.standard_normal((3, 8)); k = rng.standard_normal((3, 2))
+    r1 = orc.sliced_rms_rows(c, k, 2, [1.7, 2.4], 0.0); r2 = orc.sliced_rms_rows(5 * c, k, 2, [1.7, 2.4], 0.0)
+    assert np.allclose(r1[0], r2[0], rtol=1e-14) and np.array_equal(r1[1][:, 4:], k)
+    with pytest.raises(ValueError):
+        orc.sliced_rms_rows(np.zeros(6), np.zeros(0), 4, None, 0.0)
+
+
 # ---------------------------------------------------------------- softmax
 def test_shard_attention_against_library_softmax():
     rng = np.random.default_rng(2)
