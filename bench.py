@@ -195,6 +195,14 @@ def main():
     us_decode = timed(lambda: step.decode(0, q_pe, pools[0], bt, lens))
     us_decode_all = timed(lambda: step.decode_all(q_pe, pools, bt, lens))
     us_combine = timed(lambda: step.combine(W_UV_t))
+    us_wo = float("nan")
+    if not args.skip_extras:
+        # block output o W_O (after the timed step's last stage; weight-streaming GEMM)
+        W_O = pl.to_device(wl.draw_output_weight(w), w.dtype)
+        wo_ws_b = tp.tpla_output_projection_workspace_bytes(shape, w.d_model)
+        wo_ws = torch.empty(max(wo_ws_b, 16), dtype=torch.uint8, device=dev)
+        wo_out = torch.empty((w.B, w.d_model), dtype=torch.float32, device=dev)
+        us_wo = timed(lambda: tp.tpla_output_projection(shape, step.o, W_O, w.d_model, wo_ws, wo_ws_b, wo_out))
 
     # MLA under head-split tensor parallelism, one device's share: the same H heads
     # over the unsliced 576-wide cache (the MLA pool is exactly the g = 1 layout).
@@ -229,6 +237,7 @@ def main():
         "pct_hbm_roofline_step": 100.0 * value / HBM_PEAK_GBS,
         "stages_us": {"absorb": us_absorb, "decode_shards(all slices, split+merge)": us_decode_all,
                       "decode_shard(one slice, split+merge)": us_decode, "combine": us_combine,
+                      "output_projection(W_O, not in the step)": us_wo,
                       "one_device_share": us_absorb / w.g + us_decode + us_combine},
         "transform": {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "kernel": "decode split kernel, all g slices in one launch (tpla_decode_shards)",

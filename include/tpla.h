@@ -208,6 +208,19 @@ int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const voi
                         float* o, void* stream);
 
 /*
+ * Output projection of the attention block (Sec. 3.3: O~ = O W^O with the
+ * value up-projection kept out of W^O; Sec. 4: the quantity the devices
+ * all-reduce): out[b, :] = o[b, :, :] flattened to H d_v  @  W_O.
+ * o float [B, H, d_v] (the result of tpla_combine_shards); W_O [H d_v, D] in
+ * shape->dtype, row-major; out float [B, D].  workspace: scratch of
+ * tpla_output_projection_workspace_bytes() bytes (may be 0 -> NULL allowed).
+ * The k axis is split over workgroups and summed in a fixed order.
+ */
+size_t tpla_output_projection_workspace_bytes(const tpla_shape_t* shape, int32_t D);
+int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void* W_O, int32_t D,
+                           void* workspace, size_t workspace_bytes, float* out, void* stream);
+
+/*
  * Measurement aid for the split kernel of tpla_decode_shard (the pass over
  * the cache of Sec. 4.5's memory-bound decode).  After
  * tpla_profile_enable(n) with n > 0, each tpla_decode_shard call on this

@@ -212,6 +212,13 @@ def combine_shards(O_lat, W_UV_t):
     return o
 
 
+def output_projection(o, W_O):
+    """O~ = O W^O (Sec. 3.3): the per-head outputs o [B, H, d_v], flattened
+    head-major to [B, H d_v], times W_O [H d_v, D]."""
+    o = np.asarray(o, dtype=F64)
+    return o.reshape(o.shape[0], -1) @ np.asarray(W_O, dtype=F64)
+
+
 def tpla_decode(q_nope, q_pe, W_UK, W_UV, c_list, kpe_list, g, scale, U=None, mu=None, gamma=None):
     """Whole TPLA decode step for one layer on cached latents c_list[b]
     ([L_b, d_c], already normalised) and RoPE keys kpe_list[b] ([L_b, d_r]).

@@ -19,7 +19,8 @@ EXPORTS = (
     "tpla_last_error", "tpla_version", "tpla_transform_latent", "tpla_transform_latent_paged",
     "tpla_write_mla_cache", "tpla_absorb_query", "tpla_workspace_bytes", "tpla_decode_shard",
     "tpla_combine_shards", "tpla_profile_enable", "tpla_profile_collect", "tpla_workspace_bytes_all",
-    "tpla_decode_shards", "tpla_append_token_sliced",
+    "tpla_decode_shards", "tpla_append_token_sliced", "tpla_output_projection",
+    "tpla_output_projection_workspace_bytes",
 )
 
 
@@ -70,6 +71,10 @@ def load_library():
     lib.tpla_transform_latent_paged.argtypes = [shp, ctypes.c_int, vp, vp, vp, ctypes.POINTER(vp), vp, i64, vp]
     lib.tpla_write_mla_cache.restype = ctypes.c_int
     lib.tpla_write_mla_cache.argtypes = [shp, vp, vp, vp, i64, ctypes.c_float, vp, vp]
+    lib.tpla_output_projection_workspace_bytes.restype = ctypes.c_size_t
+    lib.tpla_output_projection_workspace_bytes.argtypes = [shp, i32]
+    lib.tpla_output_projection.restype = ctypes.c_int
+    lib.tpla_output_projection.argtypes = [shp, vp, vp, i32, vp, ctypes.c_size_t, vp, vp]
     lib.tpla_append_token_sliced.restype = ctypes.c_int
     lib.tpla_append_token_sliced.argtypes = [shp, vp, vp, fp, ctypes.c_float, vp, ctypes.POINTER(vp), vp]
     lib.tpla_absorb_query.restype = ctypes.c_int
@@ -205,6 +210,15 @@ def tpla_decode_shards(shape, q_lat, q_pe, shard_pools, block_table, max_pages_p
 def tpla_combine_shards(shape, o_lat, W_UV_t, o, stream=None):
     _check(load_library().tpla_combine_shards(
         ctypes.byref(shape), _ptr(o_lat), _ptr(W_UV_t), _ptr(o), _stream(stream)))
+
+
+def tpla_output_projection_workspace_bytes(shape, D):
+    return int(load_library().tpla_output_projection_workspace_bytes(ctypes.byref(shape), D))
+
+
+def tpla_output_projection(shape, o, W_O, D, workspace, workspace_bytes, out, stream=None):
+    _check(load_library().tpla_output_projection(
+        ctypes.byref(shape), _ptr(o), _ptr(W_O), D, _ptr(workspace), workspace_bytes, _ptr(out), _stream(stream)))
 
 
 def tpla_profile_enable(max_records):

@@ -220,4 +220,176 @@ int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const
   return check_launch("combine_shards_mfma_kernel");
 }
 
+// ---------------------------------------------------------------------------
+// Output projection  out[b, n] = sum_k x[b, k] W[k, n]  (x = the combined
+// per-head outputs flattened to [B, H d_v], W = W_O [H d_v, D]; Sec. 3.3: the
+// value up-projection is not merged into W_O, so this runs after the combine).
+// A weight-streaming skinny GEMM: grid (D / 64, KSPLIT); a workgroup owns 64
+// output columns and one contiguous k-range, walks it in chunks of OP_ROWS
+// rows double-buffered in LDS (next chunk in registers while the current one
+// feeds the MFMAs), and writes a float partial tile; a second kernel sums the
+// KSPLIT partials in order.  Inside a chunk wave w owns rows 64w..64w+63.
+constexpr int OP_COLS = 128;
+constexpr int OP_ROWS = 128;
+__global__ void __launch_bounds__(256) output_projection_mfma_kernel(const float* __restrict__ x,
+                                                                     const bf16_t* __restrict__ W,
+                                                                     float* __restrict__ part, int B, int K,
+                                                                     int N, int k_per_split) {
+  extern __shared__ u32x4 slab4[];                 // 2 buffers of OP_ROWS x OP_COLS bf16
+  constexpr int PPR = OP_COLS / 8;                 // 16 pieces per row (256 bytes: all banks)
+  constexpr int PIECES = OP_ROWS * PPR;            // 2048 per chunk
+  constexpr int PT = PIECES / 256;                 // 8 per thread
+  constexpr int WK = OP_ROWS / 4;                  // 32 rows = one k-step per wave and chunk
+  constexpr int NCB = OP_COLS / 16;                // 8 column blocks, all owned by every wave
+  static_assert(WK == 32, "one MFMA k-step per wave and chunk");
+  const int c0 = blockIdx.x * OP_COLS, kz = blockIdx.y;
+  const int k_begin = kz * k_per_split;
+  const int n_chunks = k_per_split / OP_ROWS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j16 = lane & 15, q4 = lane >> 4;
+  const int n_mb = (B + 15) / 16;
+  for (int mb0 = 0; mb0 < n_mb; mb0 += 2) {
+    f32x4 acc[2][NCB];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) acc[m][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u32x4 wreg[PT];
+    float4 xa[2][2];
+    auto fetch = [&](int t) {
+      const bf16_t* Wc = W + (size_t)(k_begin + t * OP_ROWS) * N + c0;
+#pragma unroll
+      for (int j = 0; j < PT; ++j) {
+        const int p = tid + j * 256, r = p / PPR, pc = p % PPR;
+        wreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Wc + (size_t)r * N + 8 * pc));
+      }
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+        const int b = min(16 * (mb0 + m) + j16, B - 1);
+        const float* src = x + (size_t)b * K + k_begin + t * OP_ROWS + WK * wave + 8 * q4;
+        xa[m][0] = *reinterpret_cast<const float4*>(src);
+        xa[m][1] = *reinterpret_cast<const float4*>(src + 4);
+      }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+      for (int j = 0; j < PT; ++j) {
+        const int p = tid + j * 256, r = p / PPR, pc = p % PPR;
+        slab4[buf * PIECES + r * PPR + (pc ^ wswz(r))] = wreg[j];
+      }
+    };
+    __syncthreads();                 // the previous pass is done with LDS
+    fetch(0);
+    for (int t = 0; t < n_chunks; ++t) {
+      stage(t & 1);
+      bf16x8 ah[2], al[2];
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+        const float xs[8] = {xa[m][0].x, xa[m][0].y, xa[m][0].z, xa[m][0].w,
+                             xa[m][1].x, xa[m][1].y, xa[m][1].z, xa[m][1].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const bf16_t hi16 = (bf16_t)xs[e];
+          ah[m][e] = hi16;
+          al[m][e] = (bf16_t)(xs[e] - (float)hi16);
+        }
+      }
+      __syncthreads();               // chunk t visible; nobody still reads the buffer chunk t+1 will use
+      if (t + 1 < n_chunks) fetch(t + 1);
+      const char* slab = reinterpret_cast<const char*>(slab4 + (t & 1) * PIECES);
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const bf16x8 bf = read_b_frag<PPR>(slab, WK * wave, cb, j16, q4);
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+          acc[m][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[m], bf, acc[m][cb], 0, 0, 0);
+          acc[m][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[m], bf, acc[m][cb], 0, 0, 0);
+        }
+      }
+    }
+    // sum the four waves' tiles through LDS; wave w finishes column blocks 2w, 2w+1
+    __syncthreads();
+    f32x4* red = reinterpret_cast<f32x4*>(slab4);    // [wave][m][cb][lane]
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) red[((wave * 2 + m) * NCB + cb) * 64 + lane] = acc[m][cb];
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2) {
+        const int cb = 2 * wave + c2;
+        f32x4 tsum = red[((0 * 2 + m) * NCB + cb) * 64 + lane];
+#pragma unroll
+        for (int w2 = 1; w2 < 4; ++w2) tsum += red[((w2 * 2 + m) * NCB + cb) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int bb = 16 * (mb0 + m) + 4 * q4 + i;
+          if (bb < B) part[((size_t)kz * B + bb) * N + c0 + 16 * cb + j16] = tsum[i];
+        }
+      }
+  }
+}
+
+__global__ void __launch_bounds__(256) output_projection_reduce_kernel(const float* __restrict__ part,
+                                                                       float* __restrict__ out, size_t n,
+                                                                       int ksplit) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float v = part[i];
+  for (int z = 1; z < ksplit; ++z) v += part[(size_t)z * n + i];
+  out[i] = v;
+}
+
+// Any storage type and width: one thread per output element.
+template <typename T>
+__global__ void __launch_bounds__(256) output_projection_simple_kernel(const float* __restrict__ x,
+                                                                       const T* __restrict__ W,
+                                                                       float* __restrict__ out, int K, int N) {
+  const int n = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
+  if (n >= N) return;
+  float v = 0.f;
+  for (int k = 0; k < K; ++k) v = fmaf(x[(size_t)b * K + k], load_as_f32(W + (size_t)k * N + n), v);
+  out[(size_t)b * N + n] = v;
+}
+
+// k-range split of the matrix-core path (0 = that path does not apply).
+int output_projection_ksplit(const tpla_shape_t& sh, int D) {
+  const long long K = (long long)sh.H * sh.d_v;
+  if (sh.dtype != TPLA_BF16 || D % OP_COLS != 0 || K % OP_ROWS != 0 || K > 2147483647LL) return 0;
+  const int slabs = D / OP_COLS;
+  int ks = (2 * device_cu_count() + slabs - 1) / slabs;      // about two workgroups per compute unit
+  const int chunks = (int)(K / OP_ROWS);
+  if (ks > chunks) ks = chunks;
+  if (ks < 1) ks = 1;
+  while (chunks % ks) --ks;                                   // equal k-ranges, whole chunks
+  return ks;
+}
+
+int launch_output_projection(const tpla_shape_t& sh, const float* x, const void* W_O, int D, float* part,
+                             float* out, hipStream_t st) {
+  const int K = sh.H * sh.d_v;
+  const int ks = output_projection_ksplit(sh, D);
+  if (ks == 0) {
+    const dim3 grid((unsigned)((D + 255) / 256), (unsigned)sh.B);
+    if (sh.dtype == TPLA_F32)
+      hipLaunchKernelGGL(output_projection_simple_kernel<float>, grid, dim3(256), 0, st, x,
+                         static_cast<const float*>(W_O), out, K, D);
+    else
+      hipLaunchKernelGGL(output_projection_simple_kernel<bf16_t>, grid, dim3(256), 0, st, x,
+                         static_cast<const bf16_t*>(W_O), out, K, D);
+    return check_launch("output_projection_simple_kernel");
+  }
+  const size_t smem = 2u * OP_ROWS * OP_COLS * 2;
+  float* dst = ks == 1 ? out : part;
+  hipLaunchKernelGGL(output_projection_mfma_kernel, dim3((unsigned)(D / OP_COLS), (unsigned)ks), dim3(256), smem,
+                     st, x, static_cast<const bf16_t*>(W_O), dst, sh.B, K, D, K / ks);
+  int rc = check_launch("output_projection_mfma_kernel");
+  if (rc || ks == 1) return rc;
+  const size_t n = (size_t)sh.B * D;
+  hipLaunchKernelGGL(output_projection_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
+                     out, n, ks);
+  return check_launch("output_projection_reduce_kernel");
+}
+
 }  // namespace tpla

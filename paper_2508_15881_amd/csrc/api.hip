@@ -371,6 +371,29 @@ int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const voi
   return launch_combine_shards(*shape, o_lat, W_UV_t, o, (hipStream_t)stream);
 }
 
+size_t tpla_output_projection_workspace_bytes(const tpla_shape_t* shape, int32_t D) {
+  if (check_shape(shape) != TPLA_OK || D < 1) return 0;
+  const int ks = output_projection_ksplit(*shape, D);
+  return ks > 1 ? (size_t)ks * shape->B * D * sizeof(float) : 0;
+}
+
+int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void* W_O, int32_t D,
+                           void* workspace, size_t workspace_bytes, float* out, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!o || !W_O || !out) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
+  if (D < 1) return fail(TPLA_ERR_SHAPE, "D=%d", D);
+  if ((long long)shape->H * shape->d_v > 2147483647LL || (long long)shape->B * D > 2147483647LL)
+    return fail(TPLA_ERR_UNSUPPORTED, "H*d_v or B*D above 2^31-1");
+  if (!aligned16(o) || !aligned16(W_O) || !aligned16(out) || !aligned16(workspace))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  const size_t need = tpla_output_projection_workspace_bytes(shape, D);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+  if ((D + 255) / 256 > 2147483647 / 2 || shape->B > 65535) return fail(TPLA_ERR_UNSUPPORTED, "grid too large");
+  return launch_output_projection(*shape, o, W_O, D, static_cast<float*>(workspace), out, (hipStream_t)stream);
+}
+
 int tpla_profile_enable(int32_t max_records) {
   if (max_records < 0 || max_records > (1 << 20)) return fail(TPLA_ERR_SHAPE, "max_records=%d", max_records);
   if (g_prof.ev) {

@@ -81,6 +81,11 @@ int launch_append_token_sliced(const tpla_shape_t& sh, const void* c_t, const vo
                                const struct MuFactors& alpha, float rms_eps, const int32_t* slots,
                                const ShardPools& pools, hipStream_t st);
 
+// Output projection (after the combine): out = x @ W_O.
+int output_projection_ksplit(const tpla_shape_t& sh, int D);
+int launch_output_projection(const tpla_shape_t& sh, const float* x, const void* W_O, int D, float* part,
+                             float* out, hipStream_t st);
+
 struct MuFactors {
   float v[TPLA_MAX_G];
 };

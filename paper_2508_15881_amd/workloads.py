@@ -43,6 +43,7 @@ class Workload:
     weight_std: float = 0.02
     unit_variance_rows: bool = False   # tiny config: every tensor / sqrt(last dim)
     rms_prefill: bool = False      # cache written through the RMSNorm cache-write call
+    d_model: int = 7168            # width of the block output (DeepSeek-V3 / Kimi-K2 hidden size)
 
     @property
     def dl(self):
@@ -142,6 +143,13 @@ def draw_model_side(w):
         "heavy": heavy, "signs": signs, "seq_lens": lens.astype(np.int32),
         "block_table": block_table, "n_pool_pages": max(1, n_pool), "max_pages": max_pages,
     }
+
+
+def draw_output_weight(w):
+    """W_O [H d_v, d_model] for the output-projection stage (own stream: 500)."""
+    r = _rng(w, 500)
+    W = r.standard_normal((w.H * w.d_v, w.d_model), dtype=np.float32) * np.float32(w.weight_std)
+    return to_storage(W, w.dtype)
 
 
 def draw_sequence(w, b, L, heavy=None, width=None):

@@ -370,6 +370,23 @@ def test_absorb_and_combine(dtype, Bn, H, g):
     assert rel_err(o.cpu().numpy(), orc.combine_shards(o_lat_np.astype(np.float64), wl.as_f64(Wv, dtype))) <= 1e-5
 
 
+@pytest.mark.parametrize("dtype,Bn,H,d_v,D", [("bf16", 32, 64, 128, 7168), ("bf16", 5, 32, 128, 1024), ("bf16", 40, 16, 64, 320),
+                                              ("f32", 3, 4, 32, 96), ("bf16", 2, 5, 16, 100)])
+def test_output_projection(dtype, Bn, H, d_v, D):
+    _say(f"output_projection {dtype} B={Bn} H={H} d_v={d_v} D={D}")
+    rng = np.random.default_rng(71)
+    shape = tp.TplaShape(Bn, H, 64, 2, 16, 8, d_v, 64, tp.TPLA_F32 if dtype == "f32" else tp.TPLA_BF16, 1.0)
+    o_np = rng.standard_normal((Bn, H, d_v)).astype(np.float32)
+    W = wl.to_storage(rng.standard_normal((H * d_v, D)) * 0.02, dtype)
+    ws_b = tp.tpla_output_projection_workspace_bytes(shape, D)
+    ws = torch.empty(max(ws_b, 16), dtype=torch.uint8, device="cuda")
+    out = torch.full((Bn, D), float("nan"), dtype=torch.float32, device="cuda")
+    tp.tpla_output_projection(shape, torch.from_numpy(o_np).cuda(), pl.to_device(W, dtype), D, ws, ws_b, out)
+    torch.cuda.synchronize()
+    ref = orc.output_projection(o_np.astype(np.float64), wl.as_f64(W, dtype))
+    assert rel_err(out.cpu().numpy(), ref) <= 1e-5
+
+
 # ------------------------------------------------------------ whole path, bf16, model-shaped
 @pytest.mark.parametrize("name,lens", [("dsv3_4k", [300, 1100, 64]), ("kimi_32k", [257, 900]), ("ragged_g4", [1500, 70, 640])])
 def test_whole_path_bf16_scaled_configs(name, lens):

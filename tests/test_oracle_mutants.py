@@ -24,6 +24,7 @@ PIN_FUNCS = [
     pins.test_pca_closed_form_on_diagonal_covariance,
     pins.test_bf16_rounding_and_paging_helpers,
     pins.test_sliced_rmsnorm_append,
+    pins.test_output_projection_is_head_major_and_row_parallel,
 ]
 
 
@@ -162,7 +163,13 @@ def m_sliced_rms_kpe_normalised(c_t, k_pe, g, alpha, eps):
     return [np.concatenate([r[..., :dl], r[..., dl:] * 0.5], axis=-1) for r in rows]
 
 
+def m_output_projection_value_major(o, W_O):
+    o = np.asarray(o, dtype=float)
+    return o.transpose(0, 2, 1).reshape(o.shape[0], -1) @ np.asarray(W_O, dtype=float)
+
+
 MUTANTS = [
+    ("output_projection", m_output_projection_value_major),
     ("sliced_rms_rows", m_sliced_rms_local_mean),
     ("sliced_rms_rows", m_sliced_rms_eps_scaled),
     ("sliced_rms_rows", m_sliced_rms_kpe_normalised),

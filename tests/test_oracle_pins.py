@@ -303,6 +303,26 @@ def test_row_parallel_identity_for_combine():
     assert np.allclose(orc.combine_shards(O, W), ref, rtol=1e-13)
 
 
+def test_output_projection_is_head_major_and_row_parallel():
+    rng = np.random.default_rng(14)
+    o = rng.standard_normal((3, 4, 5)); W = rng.standard_normal((20, 7))
+    ref = np.zeros((3, 7))
+    for b in range(3):
+        for h in range(4):
+            for v in range(5):
+                ref[b] += o[b, h, v] * W[h * 5 + v]
+    assert np.allclose(orc.output_projection(o, W), ref, rtol=1e-13)
+    # row-parallel over head groups (Sec. 4.2): X A = X_1 A_1 + X_2 A_2
+    parts = orc.output_projection(o[:, :2], W[:10]) + orc.output_projection(o[:, 2:], W[10:])
+    assert np.allclose(parts, ref, rtol=1e-13)
+    # absorbing W_UV into W_O (Sec. 3.3) gives the same block output
+    q_nope, q_pe, W_UK, W_UV, c, kpe = _rand_problem(rng, H=4, d_v=5, lens=(6, 3))
+    res = orc.tpla_decode(q_nope, q_pe, W_UK, W_UV, c, kpe, 1, 0.3)
+    W_VO = np.concatenate([W_UV[h] @ W[h * 5:(h + 1) * 5] for h in range(4)], axis=0)      # [H d_c, D]
+    direct = res["O_lat"][0].reshape(2, -1) @ W_VO
+    assert np.allclose(orc.output_projection(res["o"], W), direct, rtol=1e-12)
+
+
 def test_reparameterize_weights_layouts():
     rng = np.random.default_rng(10)
     W_UK = rng.standard_normal((2, 3, 4)); W_UV = rng.standard_normal((2, 4, 5))
