@@ -414,32 +414,38 @@ struct KernelInfo {
 };
 
 template <int DL, int NW>
-static int kernel_info(KernelInfo** out) {
+static KernelInfo make_kernel_info() {
   constexpr int TOK = 32, NSTAGE = 3;
-  static KernelInfo info;
-  if (!info.ready) {
-    info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE>;
-    info.fn_balanced = decode_mfma_balanced_kernel<DL, 64, NW, TOK, NSTAGE>;
-    info.smem = (size_t)NSTAGE * TOK * ((DL + 64) / 8) * 16;
-    info.threads = NW * 64;
-    // dynamic LDS above the 64 KiB default needs opting in
-    if (info.smem > 64 * 1024 &&
-        (hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)info.smem) != hipSuccess ||
-         hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn_balanced),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)info.smem) != hipSuccess)) {
-      (void)hipGetLastError();
-      return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", info.smem);
-    }
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(info.fn_balanced), info.threads,
-                                                     info.smem) != hipSuccess) {
-      (void)hipGetLastError();
-      n = 0;
-    }
-    info.blocks_per_cu = n;
-    info.ready = true;
+  KernelInfo info;
+  info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE>;
+  info.fn_balanced = decode_mfma_balanced_kernel<DL, 64, NW, TOK, NSTAGE>;
+  info.smem = (size_t)NSTAGE * TOK * ((DL + 64) / 8) * 16;
+  info.threads = NW * 64;
+  // dynamic LDS above the 64 KiB default needs opting in
+  if (info.smem > 64 * 1024 &&
+      (hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                           (int)info.smem) != hipSuccess ||
+       hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn_balanced),
+                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)info.smem) != hipSuccess)) {
+    (void)hipGetLastError();
+    info.ready = false;
+    return info;
   }
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(info.fn_balanced), info.threads,
+                                                   info.smem) != hipSuccess) {
+    (void)hipGetLastError();
+    n = 0;
+  }
+  info.blocks_per_cu = n;
+  info.ready = true;
+  return info;
+}
+
+template <int DL, int NW>
+static int kernel_info(KernelInfo** out) {
+  static KernelInfo info = make_kernel_info<DL, NW>();   // initialised once, thread-safe
+  if (!info.ready) return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", info.smem);
   *out = &info;
   return TPLA_OK;
 }

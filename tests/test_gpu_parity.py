@@ -80,6 +80,45 @@ def test_decode_shard_many_short_sequences():
     assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
 
 
+def test_decode_shard_random_batches():
+    # seeded random batches (lengths, widths, head counts, split counts) through both plans
+    rng = np.random.default_rng(2024)
+    shapes = [(DSV3, {}), (KIMI, {}), (RAGGED, {}), (wl.scaled(DSV3, H=16), {}), (wl.scaled(RAGGED, H=32), {})]
+    for case in range(12):
+        w, _ = shapes[case % len(shapes)]
+        Bn = int(rng.integers(1, 40))
+        kind = case % 3
+        if kind == 0:
+            lens = rng.integers(0, 300, size=Bn)
+        elif kind == 1:
+            lens = np.floor(np.exp(rng.uniform(0, np.log(6000), size=Bn))).astype(np.int64)
+        else:
+            lens = np.full(Bn, int(rng.integers(1, 1500)))
+        n_splits = int(rng.choice([0, 0, 1, 2, 7, 50]))
+        _say(f"random batch {case}: {w.name} H={w.H} dl={w.dl} B={Bn} tokens={int(lens.sum())} n_splits={n_splits}")
+        prob = build_shard_problem(w, lens, rng_extra=case)
+        o, lse = run_decode_shard(prob, n_splits)
+        ro, rl = oracle_decode_shard(prob)
+        nz = np.asarray(lens) > 0
+        if nz.any():
+            assert rel_err(o[nz], ro[nz]) <= TOL["bf16"]
+            assert np.max(np.abs(lse[nz] - rl[nz])) <= 1e-2
+        assert np.all(o[~nz] == 0) and np.all(np.isneginf(lse[~nz]))
+
+
+def test_profile_brackets_count_decode_launches():
+    prob = build_shard_problem(wl.scaled(DSV3, H=16), [100, 300])
+    tp.tpla_profile_enable(3)
+    for _ in range(5):
+        run_decode_shard(prob, 0)
+    ms = tp.tpla_profile_collect(8)
+    assert len(ms) == 3 and all(0.0 < m < 100.0 for m in ms)      # capped at the enabled count
+    assert tp.tpla_profile_collect(8) == []
+    tp.tpla_profile_enable(0)
+    run_decode_shard(prob, 0)
+    assert tp.tpla_profile_collect(8) == []
+
+
 def test_decode_shard_paging_is_bit_invariant():
     lens = [700, 65, 1, 2048]
     _say("decode_shard paging invariance")
