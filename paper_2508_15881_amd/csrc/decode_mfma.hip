@@ -1,7 +1,9 @@
 // bf16 shard decode on the matrix cores (gfx950).
 //
-// One workgroup = one (sequence, split).  It walks its pages in tiles of TOK
-// tokens.  A tile (TOK rows of d_c/g + d_r bf16, contiguous inside a page)
+// A workgroup processes work items: page ranges of one sequence of one latent
+// slice, either a static chunk (decode_mfma_kernel) or whatever falls into
+// its equal share of all pages (decode_mfma_balanced_kernel).  It walks an
+// item's pages in tiles of TOK tokens.  A tile (TOK rows of d_c/g + d_r bf16, contiguous inside a page)
 // goes straight from global memory into a ring of NSTAGE LDS buffers with
 // 128-bit direct-to-LDS loads, two tiles ahead of the one being consumed, and
 // is shared there by all heads.  Wave w owns heads [16w, 16w+16):
