@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--workload", default="dsv3_32k")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
+                    help="override an integer field of the workload, e.g. --set H=128 --set B=16")
     ap.add_argument("--skip-extras", action="store_true",
                     help="only the timed steps: no one-slice loop, stage timings or MLA reference "
                          "(keeps every launch of the decode kernel in a profile identical)")
@@ -102,6 +104,9 @@ def main():
     tp.load_library()           # fails loudly when the HIP library is not built
     dev = "cuda"
     w = wl.CONFIGS[args.workload]
+    if args.set:
+        w = wl.scaled(w, name=w.name + "(" + ",".join(args.set) + ")",
+                      **{k: int(v) for k, v in (kv.split("=") for kv in args.set)})
     shape = pl.make_shape(w)
     model = wl.draw_model_side(w)
     lens_np = model["seq_lens"]
