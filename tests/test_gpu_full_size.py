@@ -91,4 +91,4 @@ def test_full_size_ragged_g4():
     w = wl.CONFIGS["ragged_g4"]
     lens = wl.draw_model_side(w)["seq_lens"]
     order = np.argsort(lens)
-    _run_config("ragged_g4", [int(order[0]), int(order[len(order) // 2])])
+    _run_config("ragged_g4", [int(order[0]), int(order[len(order) // 2]), int(order[-1])])

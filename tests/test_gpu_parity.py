@@ -119,6 +119,23 @@ def test_profile_brackets_count_decode_launches():
     assert tp.tpla_profile_collect(8) == []
 
 
+def test_decode_shard_other_page_sizes_and_one_long_sequence():
+    # 16-token pages (generic kernel), bf16 and float
+    for dtype in ("bf16", "f32"):
+        w = wl.Workload("p16", B=2, H=8, d_c=256, g=2, d_r=64, d_n=16, d_v=16, dtype=dtype, page_tokens=16, seed=12)
+        _say(f"decode_shard page_tokens=16 {dtype}")
+        prob = build_shard_problem(w, [333, 16])
+        o, lse = run_decode_shard(prob, 0)
+        ro, rl = oracle_decode_shard(prob)
+        assert rel_err(o, ro) <= TOL[dtype] and np.max(np.abs(lse - rl)) <= TOL[dtype] * 10
+    # one sequence of 100k tokens: every workgroup holds a piece of it, the merge sums hundreds of partials
+    _say("decode_shard single sequence of 100000 tokens")
+    prob = build_shard_problem(wl.scaled(DSV3, H=16), [100000])
+    o, lse = run_decode_shard(prob, 0)
+    ro, rl = oracle_decode_shard(prob)
+    assert rel_err(o, ro) <= TOL["bf16"] and np.max(np.abs(lse - rl)) <= 1e-2
+
+
 def test_decode_shard_paging_is_bit_invariant():
     lens = [700, 65, 1, 2048]
     _say("decode_shard paging invariance")
