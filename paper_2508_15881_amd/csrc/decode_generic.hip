@@ -172,7 +172,19 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
   if ((dl & 3) == 0) {
     for (int c = threadIdx.x * 4; c < dl; c += blockDim.x * 4) {
       float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
-      for (int s = 0; s < cnt; ++s) {
+      int s = 0;
+      for (; s + 4 <= cnt; s += 4) {          // four partial rows in flight; summed in slot order
+        float4 p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          p[u] = *reinterpret_cast<const float4*>(a.part_acc + ((size_t)slot_of[s + u] * a.H + h) * dl + c);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float w = wgt[s + u];
+          v0 = fmaf(p[u].x, w, v0); v1 = fmaf(p[u].y, w, v1); v2 = fmaf(p[u].z, w, v2); v3 = fmaf(p[u].w, w, v3);
+        }
+      }
+      for (; s < cnt; ++s) {
         const float4 p = *reinterpret_cast<const float4*>(a.part_acc + ((size_t)slot_of[s] * a.H + h) * dl + c);
         const float w = wgt[s];
         v0 = fmaf(p.x, w, v0); v1 = fmaf(p.y, w, v1); v2 = fmaf(p.z, w, v2); v3 = fmaf(p.w, w, v3);
