@@ -134,7 +134,7 @@ def main():
     used = torch.from_numpy(used_np).to(dev)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_tr = []
-    for _ in range(3):
+    for _ in range(6):
         ev0.record()
         tp.tpla_transform_latent_paged(shape, code, signs, None, mla_pool, pools, used, len(used_np))
         ev1.record()

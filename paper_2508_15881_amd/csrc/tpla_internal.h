@@ -73,6 +73,11 @@ struct ShardPools {
 int launch_transform_paged(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
                            const ShardPools& pools, const int32_t* page_ids, int64_t n_pages,
                            hipStream_t st);
+// Matrix-core Hadamard pass (bf16, d_c 256 / 512): see transform_mfma.hip.
+bool transform_paged_mfma_supported(const TransformArgs& t, const tpla_shape_t& sh, int64_t n_pages);
+int launch_transform_paged_mfma(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
+                                const ShardPools& pools, const int32_t* page_ids, int64_t n_pages,
+                                hipStream_t st);
 int launch_write_mla_cache(const tpla_shape_t& sh, const void* c_raw, const void* k_pe,
                            const int32_t* slot_mapping, int64_t T, float rms_eps, void* mla_pool,
                            hipStream_t st);

@@ -1,9 +1,11 @@
 // Orthogonal reparameterisation kernels (Sec. 4.1 / 4.3 of the paper) and the
 // MLA-style cache write.
 //   * transform_axis_kernel: shape-agnostic, one workgroup per vector, LDS.
-//   * transform_paged_fwht_kernel: the streaming cache pass -- one row per
-//     group of d_c/8 lanes, 8 elements per lane, Walsh-Hadamard butterflies in
-//     registers (strides 1,2,4) and across lanes (strides 8..d_c/2).
+//   * transform_paged_fwht_kernel: streaming cache pass on the vector ALU -- one
+//     row per group of d_c/8 lanes, 8 elements per lane, Walsh-Hadamard
+//     butterflies in registers (strides 1,2,4) and across lanes (strides
+//     8..d_c/2).  Runs the identity (slicing-only) pass, float storage and the
+//     widths the matrix-core pass (transform_mfma.hip) does not take.
 //   * transform_paged_generic_kernel: identity / dense U / wide rows.
 #include "tpla_internal.h"
 
@@ -267,6 +269,8 @@ static int launch_paged_t(const TransformArgs& t, const tpla_shape_t& sh, const 
 int launch_transform_paged(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
                            const ShardPools& pools, const int32_t* page_ids, int64_t n_pages,
                            hipStream_t st) {
+  if (transform_paged_mfma_supported(t, sh, n_pages))
+    return launch_transform_paged_mfma(t, sh, mla_pool, pools, page_ids, n_pages, st);
   if (sh.dtype == TPLA_F32) return launch_paged_t<float>(t, sh, mla_pool, pools, page_ids, n_pages, st);
   return launch_paged_t<bf16_t>(t, sh, mla_pool, pools, page_ids, n_pages, st);
 }

@@ -1,0 +1,214 @@
+// Streaming Hadamard pass over MLA pages on the matrix cores (Sec. 4.3: U =
+// diag(s) H / sqrt(d_c), natural order; Sec. 4.1: column slices of c U go to
+// the g shard pools, the RoPE key to every one of them).
+//
+// H_{d_c} = H_NA (x) H_64 with element index e = 64 a + b, NA = d_c / 64:
+//   * H_64 over b is a contraction of the row's 64-element sub-rows with a
+//     constant +-1 matrix: bf16 inputs are exact operands, the sums are float.
+//     A sub-row is 128 contiguous bytes, and the 16 bytes a lane loads straight
+//     from global memory are already its share of the MFMA A operand.
+//   * H_NA over a runs on the accumulators.  A tile's 16 sub-rows are chosen
+//     (4 rows x 4 values of a) so that one lane ends up with all NA values of a
+//     for its row and columns: these butterflies stay inside the lane.
+//   * The columns of the constant operand are ordered so that a lane owns 4
+//     adjacent output columns: 8-byte stores, 128 contiguous bytes per 16 lanes.
+// The cross-lane butterflies of the plain-ALU kernel (about 150 instructions
+// per row) become 4 MFMAs per row.
+#include "tpla_internal.h"
+
+namespace tpla {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned opaque(unsigned x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
+template <int NA>
+struct FwhtGroup {          // one group of 4 rows as loaded: NA/4 tiles x 2 k-steps, and the RoPE keys
+  u32x4 a[NA / 4][2];
+  u32x4 kpe;
+};
+
+// One wave per `rows_per_wave` (a multiple of 4 that divides the page) consecutive
+// rows of a page, 4 rows at a time, the next 4 loaded while these are transformed.
+template <int NA>
+__global__ void __launch_bounds__(256, 4) transform_paged_fwht_mfma_kernel(
+    const bf16_t* __restrict__ mla_pool, ShardPools pools, const int32_t* __restrict__ page_ids,
+    const float* __restrict__ signs, int n_pages, int page_tokens, int rows_per_wave, int d_r, int g) {
+  constexpr int NT = NA / 4, D_C = 64 * NA;
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int waves_per_page = page_tokens / rows_per_wave;
+  const int pg = wave / waves_per_page;
+  if (pg >= n_pages) return;                       // whole waves leave; the kernel has no barrier
+  const int row_first = (wave - pg * waves_per_page) * rows_per_wave;
+  const size_t page = page_ids ? (size_t)page_ids[pg] : (size_t)pg;
+  const int dl = D_C / g;
+  const int lo = lane & 15, hi = lane >> 4;
+
+  // constant operand: lane (column group lo, k group hi) holds, for k-step s and
+  // column tile nt, H_64[k][c] for k = 32 s + 8 hi + j, c = 4 lo + nt.  Bit 5 of
+  // k meets bit 3 of lo only, so k-step 1 is k-step 0 with the sign of whole
+  // columns flipped: one set of registers and a per-lane sign mask.
+  u32x4 hb[4];
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt) {
+    const unsigned c = 4u * lo + nt;
+    const unsigned par_hi = __popc((8u * hi) & c);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const unsigned p0 = (par_hi + __popc((2u * jj) & c)) & 1u;
+      const unsigned p1 = (par_hi + __popc((2u * jj + 1u) & c)) & 1u;
+      hb[nt][jj] = (0x3F80u | (p0 << 15)) | ((0x3F80u | (p1 << 15)) << 16);
+    }
+  }
+  const unsigned step1_flip = (lo & 8) ? 0x80008000u : 0u;
+
+  // as holder of the data operand: lane (sub-row lo of the tile, k group hi);
+  // tile t, sub-row lo = 4 q + i  ->  row q of the group, a = 4 t + i
+  const int a_row = lo >> 2, a_sub = lo & 3;
+  // sign diagonal, packed: bit 15 - jj of flip[t][s] is set when element 2 jj of the
+  // lane's 8 is negated, bit 31 - jj for element 2 jj + 1
+  unsigned flip[NT][2];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      unsigned m = 0u;
+      if (signs) {
+        const float* sp = signs + 64 * (4 * t + a_sub) + 32 * s + 8 * hi;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+          m |= ((__float_as_uint(sp[2 * jj]) >> 31) << (15 - jj)) | ((__float_as_uint(sp[2 * jj + 1]) >> 31) << (31 - jj));
+      }
+      flip[t][s] = m;
+    }
+
+  const int in_pitch = D_C + d_r, out_pitch = dl + d_r;
+  const size_t tok0 = page * (size_t)page_tokens + row_first;
+  const bf16_t* in_lane = mla_pool + (tok0 + a_row) * in_pitch + 64 * a_sub + 8 * hi;
+  const int kpe_lanes = d_r >> 3;                   // lanes per row of RoPE key, 4 rows per group
+  const bool has_kpe = lane < 4 * kpe_lanes;
+  const int kpe_row = has_kpe ? lane / kpe_lanes : 0, kpe_piece = has_kpe ? lane - kpe_row * kpe_lanes : 0;
+  const bf16_t* kpe_lane = mla_pool + (tok0 + kpe_row) * in_pitch + D_C + 8 * kpe_piece;
+
+  auto load_group = [&](int gi, FwhtGroup<NA>& grp) {
+    const bf16_t* p = in_lane + (size_t)(4 * gi) * in_pitch;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+        grp.a[t][s] = *reinterpret_cast<const u32x4*>(p + 256 * t + 32 * s);
+    if (has_kpe)
+      grp.kpe = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kpe_lane + (size_t)(4 * gi) * in_pitch));
+  };
+
+  const float sc = 1.0f / sqrtf((float)D_C);
+  const int n_groups = rows_per_wave >> 2;
+  FwhtGroup<NA> cur, nxt;
+  load_group(0, cur);
+  for (int gi = 0; gi < n_groups; ++gi) {
+    if (gi + 1 < n_groups) load_group(gi + 1, nxt);
+
+    f32x4 acc[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) acc[t][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        // (masks are rebuilt from opaque copies: kept as loop invariants they
+        // would cost 28 more registers and a wave per SIMD)
+        const unsigned fw = opaque(flip[t][s]);
+        u32x4 ax = cur.a[t][s];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) ax[jj] ^= (fw << jj) & 0x80008000u;
+        const bf16x8 av = __builtin_bit_cast(bf16x8, ax);
+        const unsigned f1 = opaque(step1_flip);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+          const u32x4 hv = s ? (hb[nt] ^ f1) : hb[nt];
+          acc[t][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hv), acc[t][nt], 0, 0, 0);
+        }
+      }
+
+    // as holder of the result: row hi of the group, columns 4 lo + nt, a = 4 t + i
+    const size_t out_row = (tok0 + 4 * gi + hi) * (size_t)out_pitch;
+    float y[4][NA];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) y[nt][4 * t + i] = acc[t][nt][i];
+#pragma unroll
+      for (int h = 1; h < NA; h <<= 1)
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+          if (!(a & h)) {
+            const float u = y[nt][a], v = y[nt][a | h];
+            y[nt][a] = u + v;
+            y[nt][a | h] = u - v;
+          }
+    }
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+      const bf16x2 p0 = __builtin_convertvector(f32x2{y[0][a] * sc, y[1][a] * sc}, bf16x2);
+      const bf16x2 p1 = __builtin_convertvector(f32x2{y[2][a] * sc, y[3][a] * sc}, bf16x2);
+      const u32x2 out = {__builtin_bit_cast(unsigned, p0), __builtin_bit_cast(unsigned, p1)};
+      const int shard = (64 * a) / dl;
+      bf16_t* dst = static_cast<bf16_t*>(pools.p[shard]) + out_row + (64 * a - shard * dl) + 4 * lo;
+      __builtin_nontemporal_store(out, reinterpret_cast<u32x2*>(dst));
+    }
+    if (has_kpe) {
+      const size_t kr = (tok0 + 4 * gi + kpe_row) * (size_t)out_pitch + dl + 8 * kpe_piece;
+      for (int i = 0; i < g; ++i)
+        __builtin_nontemporal_store(cur.kpe, reinterpret_cast<u32x4*>(static_cast<bf16_t*>(pools.p[i]) + kr));
+    }
+    cur = nxt;
+  }
+}
+
+// Short runs of rows per wave on purpose: neighbouring waves then read and write
+// neighbouring addresses at about the same time, which is what the DRAM wants
+// (64 rows per wave: 5.1 TB/s, 8 rows: 5.7 TB/s at a million rows); the constant
+// set-up per wave is hidden behind the loads either way.
+static int fwht_rows_per_wave(int page_tokens) { return page_tokens % 8 == 0 ? 8 : 4; }
+
+bool transform_paged_mfma_supported(const TransformArgs& t, const tpla_shape_t& sh, int64_t n_pages) {
+  if (sh.dtype != TPLA_BF16 || t.mode != TPLA_U_HADAMARD || t.inverse) return false;
+  if (sh.d_c != 256 && sh.d_c != 512) return false;
+  const int dl = sh.d_c / sh.g;
+  if (dl % 64 != 0 || sh.d_r % 8 != 0 || sh.d_r > 128) return false;
+  const int pt = sh.page_tokens;
+  if (pt % 4 != 0) return false;
+  const int64_t waves = n_pages * (pt / fwht_rows_per_wave(pt));
+  return waves > 0 && waves < (int64_t)1 << 30;
+}
+
+int launch_transform_paged_mfma(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
+                                const ShardPools& pools, const int32_t* page_ids, int64_t n_pages,
+                                hipStream_t st) {
+  const int pt = sh.page_tokens;
+  const int rows_per_wave = fwht_rows_per_wave(pt);
+  const int64_t waves = n_pages * (pt / rows_per_wave);
+  const dim3 grid((unsigned)((waves + 3) / 4));
+  const bf16_t* in = static_cast<const bf16_t*>(mla_pool);
+  if (sh.d_c == 512)
+    hipLaunchKernelGGL(transform_paged_fwht_mfma_kernel<8>, grid, dim3(256), 0, st, in, pools, page_ids,
+                       t.signs, (int)n_pages, pt, rows_per_wave, sh.d_r, sh.g);
+  else
+    hipLaunchKernelGGL(transform_paged_fwht_mfma_kernel<4>, grid, dim3(256), 0, st, in, pools, page_ids,
+                       t.signs, (int)n_pages, pt, rows_per_wave, sh.d_r, sh.g);
+  return check_launch("transform_paged_fwht_mfma_kernel");
+}
+
+}  // namespace tpla

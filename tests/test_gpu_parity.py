@@ -303,10 +303,15 @@ def test_transform_latent_weights(dtype, mode):
     assert rel_err(wl.as_f64(pl.from_device_bits(back), dtype), wl.as_f64(W_UK, dtype)) <= (1e-5 if dtype == "f32" else 2e-2)
 
 
-@pytest.mark.parametrize("dtype,d_c,g", [("bf16", 512, 2), ("bf16", 512, 4), ("f32", 64, 2), ("bf16", 96, 2)])
-def test_transform_latent_paged(dtype, d_c, g):
-    _say(f"transform_latent_paged {dtype} d_c={d_c} g={g}")
-    d_r, pt, P = 64 if d_c == 512 else 16, 64, 7
+@pytest.mark.parametrize("dtype,d_c,g,d_r,pt", [
+    ("bf16", 512, 2, 64, 64), ("bf16", 512, 4, 64, 64), ("f32", 64, 2, 16, 64), ("bf16", 96, 2, 16, 64),
+    # matrix-core Hadamard pass: narrow slices, short / odd-sized pages, other RoPE widths, d_c = 256;
+    # then shapes it declines (d_c = 1024, pages of 6 tokens, float storage at d_c = 512)
+    ("bf16", 512, 8, 128, 16), ("bf16", 512, 1, 32, 20), ("bf16", 256, 2, 64, 128), ("bf16", 256, 4, 8, 4),
+    ("bf16", 1024, 2, 64, 16), ("bf16", 512, 2, 64, 6), ("f32", 512, 2, 64, 16)])
+def test_transform_latent_paged(dtype, d_c, g, d_r, pt):
+    _say(f"transform_latent_paged {dtype} d_c={d_c} g={g} d_r={d_r} page_tokens={pt}")
+    P = 7
     rng = np.random.default_rng(31)
     shape = tp.TplaShape(1, 16, d_c, g, d_r, 8, 8, pt, tp.TPLA_F32 if dtype == "f32" else tp.TPLA_BF16, 1.0)
     pool_np = wl.to_storage(rng.standard_normal((P, pt, d_c + d_r)), dtype)
@@ -318,6 +323,7 @@ def test_transform_latent_paged(dtype, d_c, g):
     modes = [("identity", tp.TPLA_U_IDENTITY, None)]
     if pow2:
         modes.append(("hadamard", tp.TPLA_U_HADAMARD, rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=d_c)))
+        modes.append(("hadamard", tp.TPLA_U_HADAMARD, None))       # no sign diagonal
     for name, code, signs_np in modes:
         outs = [torch.zeros((P, pt, dl + d_r), dtype=pl.torch_dtype(dtype), device="cuda") for _ in range(g)]
         signs = None if signs_np is None else torch.from_numpy(signs_np).cuda()
