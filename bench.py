@@ -209,6 +209,28 @@ def main():
         wo_out = torch.empty((w.B, w.d_model), dtype=torch.float32, device=dev)
         us_wo = timed(lambda: tp.tpla_output_projection(shape, step.o, W_O, w.d_model, wo_ws, wo_ws_b, wo_out))
 
+    # PCA calibration path (Sec. 4.3.2), not part of the step: moments of the cached latents on
+    # the GPU, eigen-solve on the host, cache turned into the dense basis on the matrix cores
+    pca = None
+    if not args.skip_extras and w.dtype == "bf16":
+        n_used = len(used_np)
+        ws_b = tp.tpla_latent_moments_workspace_bytes(shape, n_used)
+        ws_m = torch.empty(max(ws_b, 16), dtype=torch.uint8, device=dev)
+        m_sum = torch.empty(w.d_c, dtype=torch.float64, device=dev)
+        m_gram = torch.empty((w.d_c, w.d_c), dtype=torch.float64, device=dev)
+        us_mom = timed(lambda: tp.tpla_latent_moments(shape, mla_pool, used, None, n_used, ws_m, ws_b, m_sum, m_gram), reps=5)
+        tcpu = time.perf_counter()
+        U_np, eig, frac = tp.tpla_pca_basis(w.d_c, w.g, n_used * pt, m_sum.cpu().numpy(), m_gram.cpu().numpy())
+        eig_s = time.perf_counter() - tcpu
+        U_dev = torch.from_numpy(U_np).to(dev)
+        scratch_pools = [torch.empty_like(p) for p in pools]
+        us_dense = timed(lambda: tp.tpla_transform_latent_paged(shape, tp.TPLA_U_DENSE, None, U_dev, mla_pool,
+                                                                scratch_pools, used, n_used), reps=3)
+        del scratch_pools, ws_m
+        pca = {"latent_moments_us": us_mom, "eigen_solve_host_s": eig_s, "dense_transform_us": us_dense,
+               "dense_transform_TFLOPs_hi_lo": 4.0 * n_used * pt * w.d_c * w.d_c / (us_dense * 1e-6) / 1e12,
+               "variance_fractions": [float(f) for f in frac]}
+
     # MLA under head-split tensor parallelism, one device's share: the same H heads
     # over the unsliced 576-wide cache (the MLA pool is exactly the g = 1 layout).
     # Its time against one TPLA slice is this box's counterpart of the paper's ratio.
@@ -244,6 +266,7 @@ def main():
                       "decode_shard(one slice, split+merge)": us_decode, "combine": us_combine,
                       "output_projection(W_O, not in the step)": us_wo,
                       "one_device_share": us_absorb / w.g + us_decode + us_combine},
+        "pca_calibration": pca,
         "transform": {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "kernel": "decode split kernel, all g slices in one launch (tpla_decode_shards)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -221,6 +221,39 @@ int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void
                            void* workspace, size_t workspace_bytes, float* out, void* stream);
 
 /*
+ * PCA calibration, step 1 (Sec. 4.3.2: the covariance of collected latents,
+ * position features excluded): second moments of the latent part of cached
+ * rows.  mla_pool as in tpla_transform_latent_paged; page_ids int32 [n_pages]
+ * (NULL = pages 0..n_pages-1); page_fill int32 [n_pages], the number of valid
+ * tokens at the start of each listed page (NULL = every page full; the rest of
+ * a page is never read, so it may hold anything).  Writes, as DEVICE doubles,
+ * sum[d_c] = sum_r x_r and gram[d_c * d_c] = sum_r x_r^T x_r (row-major,
+ * symmetric, both triangles).  Products accumulate in float inside a split of
+ * at most 16384 rows, splits are added in double in a fixed order.
+ * workspace: tpla_latent_moments_workspace_bytes() bytes of device scratch.
+ * n_pages * page_tokens must be below 2^31.
+ */
+size_t tpla_latent_moments_workspace_bytes(const tpla_shape_t* shape, int64_t n_pages);
+int tpla_latent_moments(const tpla_shape_t* shape, const void* mla_pool, const int32_t* page_ids,
+                        const int32_t* page_fill, int64_t n_pages, void* workspace, size_t workspace_bytes,
+                        double* sum, double* gram, void* stream);
+
+/*
+ * PCA calibration, step 2 (Sec. 4.3.2), on the HOST and synchronous: all
+ * pointers are host memory.  From the moments of n_rows latents forms the
+ * covariance gram/n - mean mean^T, diagonalises it (cyclic Jacobi rotations in
+ * double) and writes U float [d_c, d_c] row-major whose COLUMN k is the
+ * eigenvector of the k-th largest eigenvalue (sign: its largest component is
+ * positive) -- the dense U of tpla_transform_latent --, eig double [d_c]
+ * descending, and frac double [g]: the share of the total variance in each
+ * contiguous slice of d_c/g components (alpha, beta of Sec. 4.3.2 for g = 2).
+ * d_c must be a multiple of g.  Returns TPLA_ERR_UNSUPPORTED if the iteration
+ * does not converge.
+ */
+int tpla_pca_basis(int32_t d_c, int32_t g, int64_t n_rows, const double* sum, const double* gram, float* U,
+                   double* eig, double* frac);
+
+/*
  * Measurement aid for the split kernel of tpla_decode_shard (the pass over
  * the cache of Sec. 4.5's memory-bound decode).  After
  * tpla_profile_enable(n) with n > 0, each tpla_decode_shard call on this

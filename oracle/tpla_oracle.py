@@ -66,6 +66,13 @@ def pca_U(F):
     return vec[:, order], lam[order]
 
 
+def latent_moments(F):
+    """First and second raw moments of calibration latents F [n, d] (Sec. 4.3.2,
+    the ingredients of the covariance): (sum_r F_r, sum_r F_r^T F_r)."""
+    F = np.asarray(F, dtype=F64)
+    return F.sum(axis=0), F.T @ F
+
+
 def variance_fractions(eigenvalues, g=2):
     """alpha, beta, ... of Sec. 4.3.2 as printed: the fraction of total
     variance captured by each contiguous slice of d/g principal components."""

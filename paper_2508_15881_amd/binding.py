@@ -20,7 +20,8 @@ EXPORTS = (
     "tpla_write_mla_cache", "tpla_absorb_query", "tpla_workspace_bytes", "tpla_decode_shard",
     "tpla_combine_shards", "tpla_profile_enable", "tpla_profile_collect", "tpla_workspace_bytes_all",
     "tpla_decode_shards", "tpla_append_token_sliced", "tpla_output_projection",
-    "tpla_output_projection_workspace_bytes",
+    "tpla_output_projection_workspace_bytes", "tpla_latent_moments_workspace_bytes", "tpla_latent_moments",
+    "tpla_pca_basis",
 )
 
 
@@ -93,6 +94,12 @@ def load_library():
     lib.tpla_profile_enable.argtypes = [i32]
     lib.tpla_profile_collect.restype = ctypes.c_int
     lib.tpla_profile_collect.argtypes = [fp, i32, ctypes.POINTER(i32)]
+    lib.tpla_latent_moments_workspace_bytes.restype = ctypes.c_size_t
+    lib.tpla_latent_moments_workspace_bytes.argtypes = [shp, i64]
+    lib.tpla_latent_moments.restype = ctypes.c_int
+    lib.tpla_latent_moments.argtypes = [shp, vp, vp, vp, i64, vp, ctypes.c_size_t, vp, vp, vp]
+    lib.tpla_pca_basis.restype = ctypes.c_int
+    lib.tpla_pca_basis.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -219,6 +226,33 @@ def tpla_output_projection_workspace_bytes(shape, D):
 def tpla_output_projection(shape, o, W_O, D, workspace, workspace_bytes, out, stream=None):
     _check(load_library().tpla_output_projection(
         ctypes.byref(shape), _ptr(o), _ptr(W_O), D, _ptr(workspace), workspace_bytes, _ptr(out), _stream(stream)))
+
+
+def tpla_latent_moments_workspace_bytes(shape, n_pages):
+    return int(load_library().tpla_latent_moments_workspace_bytes(ctypes.byref(shape), n_pages))
+
+
+def tpla_latent_moments(shape, mla_pool, page_ids, page_fill, n_pages, workspace, workspace_bytes, sum_out, gram_out,
+                        stream=None):
+    _check(load_library().tpla_latent_moments(
+        ctypes.byref(shape), _ptr(mla_pool), _ptr(page_ids), _ptr(page_fill), n_pages, _ptr(workspace),
+        workspace_bytes, _ptr(sum_out), _ptr(gram_out), _stream(stream)))
+
+
+def tpla_pca_basis(d_c, g, n_rows, sum_host, gram_host):
+    """Host call.  sum_host [d_c], gram_host [d_c, d_c]: C-contiguous float64 numpy arrays.
+    Returns (U float32 [d_c, d_c], eigenvalues float64 [d_c], fractions float64 [g])."""
+    import numpy as np
+    sum_host = np.ascontiguousarray(sum_host, dtype=np.float64)
+    gram_host = np.ascontiguousarray(gram_host, dtype=np.float64)
+    if sum_host.shape != (d_c,) or gram_host.shape != (d_c, d_c):
+        raise ValueError("sum must be [d_c] and gram [d_c, d_c]")
+    U = np.empty((d_c, d_c), dtype=np.float32)
+    eig = np.empty(d_c, dtype=np.float64)
+    frac = np.empty(g, dtype=np.float64)
+    _check(load_library().tpla_pca_basis(d_c, g, n_rows, sum_host.ctypes.data, gram_host.ctypes.data,
+                                         U.ctypes.data, eig.ctypes.data, frac.ctypes.data))
+    return U, eig, frac
 
 
 def tpla_profile_enable(max_records):

@@ -394,6 +394,36 @@ int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void
   return launch_output_projection(*shape, o, W_O, D, static_cast<float*>(workspace), out, (hipStream_t)stream);
 }
 
+size_t tpla_latent_moments_workspace_bytes(const tpla_shape_t* shape, int64_t n_pages) {
+  if (check_shape(shape) != TPLA_OK || n_pages < 1) return 0;
+  return latent_moments_workspace(*shape, n_pages);
+}
+
+int tpla_latent_moments(const tpla_shape_t* shape, const void* mla_pool, const int32_t* page_ids,
+                        const int32_t* page_fill, int64_t n_pages, void* workspace, size_t workspace_bytes,
+                        double* sum, double* gram, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!mla_pool || !sum || !gram) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
+  if (n_pages < 1) return fail(TPLA_ERR_SHAPE, "n_pages=%lld", (long long)n_pages);
+  if (n_pages * shape->page_tokens >= ((int64_t)1 << 31)) return fail(TPLA_ERR_UNSUPPORTED, "more than 2^31-1 rows");
+  if (!aligned16(mla_pool) || !aligned16(workspace) || !aligned16(sum) || !aligned16(gram))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  const size_t need = latent_moments_workspace(*shape, n_pages);
+  if (!workspace || workspace_bytes < need)
+    return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+  return launch_latent_moments(*shape, mla_pool, page_ids, page_fill, n_pages, static_cast<float*>(workspace), sum,
+                               gram, (hipStream_t)stream);
+}
+
+int tpla_pca_basis(int32_t d_c, int32_t g, int64_t n_rows, const double* sum, const double* gram, float* U,
+                   double* eig, double* frac) {
+  if (!sum || !gram || !U || !eig || !frac) return fail(TPLA_ERR_NULL, "a pointer is NULL");
+  if (d_c < 1 || d_c > 4096 || g < 1 || g > TPLA_MAX_G || d_c % g != 0 || n_rows < 1)
+    return fail(TPLA_ERR_SHAPE, "d_c=%d g=%d n_rows=%lld", d_c, g, (long long)n_rows);
+  return pca_basis_host(d_c, g, (double)n_rows, sum, gram, U, eig, frac);
+}
+
 int tpla_profile_enable(int32_t max_records) {
   if (max_records < 0 || max_records > (1 << 20)) return fail(TPLA_ERR_SHAPE, "max_records=%d", max_records);
   if (g_prof.ev) {

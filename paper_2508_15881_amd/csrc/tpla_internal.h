@@ -78,6 +78,10 @@ bool transform_paged_mfma_supported(const TransformArgs& t, const tpla_shape_t& 
 int launch_transform_paged_mfma(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
                                 const ShardPools& pools, const int32_t* page_ids, int64_t n_pages,
                                 hipStream_t st);
+bool transform_paged_dense_mfma_supported(const TransformArgs& t, const tpla_shape_t& sh, int64_t n_pages);
+int launch_transform_paged_dense_mfma(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
+                                      const ShardPools& pools, const int32_t* page_ids, int64_t n_pages,
+                                      hipStream_t st);
 int launch_write_mla_cache(const tpla_shape_t& sh, const void* c_raw, const void* k_pe,
                            const int32_t* slot_mapping, int64_t T, float rms_eps, void* mla_pool,
                            hipStream_t st);
@@ -90,6 +94,15 @@ int launch_append_token_sliced(const tpla_shape_t& sh, const void* c_t, const vo
 int output_projection_ksplit(const tpla_shape_t& sh, int D);
 int launch_output_projection(const tpla_shape_t& sh, const float* x, const void* W_O, int D, float* part,
                              float* out, hipStream_t st);
+
+// PCA calibration: see pca.hip.
+int latent_moments_splits(const tpla_shape_t& sh, int64_t n_pages);
+size_t latent_moments_workspace(const tpla_shape_t& sh, int64_t n_pages);
+int launch_latent_moments(const tpla_shape_t& sh, const void* mla_pool, const int32_t* page_ids,
+                          const int32_t* page_fill, int64_t n_pages, float* workspace, double* sum, double* gram,
+                          hipStream_t st);
+int pca_basis_host(int d, int g, double n_rows, const double* sum, const double* gram, float* U, double* eig,
+                   double* frac);
 
 struct MuFactors {
   float v[TPLA_MAX_G];

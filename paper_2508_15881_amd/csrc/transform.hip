@@ -271,6 +271,8 @@ int launch_transform_paged(const TransformArgs& t, const tpla_shape_t& sh, const
                            hipStream_t st) {
   if (transform_paged_mfma_supported(t, sh, n_pages))
     return launch_transform_paged_mfma(t, sh, mla_pool, pools, page_ids, n_pages, st);
+  if (transform_paged_dense_mfma_supported(t, sh, n_pages))
+    return launch_transform_paged_dense_mfma(t, sh, mla_pool, pools, page_ids, n_pages, st);
   if (sh.dtype == TPLA_F32) return launch_paged_t<float>(t, sh, mla_pool, pools, page_ids, n_pages, st);
   return launch_paged_t<bf16_t>(t, sh, mla_pool, pools, page_ids, n_pages, st);
 }

@@ -16,6 +16,8 @@
 // per row) become 4 MFMAs per row.
 #include "tpla_internal.h"
 
+#include <mutex>
+
 namespace tpla {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -209,6 +211,195 @@ int launch_transform_paged_mfma(const TransformArgs& t, const tpla_shape_t& sh, 
     hipLaunchKernelGGL(transform_paged_fwht_mfma_kernel<4>, grid, dim3(256), 0, st, in, pools, page_ids,
                        t.signs, (int)n_pages, pt, rows_per_wave, sh.d_r, sh.g);
   return check_launch("transform_paged_fwht_mfma_kernel");
+}
+
+// ---------------------------------------------------------------------------
+// Dense U (Sec. 4.3.2: the PCA basis) over MLA pages: Y = X U as a GEMM on the
+// matrix cores.  X rows are bf16 (exact operands, loaded from global memory
+// straight into the A layout, 8 consecutive k per lane).  U is float: every
+// entry is split into bf16 hi + lo and both products are accumulated in float,
+// so the result is rounded to bf16 once, from (nearly) the float product.
+//
+// A workgroup owns 64 output columns: its slab of U (d_c x 64, hi and lo) is
+// converted once into LDS in B-operand order (one 16-byte read per operand,
+// shared by 4 row tiles), then the workgroup walks over blocks of 512 rows, 8
+// waves x 4 tiles of 16 rows.  As in the Hadamard pass, the slab's columns are
+// ordered so that a lane owns 4 adjacent output columns.  The d_c/64 workgroups
+// that read the same rows sit on one XCD (block ids congruent mod 8), so the
+// rows come from that XCD's L2 after the first touch.
+constexpr int DENSE_WAVES = 8;
+constexpr int DENSE_ROWS = DENSE_WAVES * 64;     // rows per workgroup pass
+constexpr int DENSE_AHEAD = 4;                   // k-steps of A operands in flight per tile
+
+// First of the 8 k indices that k group `kg` holds in k-step s.  Steps come in
+// pairs over 64 elements in which a lane owns 16 consecutive ones, 8 per step:
+// its two loads hit the same 32 bytes of a cache line back to back.
+__device__ __forceinline__ int dense_k0(int s, int kg) { return 64 * (s >> 1) + 16 * kg + 8 * (s & 1); }
+
+template <int NB>                                 // d_c = 64 NB
+__global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_kernel(
+    const bf16_t* __restrict__ mla_pool, ShardPools pools, const int32_t* __restrict__ page_ids,
+    const float* __restrict__ U, int n_rows, int page_tokens, int page_shift, int d_r, int g,
+    int n_row_blocks, int row_workers) {
+  extern __shared__ u32x4 panel[];                 // [2][KS][4][64] operands: hi then lo
+  constexpr int KS = 2 * NB, D_C = 64 * NB;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lo = lane & 15, hi = lane >> 4;
+  const int id = blockIdx.x;
+  const int nb = (id >> 3) % NB;                   // column block
+  const int worker = (id / (8 * NB)) * 8 + (id & 7);
+  const int dl = D_C / g;
+
+  for (int idx = tid; idx < KS * 256; idx += DENSE_WAVES * 64) {
+    const int ln = idx & 63, nt = (idx >> 6) & 3, s = idx >> 8;
+    const int col = 64 * nb + 4 * (ln & 15) + nt;
+    const int k0 = dense_k0(s, ln >> 4);
+    u32x4 ph, pl;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const float u0 = U[(k0 + 2 * jj) * D_C + col], u1 = U[(k0 + 2 * jj + 1) * D_C + col];
+      const bf16_t h0 = (bf16_t)u0, h1 = (bf16_t)u1;
+      const bf16_t l0 = (bf16_t)(u0 - (float)h0), l1 = (bf16_t)(u1 - (float)h1);
+      ph[jj] = (unsigned)__builtin_bit_cast(unsigned short, h0) | ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16);
+      pl[jj] = (unsigned)__builtin_bit_cast(unsigned short, l0) | ((unsigned)__builtin_bit_cast(unsigned short, l1) << 16);
+    }
+    panel[idx] = ph;
+    panel[KS * 256 + idx] = pl;
+  }
+  __syncthreads();
+
+  const int in_pitch = D_C + d_r, out_pitch = dl + d_r;
+  const int shard = (64 * nb) / dl;
+  bf16_t* const out_base = static_cast<bf16_t*>(pools.p[shard]) + (64 * nb - shard * dl) + 4 * lo;
+  const int last = n_rows - 1;
+  auto token_of = [&](int row) -> size_t {           // physical token index of logical row
+    const int pg = page_shift >= 0 ? (row >> page_shift) : (int)((unsigned)row / (unsigned)page_tokens);
+    const int slot = row - pg * page_tokens;
+    const size_t page = page_ids ? (size_t)page_ids[pg] : (size_t)pg;
+    return page * (size_t)page_tokens + slot;
+  };
+
+  for (int rb = worker; rb < n_row_blocks; rb += row_workers) {
+    const int row0 = rb * DENSE_ROWS + wave * 64;
+    if (row0 <= last) {                              // whole waves skip an empty tail
+      // as holder of the data operand: row lo of each tile, k group hi
+      const bf16_t* ap[4];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) ap[mt] = mla_pool + token_of(min(row0 + 16 * mt + lo, last)) * in_pitch;
+      f32x4 acc[4][4];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      u32x4 a[DENSE_AHEAD][4];
+#pragma unroll
+      for (int d = 0; d < DENSE_AHEAD; ++d)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) a[d][mt] = *reinterpret_cast<const u32x4*>(ap[mt] + dense_k0(d, hi));
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        bf16x8 av[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) av[mt] = __builtin_bit_cast(bf16x8, a[s % DENSE_AHEAD][mt]);
+        if (s + DENSE_AHEAD < KS) {                  // refill this slot
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+            a[s % DENSE_AHEAD][mt] = *reinterpret_cast<const u32x4*>(ap[mt] + dense_k0(s + DENSE_AHEAD, hi));
+        }
+        // keep the refill ahead of this step's MFMAs: left alone, the scheduler sinks the loads
+        // to just before their use and every k-step waits a full memory latency
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+          const bf16x8 bh = __builtin_bit_cast(bf16x8, panel[(s * 4 + nt) * 64 + lane]);
+          const bf16x8 bl = __builtin_bit_cast(bf16x8, panel[KS * 256 + (s * 4 + nt) * 64 + lane]);
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) {
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], bh, acc[mt][nt], 0, 0, 0);
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], bl, acc[mt][nt], 0, 0, 0);
+          }
+        }
+      }
+      // as holder of the result: rows 16 mt + 4 hi + i, columns 64 nb + 4 lo + nt
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = row0 + 16 * mt + 4 * hi + i;
+          if (r <= last) {
+            const bf16x2 p0 = __builtin_convertvector(f32x2{acc[mt][0][i], acc[mt][1][i]}, bf16x2);
+            const bf16x2 p1 = __builtin_convertvector(f32x2{acc[mt][2][i], acc[mt][3][i]}, bf16x2);
+            const u32x2 out = {__builtin_bit_cast(unsigned, p0), __builtin_bit_cast(unsigned, p1)};
+            __builtin_nontemporal_store(out, reinterpret_cast<u32x2*>(out_base + token_of(r) * out_pitch));
+          }
+        }
+    }
+    // the RoPE key of the block's rows goes to every slice (column block 0 only)
+    if (nb == 0) {
+      const int r = rb * DENSE_ROWS + tid;
+      if (r <= last) {
+        const size_t tok = token_of(r);
+        const bf16_t* src = mla_pool + tok * in_pitch + D_C;
+        for (int c = 0; c < d_r; c += 8) {
+          const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + c));
+          for (int i = 0; i < g; ++i)
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<bf16_t*>(pools.p[i]) + tok * out_pitch + dl + c));
+        }
+      }
+    }
+  }
+}
+
+bool transform_paged_dense_mfma_supported(const TransformArgs& t, const tpla_shape_t& sh, int64_t n_pages) {
+  if (sh.dtype != TPLA_BF16 || t.mode != TPLA_U_DENSE || t.inverse || !t.U) return false;
+  if (sh.d_c != 128 && sh.d_c != 256 && sh.d_c != 512) return false;   // the slab of U must fit the LDS
+  const int dl = sh.d_c / sh.g;
+  if (dl % 64 != 0 || sh.d_r % 8 != 0) return false;
+  return n_pages > 0 && n_pages * sh.page_tokens < ((int64_t)1 << 31) - DENSE_ROWS;
+}
+
+template <int NB>
+static int launch_dense_t(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
+                          const ShardPools& pools, const int32_t* page_ids, int64_t n_pages, hipStream_t st) {
+  const size_t smem = (size_t)(2 * NB) * 256 * 16 * 2;
+  static std::mutex mu;
+  static bool opted_in[16] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(TPLA_ERR_HIP, "hipGetDevice failed");
+  if (smem > 64 * 1024) {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!opted_in[dev]) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(transform_paged_dense_mfma_kernel<NB>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(TPLA_ERR_HIP, "cannot reserve %zu bytes of LDS for transform_paged_dense_mfma_kernel", smem);
+      }
+      opted_in[dev] = true;
+    }
+  }
+  const int pt = sh.page_tokens;
+  int page_shift = -1;
+  if ((pt & (pt - 1)) == 0)
+    for (page_shift = 0; (1 << page_shift) < pt; ++page_shift) {}
+  const int n_rows = (int)(n_pages * pt);
+  const int n_row_blocks = (n_rows + DENSE_ROWS - 1) / DENSE_ROWS;
+  // one workgroup per CU where the slab fills the LDS; row workers in multiples of 8 (one per XCD)
+  int workers = device_cu_count() * (NB == 8 ? 1 : 2) / NB;
+  if (workers > n_row_blocks) workers = n_row_blocks;
+  workers = (workers + 7) / 8 * 8;
+  const dim3 grid((unsigned)(workers * NB));
+  hipLaunchKernelGGL(transform_paged_dense_mfma_kernel<NB>, grid, dim3(DENSE_WAVES * 64), smem, st,
+                     static_cast<const bf16_t*>(mla_pool), pools, page_ids, t.U, n_rows, pt, page_shift, sh.d_r,
+                     sh.g, n_row_blocks, workers);
+  return check_launch("transform_paged_dense_mfma_kernel");
+}
+
+int launch_transform_paged_dense_mfma(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
+                                      const ShardPools& pools, const int32_t* page_ids, int64_t n_pages,
+                                      hipStream_t st) {
+  if (sh.d_c == 512) return launch_dense_t<8>(t, sh, mla_pool, pools, page_ids, n_pages, st);
+  if (sh.d_c == 256) return launch_dense_t<4>(t, sh, mla_pool, pools, page_ids, n_pages, st);
+  return launch_dense_t<2>(t, sh, mla_pool, pools, page_ids, n_pages, st);
 }
 
 }  // namespace tpla

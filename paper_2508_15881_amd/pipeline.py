@@ -93,3 +93,19 @@ def transform_weights(shape, mode, signs, U, W_UK, W_UV):
     B.tpla_transform_latent(shape, mode, 0, signs, U, W_UK, W_UK_t, H * d_n, 1)
     B.tpla_transform_latent(shape, mode, 0, signs, U, W_UV, W_UV_t, H, W_UV.shape[2])
     return W_UK_t, W_UV_t
+
+
+def pca_calibrate(shape, mla_pool, page_ids, page_fill, n_rows, device="cuda"):
+    """PCA basis of the latents in the listed pages: second moments on the GPU
+    (tpla_latent_moments), eigen-decomposition on the host (tpla_pca_basis).
+    n_rows = number of valid rows (all page_fill entries, or pages x page_tokens).
+    Returns (U float32 device tensor [d_c, d_c], eigenvalues, variance fractions of the g slices)."""
+    n_pages = int(page_ids.numel()) if page_ids is not None else int(mla_pool.shape[0])
+    ws_b = B.tpla_latent_moments_workspace_bytes(shape, n_pages)
+    ws = torch.empty(max(ws_b, 16), dtype=torch.uint8, device=device)
+    s = torch.empty(shape.d_c, dtype=torch.float64, device=device)
+    G = torch.empty((shape.d_c, shape.d_c), dtype=torch.float64, device=device)
+    B.tpla_latent_moments(shape, mla_pool, page_ids, page_fill, n_pages, ws, ws_b, s, G)
+    torch.cuda.synchronize()
+    U, eig, frac = B.tpla_pca_basis(shape.d_c, shape.g, int(n_rows), s.cpu().numpy(), G.cpu().numpy())
+    return torch.from_numpy(U).to(device), eig, frac

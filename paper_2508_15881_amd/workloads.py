@@ -169,6 +169,17 @@ def draw_sequence(w, b, L, heavy=None, width=None):
     return to_storage(c, w.dtype), to_storage(k, w.dtype)
 
 
+def draw_anisotropic_latents(seed, n, d, decay=6.0, offset=0.25):
+    """Calibration-style latents [n, d] (float32): independent normal components
+    whose standard deviations fall geometrically by exp(-decay) from first to
+    last, turned by a random rotation and shifted by a constant -- so the
+    covariance has a distinct, known-shaped spectrum and a non-zero mean."""
+    r = np.random.default_rng([seed, 900])
+    rot = np.linalg.qr(r.standard_normal((d, d)))[0]
+    scales = np.exp(-decay * np.arange(d) / d)
+    return ((r.standard_normal((n, d)) * scales) @ rot.T + offset).astype(np.float32)
+
+
 # ---------------------------------------------------------------- paging
 def place_rows(pool, page_ids, rows):
     """Writes rows [L, width] of one sequence into pool [P, page_tokens, width]

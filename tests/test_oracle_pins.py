@@ -368,3 +368,17 @@ def test_bf16_rounding_and_paging_helpers():
     got = orc.paged_rows(pool, [3, 0, 4], 9)
     ref = np.concatenate([pool[3], pool[0], pool[4][:1]])
     assert np.array_equal(got, ref)
+
+
+def test_latent_moments_give_the_library_covariance():
+    # pinned to numpy's own covariance routine (biased, rows = observations) and to a hand-countable case
+    rng = np.random.default_rng(12)
+    F = rng.standard_normal((300, 5)) * np.array([3.0, 1.0, 0.5, 2.0, 0.1]) + np.array([0.5, -1.0, 0.0, 2.0, 0.3])
+    s, G = orc.latent_moments(F)
+    n = F.shape[0]
+    assert np.allclose(G / n - np.outer(s / n, s / n), np.cov(F, rowvar=False, bias=True), rtol=1e-12, atol=1e-12)
+    s2, G2 = orc.latent_moments(np.array([[1.0, 2.0], [3.0, -1.0]]))
+    assert np.array_equal(s2, [4.0, 1.0]) and np.array_equal(G2, [[10.0, -1.0], [-1.0, 5.0]])
+    # and pca_U is the eigen-decomposition of exactly that covariance
+    U, ev = orc.pca_U(F)
+    assert np.allclose(U @ np.diag(ev) @ U.T, G / n - np.outer(s / n, s / n), atol=1e-12)
