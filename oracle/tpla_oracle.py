@@ -280,6 +280,43 @@ def mla_naive(q_nope, q_pe, W_UK, W_UV, c_list, kpe_list, scale):
     return o
 
 
+def mla_prefill(q_nope, q_pe, W_UK, W_UV, c, k_pe, cu_seqlens, scale):
+    """Prefill with MLA in its un-absorbed form (Sec. 4.5: prefill stays MLA,
+    heads split over devices; Sec. 3.3 for the per-head keys and values): the
+    T tokens of all sequences are packed, sequence b owning rows
+    cu_seqlens[b]..cu_seqlens[b+1]-1.  Token t of a sequence attends to tokens
+    0..t of the same sequence (causal):
+        k[s, h] = W_UK[h] c_s,  v[s, h] = c_s W_UV[h]
+        score[t, s, h] = scale (q_nope[t, h] . k[s, h] + q_pe[t, h] . k_pe[s]),  s <= t
+        o[t, h] = sum_s softmax_s(score[t, :, h]) v[s, h]
+    q_nope [T, H, d_n], q_pe [T, H, d_r], c [T, d_c], k_pe [T, d_r].
+    Returns o [T, H, d_v]."""
+    q_nope = np.asarray(q_nope, dtype=F64)
+    q_pe = np.asarray(q_pe, dtype=F64)
+    W_UK = np.asarray(W_UK, dtype=F64)
+    W_UV = np.asarray(W_UV, dtype=F64)
+    c = np.asarray(c, dtype=F64)
+    k_pe = np.asarray(k_pe, dtype=F64)
+    T, Hh, _ = q_nope.shape
+    o = np.zeros((T, Hh, W_UV.shape[2]), dtype=F64)
+    for b in range(len(cu_seqlens) - 1):
+        t0, t1 = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        L = t1 - t0
+        if L == 0:
+            continue
+        future = np.triu(np.ones((L, L), dtype=bool), k=1)          # [t, s] with s > t
+        for h in range(Hh):
+            k = c[t0:t1] @ W_UK[h].T                                 # [L, d_n]
+            v = c[t0:t1] @ W_UV[h]                                   # [L, d_v]
+            s = F64(scale) * (q_nope[t0:t1, h] @ k.T + q_pe[t0:t1, h] @ k_pe[t0:t1].T)
+            s = np.where(future, -np.inf, s)
+            s = s - s.max(axis=1, keepdims=True)
+            p = np.exp(s)
+            p /= p.sum(axis=1, keepdims=True)
+            o[t0:t1, h] = p @ v
+    return o
+
+
 def tpla_bruteforce(q_nope, q_pe, W_UK, W_UV, c_list, kpe_list, g, scale, U=None, mu=None):
     """TPLA decode written with scalar Python loops only (tiny shapes).
     Independent of the vectorised functions above: used to cross-check them."""

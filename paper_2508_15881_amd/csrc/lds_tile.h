@@ -1,0 +1,63 @@
+// Building blocks shared by the kernels that stream bf16 tiles through LDS with
+// direct-to-LDS loads and feed them to 16x16x32 MFMAs (decode_mfma.hip,
+// prefill_mfma.hip): compile-time loops, LDS reads in inline assembly with
+// hand-placed waits, and the tile swizzle.
+#pragma once
+#include <utility>
+#include "tpla_internal.h"
+
+namespace tpla {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float LAZY = 8.0f;   // log2 units: the softmax reference lags the running maximum by at most this
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// Compile-time loop: f receives std::integral_constant<int, i>, so i can feed
+// instruction immediates.
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
+
+// s_waitcnt immediate that only waits on the vector-memory counter.
+__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+template <int OFF>
+__device__ __forceinline__ void lds_read_b128(bf16x8& dst, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+// Transposing read: lane j of each 16-lane group points at 4 bf16 of row j/4,
+// columns 4*(j%4)..; lane i receives column i of those 4 rows.
+template <int OFF>
+__device__ __forceinline__ void lds_read_tr_b64(u32x2& dst, unsigned addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+// Waits until at most N LDS operations of this wave are outstanding; the
+// operands are tied so that their consumers cannot be scheduled before it.
+template <int N>
+__device__ __forceinline__ void lds_wait(bf16x8& a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+
+// 16-byte pieces of a tile are stored at a swizzled position: piece c of
+// token `tok` lives at piece index tok * RC + (c ^ swz(tok)).  RC is 8 mod 16,
+// so rows alternate between the two halves of the 64 LDS banks and swz, a
+// bijection of (tok >> 1) & 7, supplies the other three bits: the row-wise
+// reads (16 lanes = 16 tokens x 16 B at one column) and the transposing reads
+// (16 tokens x 32 B at one column) then run at the LDS issue rate of one wave
+// instruction per 4 cycles (measured; other XOR maps were no faster).
+// The direct-to-LDS load writes lane l of an instruction at base + 16 l, so
+// the swizzle is applied to the global address each lane fetches from.
+__device__ __forceinline__ int swz(int tok) { return (tok >> 1) & 7; }
+
+}  // namespace tpla

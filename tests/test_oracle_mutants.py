@@ -25,6 +25,8 @@ PIN_FUNCS = [
     pins.test_bf16_rounding_and_paging_helpers,
     pins.test_sliced_rmsnorm_append,
     pins.test_output_projection_is_head_major_and_row_parallel,
+    pins.test_latent_moments_give_the_library_covariance,
+    pins.test_prefill_is_token_by_token_decode_over_each_sequence_prefix,
 ]
 
 
@@ -168,7 +170,52 @@ def m_output_projection_value_major(o, W_O):
     return o.transpose(0, 2, 1).reshape(o.shape[0], -1) @ np.asarray(W_O, dtype=float)
 
 
+def _prefill_variant(mask_from, rope, respect_boundaries):
+    """Prefill re-typed with one thing changed: first masked key offset, RoPE term, sequence walls."""
+    def f(q_nope, q_pe, W_UK, W_UV, c, k_pe, cu_seqlens, scale):
+        q_nope, q_pe, c, k_pe = (np.asarray(x, dtype=np.float64) for x in (q_nope, q_pe, c, k_pe))
+        T, Hh, _ = q_nope.shape
+        o = np.zeros((T, Hh, np.asarray(W_UV).shape[2]))
+        cu = list(cu_seqlens) if respect_boundaries else [0, T]
+        for b in range(len(cu) - 1):
+            t0, t1 = int(cu[b]), int(cu[b + 1])
+            L = t1 - t0
+            if L == 0:
+                continue
+            masked = np.triu(np.ones((L, L), dtype=bool), k=mask_from)
+            for h in range(Hh):
+                k = c[t0:t1] @ np.asarray(W_UK)[h].T
+                v = c[t0:t1] @ np.asarray(W_UV)[h]
+                s_ = scale * (q_nope[t0:t1, h] @ k.T + (q_pe[t0:t1, h] @ k_pe[t0:t1].T if rope else 0.0))
+                s_ = np.where(masked, -1e300, s_)
+                p = np.exp(s_ - s_.max(axis=1, keepdims=True))
+                o[t0:t1, h] = (p / p.sum(axis=1, keepdims=True)) @ v
+        return o
+    return f
+
+
+m_prefill_sees_next_token = _prefill_variant(2, True, True)
+m_prefill_sees_next_token.__name__ = "m_prefill_sees_next_token"
+m_prefill_not_causal = _prefill_variant(10 ** 6, True, True)
+m_prefill_not_causal.__name__ = "m_prefill_not_causal"
+m_prefill_no_rope = _prefill_variant(1, False, True)
+m_prefill_no_rope.__name__ = "m_prefill_no_rope"
+m_prefill_no_sequence_walls = _prefill_variant(1, True, False)
+m_prefill_no_sequence_walls.__name__ = "m_prefill_no_sequence_walls"
+
+
+def m_moments_centered(F):
+    F = np.asarray(F, dtype=np.float64)
+    Fc = F - F.mean(axis=0, keepdims=True)
+    return F.sum(axis=0), Fc.T @ Fc
+
+
 MUTANTS = [
+    ("mla_prefill", m_prefill_sees_next_token),
+    ("mla_prefill", m_prefill_not_causal),
+    ("mla_prefill", m_prefill_no_rope),
+    ("mla_prefill", m_prefill_no_sequence_walls),
+    ("latent_moments", m_moments_centered),
     ("output_projection", m_output_projection_value_major),
     ("sliced_rms_rows", m_sliced_rms_local_mean),
     ("sliced_rms_rows", m_sliced_rms_eps_scaled),

@@ -382,3 +382,39 @@ def test_latent_moments_give_the_library_covariance():
     # and pca_U is the eigen-decomposition of exactly that covariance
     U, ev = orc.pca_U(F)
     assert np.allclose(U @ np.diag(ev) @ U.T, G / n - np.outer(s / n, s / n), atol=1e-12)
+
+
+# ------------------------------------------------------------------- prefill
+def test_prefill_is_token_by_token_decode_over_each_sequence_prefix():
+    """Causal prefill of packed sequences = for every token, MLA decode (pinned above
+    against brute force) whose cache is that sequence's prefix up to and including the token."""
+    rng = np.random.default_rng(21)
+    H, d_n, d_r, d_c, d_v = 2, 3, 2, 4, 3
+    lens = [5, 1, 0, 6]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    T = int(cu[-1])
+    q_nope, q_pe = rng.standard_normal((T, H, d_n)), rng.standard_normal((T, H, d_r))
+    W_UK, W_UV = rng.standard_normal((H, d_n, d_c)), rng.standard_normal((H, d_c, d_v))
+    c, kpe = rng.standard_normal((T, d_c)), rng.standard_normal((T, d_r))
+    scale = 0.37
+    o = orc.mla_prefill(q_nope, q_pe, W_UK, W_UV, c, kpe, cu, scale)
+    assert o.shape == (T, H, d_v)
+    for b, L in enumerate(lens):
+        for i in range(L):
+            t = cu[b] + i
+            ref = orc.mla_naive(q_nope[t:t + 1], q_pe[t:t + 1], W_UK, W_UV, [c[cu[b]:t + 1]], [kpe[cu[b]:t + 1]], scale)
+            assert np.allclose(o[t], ref[0], rtol=1e-12, atol=1e-13), (b, i)
+        if L:
+            # the first token sees only itself: its output is its own value vector
+            assert np.allclose(o[cu[b]], np.einsum("c,hcv->hv", c[cu[b]], W_UV), rtol=1e-12, atol=1e-13)
+    # scalar-loop check of one entry (second sequence-of-5 token 3, head 1)
+    t, h, t0 = 3, 1, 0
+    sc = [scale * (sum(q_nope[t, h, n] * sum(W_UK[h, n, a] * c[s_, a] for a in range(d_c)) for n in range(d_n))
+                   + sum(q_pe[t, h, r] * kpe[s_, r] for r in range(d_r))) for s_ in range(t0, t + 1)]
+    w = np.exp(np.array(sc) - max(sc)); w /= w.sum()
+    ref = [sum(w[j] * sum(c[t0 + j, a] * W_UV[h, a, v] for a in range(d_c)) for j in range(len(sc))) for v in range(d_v)]
+    assert np.allclose(o[t, h], ref, rtol=1e-12, atol=1e-13)
+    # a change in a later token or in another sequence never reaches an earlier output
+    c2 = c.copy(); c2[4] += 1.0; c2[7] -= 2.0
+    o2 = orc.mla_prefill(q_nope, q_pe, W_UK, W_UV, c2, kpe, cu, scale)
+    assert np.array_equal(o2[:4], o[:4]) and np.array_equal(o2[5:7], o[5:7])
