@@ -221,6 +221,29 @@ int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void
                            void* workspace, size_t workspace_bytes, float* out, void* stream);
 
 /*
+ * Prefill attention with MLA in its un-absorbed form (Sec. 4.5: the prefill
+ * phase keeps MLA, heads split over devices; Sec. 3.3: per-head keys
+ * k = W_UK[h] c and values v = c W_UV[h], the RoPE key shared by all heads).
+ * The T tokens of shape->B sequences are packed; cu_seqlens int32 [B + 1]
+ * (device, cu_seqlens[0] = 0, non-decreasing, cu_seqlens[B] = T) gives their
+ * row ranges; token t attends to the tokens of its own sequence up to and
+ * including itself.  q_nope [T, H, d_n], q_pe [T, H, d_r], c [T, d_c] (the
+ * normalised latent, as cached), k_pe [T, d_r], W_UK [H, d_n, d_c],
+ * W_UV [H, d_c, d_v] in shape->dtype (original basis: no U); o float
+ * [T, H, d_v].  max_seq_len: an upper bound of the longest sequence (queries
+ * beyond it are not computed).  workspace:
+ * tpla_prefill_workspace_bytes() bytes (the projected keys and values, bf16).
+ * shape->g, page_tokens are not used.  Implemented for bf16 with d_n = d_v =
+ * 128, d_r = 64, d_c a multiple of 128 up to 512 (TPLA_ERR_UNSUPPORTED
+ * otherwise).  The latent rows are what tpla_write_mla_cache stores.
+ */
+size_t tpla_prefill_workspace_bytes(const tpla_shape_t* shape, int64_t T);
+int tpla_prefill_attention(const tpla_shape_t* shape, const void* q_nope, const void* q_pe, const void* c,
+                           const void* k_pe, const void* W_UK, const void* W_UV, const int32_t* cu_seqlens,
+                           int64_t T, int32_t max_seq_len, void* workspace, size_t workspace_bytes, float* o,
+                           void* stream);
+
+/*
  * PCA calibration, step 1 (Sec. 4.3.2: the covariance of collected latents,
  * position features excluded): second moments of the latent part of cached
  * rows.  mla_pool as in tpla_transform_latent_paged; page_ids int32 [n_pages]

@@ -21,7 +21,7 @@ EXPORTS = (
     "tpla_combine_shards", "tpla_profile_enable", "tpla_profile_collect", "tpla_workspace_bytes_all",
     "tpla_decode_shards", "tpla_append_token_sliced", "tpla_output_projection",
     "tpla_output_projection_workspace_bytes", "tpla_latent_moments_workspace_bytes", "tpla_latent_moments",
-    "tpla_pca_basis",
+    "tpla_pca_basis", "tpla_prefill_workspace_bytes", "tpla_prefill_attention",
 )
 
 
@@ -98,6 +98,10 @@ def load_library():
     lib.tpla_latent_moments_workspace_bytes.argtypes = [shp, i64]
     lib.tpla_latent_moments.restype = ctypes.c_int
     lib.tpla_latent_moments.argtypes = [shp, vp, vp, vp, i64, vp, ctypes.c_size_t, vp, vp, vp]
+    lib.tpla_prefill_workspace_bytes.restype = ctypes.c_size_t
+    lib.tpla_prefill_workspace_bytes.argtypes = [shp, i64]
+    lib.tpla_prefill_attention.restype = ctypes.c_int
+    lib.tpla_prefill_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, ctypes.c_size_t, vp, vp]
     lib.tpla_pca_basis.restype = ctypes.c_int
     lib.tpla_pca_basis.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp]
     _lib = lib
@@ -226,6 +230,17 @@ def tpla_output_projection_workspace_bytes(shape, D):
 def tpla_output_projection(shape, o, W_O, D, workspace, workspace_bytes, out, stream=None):
     _check(load_library().tpla_output_projection(
         ctypes.byref(shape), _ptr(o), _ptr(W_O), D, _ptr(workspace), workspace_bytes, _ptr(out), _stream(stream)))
+
+
+def tpla_prefill_workspace_bytes(shape, T):
+    return int(load_library().tpla_prefill_workspace_bytes(ctypes.byref(shape), T))
+
+
+def tpla_prefill_attention(shape, q_nope, q_pe, c, k_pe, W_UK, W_UV, cu_seqlens, T, max_seq_len, workspace,
+                           workspace_bytes, o, stream=None):
+    _check(load_library().tpla_prefill_attention(
+        ctypes.byref(shape), _ptr(q_nope), _ptr(q_pe), _ptr(c), _ptr(k_pe), _ptr(W_UK), _ptr(W_UV), _ptr(cu_seqlens),
+        T, max_seq_len, _ptr(workspace), workspace_bytes, _ptr(o), _stream(stream)))
 
 
 def tpla_latent_moments_workspace_bytes(shape, n_pages):

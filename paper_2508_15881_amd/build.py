@@ -18,7 +18,7 @@ LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libtpla.so")
 
 SOURCES = ["api.hip", "decode_mfma.hip", "decode_generic.hip", "transform.hip", "transform_mfma.hip", "absorb_combine.hip",
-           "absorb_combine_mfma.hip", "pca.hip"]
+           "absorb_combine_mfma.hip", "pca.hip", "prefill_mfma.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -394,6 +394,34 @@ int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void
   return launch_output_projection(*shape, o, W_O, D, static_cast<float*>(workspace), out, (hipStream_t)stream);
 }
 
+size_t tpla_prefill_workspace_bytes(const tpla_shape_t* shape, int64_t T) {
+  if (check_shape(shape) != TPLA_OK || T < 1) return 0;
+  return (size_t)T * shape->H * (shape->d_n + shape->d_v) * 2;
+}
+
+int tpla_prefill_attention(const tpla_shape_t* shape, const void* q_nope, const void* q_pe, const void* c,
+                           const void* k_pe, const void* W_UK, const void* W_UV, const int32_t* cu_seqlens,
+                           int64_t T, int32_t max_seq_len, void* workspace, size_t workspace_bytes, float* o,
+                           void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!q_nope || !q_pe || !c || !k_pe || !W_UK || !W_UV || !cu_seqlens || !o)
+    return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
+  if (T < 1 || max_seq_len < 1) return fail(TPLA_ERR_SHAPE, "T=%lld max_seq_len=%d", (long long)T, max_seq_len);
+  if (!prefill_mfma_supported(*shape))
+    return fail(TPLA_ERR_UNSUPPORTED, "prefill needs bf16, d_n = d_v = 128, d_r = 64, d_c a multiple of 128 up to 512");
+  if (T * shape->H >= ((int64_t)1 << 31) / 2 || shape->B > 65535 || shape->H > 65535)
+    return fail(TPLA_ERR_UNSUPPORTED, "T*H, B or H too large for this kernel");
+  if (!aligned16(q_nope) || !aligned16(q_pe) || !aligned16(c) || !aligned16(k_pe) || !aligned16(W_UK) ||
+      !aligned16(W_UV) || !aligned16(workspace) || !aligned16(o))
+    return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  const size_t need = tpla_prefill_workspace_bytes(shape, T);
+  if (!workspace || workspace_bytes < need)
+    return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+  return launch_prefill_attention(*shape, q_nope, q_pe, c, k_pe, W_UK, W_UV, cu_seqlens, (int)T, max_seq_len,
+                                  workspace, o, (hipStream_t)stream);
+}
+
 size_t tpla_latent_moments_workspace_bytes(const tpla_shape_t* shape, int64_t n_pages) {
   if (check_shape(shape) != TPLA_OK || n_pages < 1) return 0;
   return latent_moments_workspace(*shape, n_pages);

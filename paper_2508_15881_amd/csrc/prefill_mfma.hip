@@ -1,0 +1,423 @@
+// Prefill with MLA in its un-absorbed form (Sec. 4.5 of the paper: the prefill
+// phase keeps MLA with the heads split over devices; Sec. 3.3 for the per-head
+// keys and values), bf16 on the matrix cores, for packed variable-length
+// sequences with a causal mask.
+//
+//   prefill_kv_project_kernel     kv[t, h] = [ c_t W_UV[h] | W_UK[h] c_t ]   (values, no-RoPE keys)
+//   prefill_attention_mfma_kernel o[t, h]  = sum_{s<=t} softmax_s(scale (q_nope.k + q_pe.k_pe)) v
+//
+// The attention kernel is the decode kernel's tile machinery turned around: a
+// workgroup owns 128 consecutive queries of one (sequence, head), a wave 32 of
+// them as two blocks of 16, and 32-key tiles [V 128 | K 128 | k_pe 64] go
+// through a ring of 3 LDS buffers with direct-to-LDS loads (the RoPE key comes
+// from the array shared by all heads).  Queries are the MFMA N dimension:
+//   S^T[key, query] = K[key, :] . Q[query, :]          M = keys, N = queries
+//   O^T[dim, query] += V^T[dim, key] . P^T[key, query]  M = value dims, N = queries
+// so a lane only ever sees one query per block, the online softmax needs no
+// LDS, and P stays in registers between the two products.  Key tiles above the
+// diagonal are never loaded; blocks entirely above it skip the tile.
+#include "lds_tile.h"
+
+#include <algorithm>
+#include <mutex>
+
+namespace tpla {
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------
+// Up-projection: Y[t, n] = sum_k c[t, k] B[k, n] per head, B = W_UV[h] (values)
+// or W_UK[h]^T (keys).  Same shape of kernel as the dense cache transform: the
+// head's weight goes to LDS once in B-operand order, the workgroup (8 waves x
+// 4 row tiles) walks over blocks of 512 tokens, A operands straight from
+// global memory with 4 k-steps in flight.
+constexpr int PJ_WAVES = 8;
+constexpr int PJ_ROWS = PJ_WAVES * 64;
+constexpr int PJ_AHEAD = 2;
+
+__device__ __forceinline__ int pj_k0(int s, int kg) { return 64 * (s >> 1) + 16 * kg + 8 * (s & 1); }
+
+// grid: (2 H, row workers); blockIdx.x = 2 h + part (0: values, 1: keys)
+__global__ void __launch_bounds__(PJ_WAVES * 64) prefill_kv_project_kernel(
+    const bf16_t* __restrict__ c, const bf16_t* __restrict__ W_UK, const bf16_t* __restrict__ W_UV,
+    bf16_t* __restrict__ kv, int T, int H, int d_c) {
+  extern __shared__ u32x4 panel[];                 // [KS][8][64] operands of 8 bf16
+  const int KS = d_c >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lo = lane & 15, hi = lane >> 4;
+  const int h = blockIdx.x >> 1, part = blockIdx.x & 1;
+
+  for (int idx = tid; idx < KS * 512; idx += PJ_WAVES * 64) {
+    const int ln = idx & 63, nt = (idx >> 6) & 7, s = idx >> 9;
+    const int n = 64 * (nt >> 2) + 4 * (ln & 15) + (nt & 3);      // a lane owns 4 adjacent columns per half
+    const int k0 = pj_k0(s, ln >> 4);
+    u32x4 v;
+    if (part) {
+      v = *reinterpret_cast<const u32x4*>(W_UK + ((size_t)h * 128 + n) * d_c + k0);      // W_UK[h][n][k], k contiguous
+    } else {
+      const unsigned short* w = reinterpret_cast<const unsigned short*>(W_UV) + ((size_t)h * d_c + k0) * 128 + n;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) v[jj] = (unsigned)w[(2 * jj) * 128] | ((unsigned)w[(2 * jj + 1) * 128] << 16);
+    }
+    panel[idx] = v;
+  }
+  __syncthreads();
+
+  const int last = T - 1;
+  const int n_blocks = (T + PJ_ROWS - 1) / PJ_ROWS;
+  for (int rb = blockIdx.y; rb < n_blocks; rb += gridDim.y) {
+    const int row0 = rb * PJ_ROWS + wave * 64;
+    if (row0 > last) continue;                       // whole waves; no barrier below
+    const bf16_t* ap[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) ap[mt] = c + (size_t)min(row0 + 16 * mt + lo, last) * d_c;
+    f32x4 acc[4][8];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u32x4 a[PJ_AHEAD][4];
+#pragma unroll
+    for (int d = 0; d < PJ_AHEAD; ++d)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) a[d][mt] = *reinterpret_cast<const u32x4*>(ap[mt] + pj_k0(d < KS ? d : KS - 1, hi));
+    for (int s0 = 0; s0 < KS; s0 += PJ_AHEAD) {
+#pragma unroll
+      for (int d = 0; d < PJ_AHEAD; ++d) {
+        const int s = s0 + d;                        // KS is a multiple of PJ_AHEAD (d_c % 128 == 0)
+        bf16x8 av[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) av[mt] = __builtin_bit_cast(bf16x8, a[d][mt]);
+        const int sn = min(s + PJ_AHEAD, KS - 1);    // the last refills repeat a valid address, unused
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) a[d][mt] = *reinterpret_cast<const u32x4*>(ap[mt] + pj_k0(sn, hi));
+        __builtin_amdgcn_sched_barrier(0);           // keep the refill ahead of this step's MFMAs
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+          const bf16x8 bv = __builtin_bit_cast(bf16x8, panel[(s * 8 + nt) * 64 + lane]);
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], bv, acc[mt][nt], 0, 0, 0);
+        }
+      }
+    }
+    // rows 16 mt + 4 hi + i, columns 64 half + 4 lo + (nt & 3)
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = row0 + 16 * mt + 4 * hi + i;
+        if (r <= last) {
+          bf16_t* dst = kv + ((size_t)r * H + h) * 256 + 128 * part + 4 * lo;
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const bf16x2 p0 = __builtin_convertvector(f32x2{acc[mt][4 * half][i], acc[mt][4 * half + 1][i]}, bf16x2);
+            const bf16x2 p1 = __builtin_convertvector(f32x2{acc[mt][4 * half + 2][i], acc[mt][4 * half + 3][i]}, bf16x2);
+            const u32x2 out = {__builtin_bit_cast(unsigned, p0), __builtin_bit_cast(unsigned, p1)};
+            *reinterpret_cast<u32x2*>(dst + 64 * half) = out;
+          }
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------
+constexpr int PF_TOK = 32;                 // keys per tile
+constexpr int PF_NSTAGE = 3;
+constexpr int PF_RC = 40;                  // 16-byte pieces per tile row: V 16, K 16, k_pe 8
+constexpr int PF_NW = 4;
+constexpr int PF_QB = 2;                   // blocks of 16 queries per wave
+constexpr int PF_QT = PF_NW * PF_QB * 16;  // queries per workgroup
+constexpr int PF_TC = PF_TOK * PF_RC;      // pieces per tile
+constexpr int PF_TILE_BYTES = PF_TC * 16;
+constexpr int PF_NI = PF_TC / 64;          // direct-to-LDS instructions per tile
+constexpr int PF_CPT = PF_NI / PF_NW;      // of which each wave issues this many
+static_assert(PF_NI % PF_NW == 0, "every wave issues the same number of tile loads");
+
+struct PrefillArgs {
+  const bf16_t* q_nope;   // [T, H, 128]
+  const bf16_t* q_pe;     // [T, H, 64]
+  const bf16_t* kv;       // [T, H, 256]: values then no-RoPE keys
+  const bf16_t* k_pe;     // [T, 64]
+  const int32_t* cu;      // [B + 1]
+  float* o;               // [T, H, 128]
+  int H;
+  float scale_log2;
+};
+
+// grid: (query tiles of the longest sequence, H, sequences)
+__global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(PrefillArgs a) {
+  extern __shared__ u32x4 smem[];
+  const int seq = blockIdx.z, h = blockIdx.y;
+  const int t0 = a.cu[seq], L = a.cu[seq + 1] - t0;
+  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;     // long key ranges first
+  if (qt * PF_QT >= L) return;
+  const int q0 = qt * PF_QT;
+  const int kend = min(L, q0 + PF_QT);                     // keys 0 .. kend-1 are needed
+  const int ntiles = (kend + PF_TOK - 1) / PF_TOK;
+
+  const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)smem);
+  const int tid = threadIdx.x, lane = tid & 63;
+  // scalar on purpose: the per-block skips below must be scalar branches, an MFMA does not honour a lane mask
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j16 = lane & 15, q4 = lane >> 4;
+
+  // ---- direct-to-LDS bookkeeping: instruction k of a tile fills pieces [64k, 64k+64) ----
+  int ld_tok[PF_CPT];
+  unsigned ld_src[PF_CPT];       // byte offset inside the key's kv row, or 0x80000000 | offset inside its k_pe row
+  const char* kv_base = reinterpret_cast<const char*>(a.kv) + ((size_t)t0 * a.H + h) * 512;
+  const char* kpe_base = reinterpret_cast<const char*>(a.k_pe) + (size_t)t0 * 128;
+  const size_t kv_pitch = (size_t)a.H * 512;
+#pragma unroll
+  for (int j = 0; j < PF_CPT; ++j) {
+    const int x = (wave + j * PF_NW) * 64 + lane;          // LDS piece index
+    const int tok = x / PF_RC, cs = x % PF_RC;
+    const int cg = cs ^ swz(tok);                          // the piece of the row that lives there
+    ld_tok[j] = tok;
+    ld_src[j] = cg < 32 ? (unsigned)(cg * 16) : (0x80000000u | (unsigned)((cg - 32) * 16));
+  }
+  auto issue = [&](int t) {
+    char* dst = reinterpret_cast<char*>(smem) + (t % PF_NSTAGE) * PF_TILE_BYTES;
+#pragma unroll
+    for (int j = 0; j < PF_CPT; ++j) {
+      // keys past the end of the sequence repeat its last key: finite values, masked below
+      const int key = min(t * PF_TOK + ld_tok[j], L - 1);
+      const char* src = (ld_src[j] & 0x80000000u) ? kpe_base + (size_t)key * 128 + (ld_src[j] & 0xFFFF)
+                                                   : kv_base + (size_t)key * kv_pitch + ld_src[j];
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(dst + (wave + j * PF_NW) * 1024),
+                                       16, 0, 0);
+    }
+  };
+
+  // ---- per-lane LDS byte offsets (as in the decode kernel, row of 40 pieces) ----
+  const int xk = swz(j16);
+  unsigned k_off[2];
+  k_off[0] = (unsigned)((j16 * PF_RC + ((q4) ^ xk)) * 16);
+  k_off[1] = (unsigned)((j16 * PF_RC + ((4 | q4) ^ xk)) * 16);
+  const int v_tok = 4 * q4 + (j16 >> 2);
+  const int xv = swz(v_tok);
+  const int cb = (j16 & 3) >> 1;
+  unsigned v_off[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+    v_off[d] = (unsigned)((v_tok * PF_RC + (((d << 1) | cb) ^ xv)) * 16 + (j16 & 1) * 8);
+
+  issue(0);
+  if (ntiles > 1) issue(1);
+
+  // ---- this wave's queries as B operands: block qb holds queries qbase[qb] + j16 ----
+  constexpr int KS = 6;                    // k-steps of the 192-wide score product
+  constexpr int DB = 8;                    // 16-wide blocks of the 128 value dims
+  bf16x8 qreg[PF_QB][KS];
+  int qbase[PF_QB];
+#pragma unroll
+  for (int qb = 0; qb < PF_QB; ++qb) {
+    qbase[qb] = q0 + wave * (16 * PF_QB) + qb * 16;
+    const size_t row = (size_t)(t0 + min(qbase[qb] + j16, L - 1)) * a.H + h;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int k0 = ks * 32 + q4 * 8;
+      qreg[qb][ks] = (k0 < 128) ? *reinterpret_cast<const bf16x8*>(a.q_nope + row * 128 + k0)
+                                : *reinterpret_cast<const bf16x8*>(a.q_pe + row * 64 + (k0 - 128));
+    }
+  }
+#pragma unroll
+  for (int qb = 0; qb < PF_QB; ++qb)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[qb][ks]));   // complete before the loop
+
+  f32x4 acc[PF_QB][DB];
+  float m_run[PF_QB], l_run[PF_QB];
+#pragma unroll
+  for (int qb = 0; qb < PF_QB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int d = 0; d < DB; ++d) acc[qb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int t = 0; t < ntiles; ++t) {
+    if (t + 1 < ntiles)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(PF_CPT));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();            // tile t visible to all waves, tile t-1 no longer read
+    if (t + 2 < ntiles) issue(t + 2);
+    const int key0 = t * PF_TOK;
+    // a block takes part while the tile holds a key <= its last query (wave-uniform)
+    bool active[PF_QB];
+#pragma unroll
+    for (int qb = 0; qb < PF_QB; ++qb) active[qb] = key0 <= qbase[qb] + 15;
+    if (!active[PF_QB - 1]) continue;        // later blocks have later queries: nothing to do for this wave
+    const unsigned tile = lds_base + (unsigned)((t % PF_NSTAGE) * PF_TILE_BYTES);
+
+    // ---- scores: pieces 16..39 of the row (k-steps 4..9 of the 40-piece row) ----
+    f32x4 sacc[PF_QB][2];
+#pragma unroll
+    for (int qb = 0; qb < PF_QB; ++qb) sacc[qb][0] = sacc[qb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    {
+      constexpr int NQ = KS * 2;             // K fragments, in order (ks, tb)
+      bf16x8 kf[4];
+      const unsigned ka[2] = {tile + k_off[0], tile + k_off[1]};
+      static_for<4>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int ks = i / 2 + 4, tb = i % 2;
+        lds_read_b128<(ks >> 1) * 128 + tb * (16 * PF_RC * 16)>(kf[i], ka[ks & 1]);
+      });
+      static_for<NQ>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int ks = i / 2, tb = i % 2;
+        constexpr int ahead = (NQ - 1 - i) < 3 ? (NQ - 1 - i) : 3;
+        lds_wait<ahead>(kf[i & 3]);
+#pragma unroll
+        for (int qb = 0; qb < PF_QB; ++qb)
+          if (active[qb])
+            sacc[qb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i & 3], qreg[qb][ks], sacc[qb][tb], 0, 0, 0);
+        if constexpr (i + 4 < NQ) {
+          constexpr int ks2 = (i + 4) / 2 + 4, tb2 = (i + 4) % 2;
+          lds_read_b128<(ks2 >> 1) * 128 + tb2 * (16 * PF_RC * 16)>(kf[i & 3], ka[ks2 & 1]);
+        }
+      });
+    }
+
+    // ---- causal mask + online softmax (lane = one query per block; keys key0 + 16 tb + 4 q4 + i) ----
+    bf16x8 pb[PF_QB];
+#pragma unroll
+    for (int qb = 0; qb < PF_QB; ++qb) {
+      if (!active[qb]) continue;
+      if (key0 + PF_TOK - 1 > qbase[qb]) {   // the tile reaches past this block's first query
+        const int query = qbase[qb] + j16;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (key0 + 16 * tb + 4 * q4 + i > query) sacc[qb][tb][i] = -INFINITY;
+      }
+      float mx = sacc[qb][0][0];
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, sacc[qb][tb][i]);
+      mx *= a.scale_log2;
+      if (__any(mx > m_run[qb] + LAZY)) {
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[qb], mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);   // 0 on the first tile
+        l_run[qb] *= alpha;
+        m_run[qb] = m_new;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) acc[qb][d] *= alpha;
+      }
+      float psum = 0.f;
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][tb][i], a.scale_log2, -m_run[qb]));
+          sacc[qb][tb][i] = p;
+          psum += p;
+        }
+      l_run[qb] += psum;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        pb[qb][i] = (bf16_t)sacc[qb][0][i];
+        pb[qb][4 + i] = (bf16_t)sacc[qb][1][i];
+      }
+    }
+
+    // ---- output: O^T += V^T P^T, V = pieces 0..15 of the row ----
+    {
+      u32x2 vlo[4], vhi[4];
+      unsigned va[4];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) va[d] = tile + v_off[d];
+      static_for<4>([&](auto ic) {
+        constexpr int d = decltype(ic)::value;
+        lds_read_tr_b64<0>(vlo[d], va[d & 3]);
+        lds_read_tr_b64<16 * PF_RC * 16>(vhi[d], va[d & 3]);
+      });
+      static_for<DB>([&](auto ic) {
+        constexpr int d = decltype(ic)::value;
+        constexpr int ahead = (DB - 1 - d) < 3 ? (DB - 1 - d) : 3;
+        lds_wait<2 * ahead>(vlo[d & 3], vhi[d & 3]);
+        const u32x4 v4 = {vlo[d & 3][0], vlo[d & 3][1], vhi[d & 3][0], vhi[d & 3][1]};
+#pragma unroll
+        for (int qb = 0; qb < PF_QB; ++qb)
+          if (active[qb])
+            acc[qb][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v4), pb[qb], acc[qb][d], 0, 0, 0);
+        if constexpr (d + 4 < DB) {
+          constexpr int d2 = d + 4;
+          lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d & 3], va[d2 & 3]);
+          lds_read_tr_b64<(d2 >> 2) * 128 + 16 * PF_RC * 16>(vhi[d & 3], va[d2 & 3]);
+        }
+      });
+    }
+  }
+
+  // ---- normalise and store: lane holds query qbase + j16, dims 16 d + 4 q4 .. +4 ----
+#pragma unroll
+  for (int qb = 0; qb < PF_QB; ++qb) {
+    float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    const int query = qbase[qb] + j16;
+    if (query < L) {
+      const float inv = 1.0f / l_tot;
+      float* po = a.o + ((size_t)(t0 + query) * a.H + h) * 128 + 4 * q4;
+#pragma unroll
+      for (int d = 0; d < DB; ++d) *reinterpret_cast<f32x4*>(po + 16 * d) = acc[qb][d] * inv;
+    }
+  }
+}
+
+bool prefill_mfma_supported(const tpla_shape_t& sh) {
+  return sh.dtype == TPLA_BF16 && sh.d_n == 128 && sh.d_v == 128 && sh.d_r == 64 && sh.d_c % 128 == 0 &&
+         sh.d_c <= 512;
+}
+
+int launch_prefill_attention(const tpla_shape_t& sh, const void* q_nope, const void* q_pe, const void* c,
+                             const void* k_pe, const void* W_UK, const void* W_UV, const int32_t* cu_seqlens,
+                             int T, int max_seq_len, void* kv_workspace, float* o, hipStream_t st) {
+  // 1. values and no-RoPE keys of every (token, head)
+  const size_t smem = (size_t)(sh.d_c / 32) * 512 * 16;
+  static std::mutex mu;
+  static bool opted_in[16] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return fail(TPLA_ERR_HIP, "hipGetDevice failed");
+  if (smem > 64 * 1024) {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!opted_in[dev]) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kv_project_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(TPLA_ERR_HIP, "cannot reserve 128 KiB of LDS for prefill_kv_project_kernel");
+      }
+      opted_in[dev] = true;
+    }
+  }
+  const int n_blocks = (T + PJ_ROWS - 1) / PJ_ROWS;
+  int workers = (device_cu_count() + 2 * sh.H - 1) / (2 * sh.H);
+  workers = std::max(1, std::min(workers, n_blocks));
+  hipLaunchKernelGGL(prefill_kv_project_kernel, dim3(2 * sh.H, workers), dim3(PJ_WAVES * 64), smem, st,
+                     static_cast<const bf16_t*>(c), static_cast<const bf16_t*>(W_UK),
+                     static_cast<const bf16_t*>(W_UV), static_cast<bf16_t*>(kv_workspace), T, sh.H, sh.d_c);
+  int rc = check_launch("prefill_kv_project_kernel");
+  if (rc) return rc;
+  // 2. causal attention
+  PrefillArgs a;
+  a.q_nope = static_cast<const bf16_t*>(q_nope);
+  a.q_pe = static_cast<const bf16_t*>(q_pe);
+  a.kv = static_cast<const bf16_t*>(kv_workspace);
+  a.k_pe = static_cast<const bf16_t*>(k_pe);
+  a.cu = cu_seqlens;
+  a.o = o;
+  a.H = sh.H;
+  a.scale_log2 = sh.sm_scale * 1.4426950408889634f;
+  const dim3 grid((max_seq_len + PF_QT - 1) / PF_QT, sh.H, sh.B);
+  hipLaunchKernelGGL(prefill_attention_mfma_kernel, grid, dim3(PF_NW * 64), PF_NSTAGE * PF_TILE_BYTES, st, a);
+  return check_launch("prefill_attention_mfma_kernel");
+}
+
+}  // namespace tpla

@@ -95,6 +95,12 @@ int output_projection_ksplit(const tpla_shape_t& sh, int D);
 int launch_output_projection(const tpla_shape_t& sh, const float* x, const void* W_O, int D, float* part,
                              float* out, hipStream_t st);
 
+// Prefill (un-absorbed MLA, causal, packed sequences): see prefill_mfma.hip.
+bool prefill_mfma_supported(const tpla_shape_t& sh);
+int launch_prefill_attention(const tpla_shape_t& sh, const void* q_nope, const void* q_pe, const void* c,
+                             const void* k_pe, const void* W_UK, const void* W_UV, const int32_t* cu_seqlens,
+                             int T, int max_seq_len, void* kv_workspace, float* o, hipStream_t st);
+
 // PCA calibration: see pca.hip.
 int latent_moments_splits(const tpla_shape_t& sh, int64_t n_pages);
 size_t latent_moments_workspace(const tpla_shape_t& sh, int64_t n_pages);

@@ -562,6 +562,61 @@ def test_pca_whole_path_bf16():
     assert rel_err(np.abs(step.o_lat.cpu().numpy()), np.abs(ref["O_lat"])) <= TOL["bf16"]
 
 
+# ------------------------------------------------------------ prefill (un-absorbed MLA, causal, packed)
+def _prefill_problem(seed, lens, H, d_c):
+    rng = np.random.default_rng([seed, 41])
+    T = int(sum(lens))
+    q_nope = wl.to_storage(rng.standard_normal((T, H, 128)), "bf16")
+    q_pe = wl.to_storage(rng.standard_normal((T, H, 64)), "bf16")
+    c = wl.to_storage(rng.standard_normal((T, d_c)), "bf16")
+    k_pe = wl.to_storage(rng.standard_normal((T, 64)), "bf16")
+    W_UK = wl.to_storage(rng.standard_normal((H, 128, d_c)) * 0.02, "bf16")
+    W_UV = wl.to_storage(rng.standard_normal((H, d_c, 128)) * 0.02, "bf16")
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    return {"q_nope": q_nope, "q_pe": q_pe, "c": c, "k_pe": k_pe, "W_UK": W_UK, "W_UV": W_UV, "cu": cu, "T": T}
+
+
+def _run_prefill(p, H, d_c, B, max_len):
+    shape = tp.TplaShape(B, H, d_c, 1, 64, 128, 128, 64, tp.TPLA_BF16, 1.0 / np.sqrt(192.0))
+    ws_b = tp.tpla_prefill_workspace_bytes(shape, p["T"])
+    ws = torch.full((ws_b,), 0xFF, dtype=torch.uint8, device="cuda")
+    o = torch.full((p["T"], H, 128), float("nan"), dtype=torch.float32, device="cuda")
+    dev = {k: pl.to_device(p[k], "bf16") for k in ("q_nope", "q_pe", "c", "k_pe", "W_UK", "W_UV")}
+    tp.tpla_prefill_attention(shape, dev["q_nope"], dev["q_pe"], dev["c"], dev["k_pe"], dev["W_UK"], dev["W_UV"],
+                              torch.from_numpy(p["cu"]).cuda(), p["T"], max_len, ws, ws_b, o)
+    torch.cuda.synchronize()
+    return o.cpu().numpy(), shape
+
+
+@pytest.mark.parametrize("lens,H,d_c", [([1], 1, 128), ([37, 1, 128, 0, 300, 129], 4, 512), ([700], 3, 256),
+                                        ([31, 32, 33, 127, 128, 129, 255, 257], 2, 512)])
+def test_prefill_attention_matches_oracle(lens, H, d_c):
+    _say(f"prefill_attention lens={lens} H={H} d_c={d_c}")
+    p = _prefill_problem(len(lens) * 100 + H, lens, H, d_c)
+    f64 = {k: wl.as_f64(p[k], "bf16") for k in ("q_nope", "q_pe", "c", "k_pe", "W_UK", "W_UV")}
+    ref = orc.mla_prefill(f64["q_nope"], f64["q_pe"], f64["W_UK"], f64["W_UV"], f64["c"], f64["k_pe"], p["cu"],
+                          1.0 / np.sqrt(192.0))
+    for max_len in (max(lens), max(lens) + 200):            # a loose bound only adds idle workgroups
+        o, _ = _run_prefill(p, H, d_c, len(lens), max_len)
+        assert np.all(np.isfinite(o))                        # every row written, nothing leaks from the padding
+        assert rel_err(o, ref) <= TOL["bf16"]
+        # per-token check as well: early tokens have few keys and large outputs, late ones small
+        den = np.max(np.abs(ref), axis=(1, 2), keepdims=True)
+        assert np.max(np.abs(o - ref) / den) <= 2e-2
+
+
+def test_prefill_attention_rejects_what_it_does_not_implement():
+    p = _prefill_problem(1, [8], 1, 128)
+    A = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    for kw in ({"d_n": 64}, {"d_r": 32}, {"dtype": tp.TPLA_F32}, {"d_c": 1024}):
+        f = dict(B=1, H=1, d_c=128, g=1, d_r=64, d_n=128, d_v=128, page_tokens=64, dtype=tp.TPLA_BF16, sm_scale=0.1)
+        f.update(kw)
+        shape = tp.TplaShape(f["B"], f["H"], f["d_c"], f["g"], f["d_r"], f["d_n"], f["d_v"], f["page_tokens"], f["dtype"], f["sm_scale"])
+        with pytest.raises(tp.TplaError) as e:
+            tp.tpla_prefill_attention(shape, A, A, A, A, A, A, A, 8, 8, A, 1 << 30, A)
+        assert e.value.code == -7
+
+
 # ------------------------------------------------------------ whole path, bf16, model-shaped
 @pytest.mark.parametrize("name,lens", [("dsv3_4k", [300, 1100, 64]), ("kimi_32k", [257, 900]), ("ragged_g4", [1500, 70, 640])])
 def test_whole_path_bf16_scaled_configs(name, lens):
