@@ -165,26 +165,29 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
 
   // ---- direct-to-LDS bookkeeping: instruction k of a tile fills pieces [64k, 64k+64) ----
   int ld_tok[PF_CPT];
-  unsigned ld_src[PF_CPT];       // byte offset inside the key's kv row, or 0x80000000 | offset inside its k_pe row
+  const char* ld_ptr[PF_CPT];    // source of the piece for key ld_tok of tile 0 ...
+  unsigned ld_step[PF_CPT];      // ... plus this many bytes per tile, and per key (clamped last tile)
   const char* kv_base = reinterpret_cast<const char*>(a.kv) + ((size_t)t0 * a.H + h) * 512;
   const char* kpe_base = reinterpret_cast<const char*>(a.k_pe) + (size_t)t0 * 128;
-  const size_t kv_pitch = (size_t)a.H * 512;
+  const unsigned kv_pitch = (unsigned)a.H * 512u;
 #pragma unroll
   for (int j = 0; j < PF_CPT; ++j) {
     const int x = (wave + j * PF_NW) * 64 + lane;          // LDS piece index
     const int tok = x / PF_RC, cs = x % PF_RC;
     const int cg = cs ^ swz(tok);                          // the piece of the row that lives there
     ld_tok[j] = tok;
-    ld_src[j] = cg < 32 ? (unsigned)(cg * 16) : (0x80000000u | (unsigned)((cg - 32) * 16));
+    const bool from_kv = cg < 32;                          // V and no-RoPE K; else the shared RoPE key
+    ld_step[j] = from_kv ? kv_pitch : 128u;
+    ld_ptr[j] = from_kv ? kv_base + cg * 16 : kpe_base + (cg - 32) * 16;
   }
   auto issue = [&](int t) {
     char* dst = reinterpret_cast<char*>(smem) + (t % PF_NSTAGE) * PF_TILE_BYTES;
+    const bool whole = (t + 1) * PF_TOK <= L;
 #pragma unroll
     for (int j = 0; j < PF_CPT; ++j) {
       // keys past the end of the sequence repeat its last key: finite values, masked below
-      const int key = min(t * PF_TOK + ld_tok[j], L - 1);
-      const char* src = (ld_src[j] & 0x80000000u) ? kpe_base + (size_t)key * 128 + (ld_src[j] & 0xFFFF)
-                                                   : kv_base + (size_t)key * kv_pitch + ld_src[j];
+      const int key = whole ? t * PF_TOK + ld_tok[j] : min(t * PF_TOK + ld_tok[j], L - 1);
+      const char* src = ld_ptr[j] + (size_t)key * ld_step[j];
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                        (__attribute__((address_space(3))) void*)(dst + (wave + j * PF_NW) * 1024),
                                        16, 0, 0);
@@ -246,115 +249,120 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
     __builtin_amdgcn_s_barrier();            // tile t visible to all waves, tile t-1 no longer read
     if (t + 2 < ntiles) issue(t + 2);
     const int key0 = t * PF_TOK;
-    // a block takes part while the tile holds a key <= its last query (wave-uniform)
-    bool active[PF_QB];
+    // Blocks take part while the tile holds a key <= their last query; later blocks have later
+    // queries, so the idle ones are the first `idle` blocks (wave-uniform).  The tile body is
+    // compiled once per value of `idle`: no branch sits between the MFMAs.
+    int idle = 0;
 #pragma unroll
-    for (int qb = 0; qb < PF_QB; ++qb) active[qb] = key0 <= qbase[qb] + 15;
-    if (!active[PF_QB - 1]) continue;        // later blocks have later queries: nothing to do for this wave
-    const unsigned tile = lds_base + (unsigned)((t % PF_NSTAGE) * PF_TILE_BYTES);
+    for (int qb = 0; qb < PF_QB; ++qb) idle += (key0 > qbase[qb] + 15) ? 1 : 0;
+    if (idle == PF_QB) continue;
+    auto tile_body = [&](auto first) {
+      constexpr int QB0 = decltype(first)::value;
+      const unsigned tile = lds_base + (unsigned)((t % PF_NSTAGE) * PF_TILE_BYTES);
 
-    // ---- scores: pieces 16..39 of the row (k-steps 4..9 of the 40-piece row) ----
-    f32x4 sacc[PF_QB][2];
-#pragma unroll
-    for (int qb = 0; qb < PF_QB; ++qb) sacc[qb][0] = sacc[qb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-    {
-      constexpr int NQ = KS * 2;             // K fragments, in order (ks, tb)
-      bf16x8 kf[4];
-      const unsigned ka[2] = {tile + k_off[0], tile + k_off[1]};
-      static_for<4>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        constexpr int ks = i / 2 + 4, tb = i % 2;
-        lds_read_b128<(ks >> 1) * 128 + tb * (16 * PF_RC * 16)>(kf[i], ka[ks & 1]);
-      });
-      static_for<NQ>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        constexpr int ks = i / 2, tb = i % 2;
-        constexpr int ahead = (NQ - 1 - i) < 3 ? (NQ - 1 - i) : 3;
-        lds_wait<ahead>(kf[i & 3]);
-#pragma unroll
-        for (int qb = 0; qb < PF_QB; ++qb)
-          if (active[qb])
+      // ---- scores: pieces 16..39 of the row (k-steps 4..9 of the 40-piece row) ----
+      f32x4 sacc[PF_QB][2];
+  #pragma unroll
+      for (int qb = QB0; qb < PF_QB; ++qb) sacc[qb][0] = sacc[qb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+      {
+        constexpr int NQ = KS * 2;             // K fragments, in order (ks, tb)
+        bf16x8 kf[4];
+        const unsigned ka[2] = {tile + k_off[0], tile + k_off[1]};
+        static_for<4>([&](auto ic) {
+          constexpr int i = decltype(ic)::value;
+          constexpr int ks = i / 2 + 4, tb = i % 2;
+          lds_read_b128<(ks >> 1) * 128 + tb * (16 * PF_RC * 16)>(kf[i], ka[ks & 1]);
+        });
+        static_for<NQ>([&](auto ic) {
+          constexpr int i = decltype(ic)::value;
+          constexpr int ks = i / 2, tb = i % 2;
+          constexpr int ahead = (NQ - 1 - i) < 3 ? (NQ - 1 - i) : 3;
+          lds_wait<ahead>(kf[i & 3]);
+  #pragma unroll
+          for (int qb = QB0; qb < PF_QB; ++qb)
             sacc[qb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i & 3], qreg[qb][ks], sacc[qb][tb], 0, 0, 0);
-        if constexpr (i + 4 < NQ) {
-          constexpr int ks2 = (i + 4) / 2 + 4, tb2 = (i + 4) % 2;
-          lds_read_b128<(ks2 >> 1) * 128 + tb2 * (16 * PF_RC * 16)>(kf[i & 3], ka[ks2 & 1]);
-        }
-      });
-    }
+          if constexpr (i + 4 < NQ) {
+            constexpr int ks2 = (i + 4) / 2 + 4, tb2 = (i + 4) % 2;
+            lds_read_b128<(ks2 >> 1) * 128 + tb2 * (16 * PF_RC * 16)>(kf[i & 3], ka[ks2 & 1]);
+          }
+        });
+      }
 
-    // ---- causal mask + online softmax (lane = one query per block; keys key0 + 16 tb + 4 q4 + i) ----
-    bf16x8 pb[PF_QB];
-#pragma unroll
-    for (int qb = 0; qb < PF_QB; ++qb) {
-      if (!active[qb]) continue;
-      if (key0 + PF_TOK - 1 > qbase[qb]) {   // the tile reaches past this block's first query
-        const int query = qbase[qb] + j16;
-#pragma unroll
+      // ---- causal mask + online softmax (lane = one query per block; keys key0 + 16 tb + 4 q4 + i) ----
+      bf16x8 pb[PF_QB];
+  #pragma unroll
+      for (int qb = QB0; qb < PF_QB; ++qb) {
+        if (key0 + PF_TOK - 1 > qbase[qb]) {   // the tile reaches past this block's first query
+          const int query = qbase[qb] + j16;
+  #pragma unroll
+          for (int tb = 0; tb < 2; ++tb)
+  #pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (key0 + 16 * tb + 4 * q4 + i > query) sacc[qb][tb][i] = -INFINITY;
+        }
+        float mx = sacc[qb][0][0];
+  #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (key0 + 16 * tb + 4 * q4 + i > query) sacc[qb][tb][i] = -INFINITY;
-      }
-      float mx = sacc[qb][0][0];
-#pragma unroll
-      for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, sacc[qb][tb][i]);
-      mx *= a.scale_log2;
-      if (__any(mx > m_run[qb] + LAZY)) {
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[qb], mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);   // 0 on the first tile
-        l_run[qb] *= alpha;
-        m_run[qb] = m_new;
-#pragma unroll
-        for (int d = 0; d < DB; ++d) acc[qb][d] *= alpha;
-      }
-      float psum = 0.f;
-#pragma unroll
-      for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
+  #pragma unroll
+          for (int i = 0; i < 4; ++i) mx = fmaxf(mx, sacc[qb][tb][i]);
+        mx *= a.scale_log2;
+        if (__any(mx > m_run[qb] + LAZY)) {
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = fmaxf(m_run[qb], mx);
+          const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);   // 0 on the first tile
+          l_run[qb] *= alpha;
+          m_run[qb] = m_new;
+  #pragma unroll
+          for (int d = 0; d < DB; ++d) acc[qb][d] *= alpha;
+        }
+        float psum = 0.f;
+  #pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+  #pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][tb][i], a.scale_log2, -m_run[qb]));
+            sacc[qb][tb][i] = p;
+            psum += p;
+          }
+        l_run[qb] += psum;
+  #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][tb][i], a.scale_log2, -m_run[qb]));
-          sacc[qb][tb][i] = p;
-          psum += p;
+          pb[qb][i] = (bf16_t)sacc[qb][0][i];
+          pb[qb][4 + i] = (bf16_t)sacc[qb][1][i];
         }
-      l_run[qb] += psum;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        pb[qb][i] = (bf16_t)sacc[qb][0][i];
-        pb[qb][4 + i] = (bf16_t)sacc[qb][1][i];
       }
-    }
 
-    // ---- output: O^T += V^T P^T, V = pieces 0..15 of the row ----
-    {
-      u32x2 vlo[4], vhi[4];
-      unsigned va[4];
-#pragma unroll
-      for (int d = 0; d < 4; ++d) va[d] = tile + v_off[d];
-      static_for<4>([&](auto ic) {
-        constexpr int d = decltype(ic)::value;
-        lds_read_tr_b64<0>(vlo[d], va[d & 3]);
-        lds_read_tr_b64<16 * PF_RC * 16>(vhi[d], va[d & 3]);
-      });
-      static_for<DB>([&](auto ic) {
-        constexpr int d = decltype(ic)::value;
-        constexpr int ahead = (DB - 1 - d) < 3 ? (DB - 1 - d) : 3;
-        lds_wait<2 * ahead>(vlo[d & 3], vhi[d & 3]);
-        const u32x4 v4 = {vlo[d & 3][0], vlo[d & 3][1], vhi[d & 3][0], vhi[d & 3][1]};
-#pragma unroll
-        for (int qb = 0; qb < PF_QB; ++qb)
-          if (active[qb])
+      // ---- output: O^T += V^T P^T, V = pieces 0..15 of the row ----
+      {
+        u32x2 vlo[4], vhi[4];
+        unsigned va[4];
+  #pragma unroll
+        for (int d = 0; d < 4; ++d) va[d] = tile + v_off[d];
+        static_for<4>([&](auto ic) {
+          constexpr int d = decltype(ic)::value;
+          lds_read_tr_b64<0>(vlo[d], va[d & 3]);
+          lds_read_tr_b64<16 * PF_RC * 16>(vhi[d], va[d & 3]);
+        });
+        static_for<DB>([&](auto ic) {
+          constexpr int d = decltype(ic)::value;
+          constexpr int ahead = (DB - 1 - d) < 3 ? (DB - 1 - d) : 3;
+          lds_wait<2 * ahead>(vlo[d & 3], vhi[d & 3]);
+          const u32x4 v4 = {vlo[d & 3][0], vlo[d & 3][1], vhi[d & 3][0], vhi[d & 3][1]};
+  #pragma unroll
+          for (int qb = QB0; qb < PF_QB; ++qb)
             acc[qb][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v4), pb[qb], acc[qb][d], 0, 0, 0);
-        if constexpr (d + 4 < DB) {
-          constexpr int d2 = d + 4;
-          lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d & 3], va[d2 & 3]);
-          lds_read_tr_b64<(d2 >> 2) * 128 + 16 * PF_RC * 16>(vhi[d & 3], va[d2 & 3]);
-        }
-      });
-    }
+          if constexpr (d + 4 < DB) {
+            constexpr int d2 = d + 4;
+            lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d & 3], va[d2 & 3]);
+            lds_read_tr_b64<(d2 >> 2) * 128 + 16 * PF_RC * 16>(vhi[d & 3], va[d2 & 3]);
+          }
+        });
+      }
+    };
+    static_for<PF_QB>([&](auto ic) {
+      if (idle == decltype(ic)::value) tile_body(ic);
+    });
   }
 
   // ---- normalise and store: lane holds query qbase + j16, dims 16 d + 4 q4 .. +4 ----
