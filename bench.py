@@ -231,6 +231,30 @@ def main():
                "dense_transform_TFLOPs_hi_lo": 4.0 * n_used * pt * w.d_c * w.d_c / (us_dense * 1e-6) / 1e12,
                "variance_fractions": [float(f) for f in frac]}
 
+    # Prefill of one context-length sequence with un-absorbed MLA (the other phase of Sec. 4.5;
+    # MFMA-bound, not part of the decode step): key/value up-projection + causal attention
+    prefill = None
+    if not args.skip_extras and w.dtype == "bf16" and w.d_n == 128 and w.d_v == 128 and w.d_r == 64:
+        Lp = int(lens_np.max())
+        shape_p = pl.make_shape(wl.scaled(w, B=1, g=1))
+        gen = torch.Generator(device=dev); gen.manual_seed(w.seed)
+        pq_nope = torch.randn((Lp, w.H, w.d_n), device=dev, dtype=tdt, generator=gen)
+        pq_pe = torch.randn((Lp, w.H, w.d_r), device=dev, dtype=tdt, generator=gen)
+        pc = torch.randn((Lp, w.d_c), device=dev, dtype=tdt, generator=gen)
+        pk = torch.randn((Lp, w.d_r), device=dev, dtype=tdt, generator=gen)
+        pcu = torch.tensor([0, Lp], dtype=torch.int32, device=dev)
+        pws_b = tp.tpla_prefill_workspace_bytes(shape_p, Lp)
+        pws = torch.empty(pws_b, dtype=torch.uint8, device=dev)
+        po = torch.empty((Lp, w.H, w.d_v), dtype=torch.float32, device=dev)
+        W_UK0, W_UV0 = pl.to_device(model["W_UK"], w.dtype), pl.to_device(model["W_UV"], w.dtype)
+        us_pf = timed(lambda: tp.tpla_prefill_attention(shape_p, pq_nope, pq_pe, pc, pk, W_UK0, W_UV0, pcu, Lp, Lp,
+                                                        pws, pws_b, po), reps=3)
+        flop = 2.0 * (w.d_n + w.d_r + w.d_v) * w.H * (Lp * (Lp + 1) / 2) + 2.0 * Lp * w.d_c * w.H * (w.d_n + w.d_v)
+        prefill = {"tokens": Lp, "heads": w.H, "ms": us_pf * 1e-3, "TFLOP/s": flop / (us_pf * 1e-6) / 1e12,
+                   "bound": "mfma", "peak_TFLOP/s": 2500.0, "frac": flop / (us_pf * 1e-6) / 1e12 / 2500.0,
+                   "flop_counted": "causal half of QK^T and PV plus the key/value up-projection"}
+        del pq_nope, pq_pe, pws, po
+
     # MLA under head-split tensor parallelism, one device's share: the same H heads
     # over the unsliced 576-wide cache (the MLA pool is exactly the g = 1 layout).
     # Its time against one TPLA slice is this box's counterpart of the paper's ratio.
@@ -267,6 +291,7 @@ def main():
                       "output_projection(W_O, not in the step)": us_wo,
                       "one_device_share": us_absorb / w.g + us_decode + us_combine},
         "pca_calibration": pca,
+        "prefill_mla": prefill,
         "transform": {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "kernel": "decode split kernel, all g slices in one launch (tpla_decode_shards)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -143,15 +143,23 @@ struct PrefillArgs {
   const int32_t* cu;      // [B + 1]
   float* o;               // [T, H, 128]
   int H;
+  int n_qt;        // query tiles of the longest sequence
+  int head_group;  // divides H
   float scale_log2;
 };
 
-// grid: (query tiles of the longest sequence, H, sequences)
+// grid: (query tiles of the longest sequence x H, sequences).  Order inside a sequence: groups of
+// head_group heads; inside a group the query tiles from last (longest key range) to first, the
+// heads of the group innermost.  The workgroups in flight then share the keys and values of a
+// few heads (they stay in the last-level cache) and the grid ends on short work items.
 __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(PrefillArgs a) {
   extern __shared__ u32x4 smem[];
-  const int seq = blockIdx.z, h = blockIdx.y;
+  const int seq = blockIdx.y;
+  const int per_group = a.n_qt * a.head_group;
+  const int hg = blockIdx.x / per_group, rem = blockIdx.x - hg * per_group;
+  const int h = hg * a.head_group + rem % a.head_group;
+  const int qt = a.n_qt - 1 - rem / a.head_group;          // long key ranges first
   const int t0 = a.cu[seq], L = a.cu[seq + 1] - t0;
-  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;     // long key ranges first
   if (qt * PF_QT >= L) return;
   const int q0 = qt * PF_QT;
   const int kend = min(L, q0 + PF_QT);                     // keys 0 .. kend-1 are needed
@@ -423,7 +431,10 @@ int launch_prefill_attention(const tpla_shape_t& sh, const void* q_nope, const v
   a.o = o;
   a.H = sh.H;
   a.scale_log2 = sh.sm_scale * 1.4426950408889634f;
-  const dim3 grid((max_seq_len + PF_QT - 1) / PF_QT, sh.H, sh.B);
+  a.n_qt = (max_seq_len + PF_QT - 1) / PF_QT;
+  a.head_group = sh.H % 8 == 0 ? 8 : (sh.H % 4 == 0 ? 4 : (sh.H % 2 == 0 ? 2 : 1));
+  if ((long long)a.n_qt * sh.H > 2147483647LL) return fail(TPLA_ERR_UNSUPPORTED, "grid too large");
+  const dim3 grid((unsigned)(a.n_qt * sh.H), sh.B);
   hipLaunchKernelGGL(prefill_attention_mfma_kernel, grid, dim3(PF_NW * 64), PF_NSTAGE * PF_TILE_BYTES, st, a);
   return check_launch("prefill_attention_mfma_kernel");
 }

@@ -92,3 +92,40 @@ def test_full_size_ragged_g4():
     lens = wl.draw_model_side(w)["seq_lens"]
     order = np.argsort(lens)
     _run_config("ragged_g4", [int(order[0]), int(order[len(order) // 2]), int(order[-1])])
+
+
+def test_full_size_prefill_32k_sampled_tokens():
+    """One 32768-token sequence at 64 heads (the DeepSeek-V3 per-device shape), checked on
+    sampled (token, head) outputs: the oracle's prefill row for a token equals its decode over the
+    prefix, which it can afford for a handful of tokens."""
+    L, H, d_c = 32768, 64, 512
+    print(f"full-size prefill: L={L} H={H}", flush=True)
+    dev = "cuda"
+    rng = np.random.default_rng([7, 41])
+    shape = tp.TplaShape(1, H, d_c, 1, 64, 128, 128, 64, tp.TPLA_BF16, 1.0 / np.sqrt(192.0))
+    c = wl.to_storage(rng.standard_normal((L, d_c), dtype=np.float32), "bf16")
+    k_pe = wl.to_storage(rng.standard_normal((L, 64), dtype=np.float32), "bf16")
+    W_UK = wl.to_storage(rng.standard_normal((H, 128, d_c)) * 0.02, "bf16")
+    W_UV = wl.to_storage(rng.standard_normal((H, d_c, 128)) * 0.02, "bf16")
+    gen = torch.Generator(device=dev); gen.manual_seed(7)
+    q_nope = torch.randn((L, H, 128), device=dev, dtype=torch.bfloat16, generator=gen)
+    q_pe = torch.randn((L, H, 64), device=dev, dtype=torch.bfloat16, generator=gen)
+    ws_b = tp.tpla_prefill_workspace_bytes(shape, L)
+    ws = torch.empty(ws_b, dtype=torch.uint8, device=dev)
+    o = torch.full((L, H, 128), float("nan"), dtype=torch.float32, device=dev)
+    tp.tpla_prefill_attention(shape, q_nope, q_pe, pl.to_device(c, "bf16"), pl.to_device(k_pe, "bf16"),
+                              pl.to_device(W_UK, "bf16"), pl.to_device(W_UV, "bf16"),
+                              torch.tensor([0, L], dtype=torch.int32, device=dev), L, L, ws, ws_b, o)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(o).all())
+    print("  kernel done", flush=True)
+    c64, k64 = wl.as_f64(c, "bf16"), wl.as_f64(k_pe, "bf16")
+    heads = [0, 21, 63]
+    Wk, Wv = wl.as_f64(W_UK, "bf16")[heads], wl.as_f64(W_UV, "bf16")[heads]
+    for t in (0, 1, 127, 128, 4097, 20000, L - 1):
+        qn = q_nope[t, heads].double().cpu().numpy()[None]
+        qp = q_pe[t, heads].double().cpu().numpy()[None]
+        ref = orc.mla_naive(qn, qp, Wk, Wv, [c64[:t + 1]], [k64[:t + 1]], 1.0 / np.sqrt(192.0))[0]
+        got = o[t, heads].cpu().numpy()
+        assert rel_err(got, ref) <= TOL["bf16"], t
+        print(f"  token {t}: rel err {rel_err(got, ref):.2e}", flush=True)
