@@ -127,6 +127,8 @@ constexpr int PF_TOK = 32;                 // keys per tile
 constexpr int PF_NSTAGE = 3;
 constexpr int PF_RC = 40;                  // 16-byte pieces per tile row: V 16, K 16, k_pe 8
 constexpr int PF_NW = 4;
+constexpr int PF_VRING = 4;               // V fragments in flight ahead of the output MFMAs
+constexpr int PF_KRING = 8;               // K fragments in flight ahead of the score MFMAs
 constexpr int PF_QB = 2;                   // blocks of 16 queries per wave
 constexpr int PF_QT = PF_NW * PF_QB * 16;  // queries per workgroup
 constexpr int PF_TC = PF_TOK * PF_RC;      // pieces per tile
@@ -274,9 +276,9 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
       for (int qb = QB0; qb < PF_QB; ++qb) sacc[qb][0] = sacc[qb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
       {
         constexpr int NQ = KS * 2;             // K fragments, in order (ks, tb)
-        bf16x8 kf[4];
+        bf16x8 kf[PF_KRING];
         const unsigned ka[2] = {tile + k_off[0], tile + k_off[1]};
-        static_for<4>([&](auto ic) {
+        static_for<PF_KRING>([&](auto ic) {
           constexpr int i = decltype(ic)::value;
           constexpr int ks = i / 2 + 4, tb = i % 2;
           lds_read_b128<(ks >> 1) * 128 + tb * (16 * PF_RC * 16)>(kf[i], ka[ks & 1]);
@@ -284,17 +286,28 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
         static_for<NQ>([&](auto ic) {
           constexpr int i = decltype(ic)::value;
           constexpr int ks = i / 2, tb = i % 2;
-          constexpr int ahead = (NQ - 1 - i) < 3 ? (NQ - 1 - i) : 3;
-          lds_wait<ahead>(kf[i & 3]);
+          constexpr int ahead = (NQ - 1 - i) < PF_KRING - 1 ? (NQ - 1 - i) : PF_KRING - 1;
+          lds_wait<ahead>(kf[i % PF_KRING]);
   #pragma unroll
           for (int qb = QB0; qb < PF_QB; ++qb)
-            sacc[qb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i & 3], qreg[qb][ks], sacc[qb][tb], 0, 0, 0);
-          if constexpr (i + 4 < NQ) {
-            constexpr int ks2 = (i + 4) / 2 + 4, tb2 = (i + 4) % 2;
-            lds_read_b128<(ks2 >> 1) * 128 + tb2 * (16 * PF_RC * 16)>(kf[i & 3], ka[ks2 & 1]);
+            sacc[qb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i % PF_KRING], qreg[qb][ks], sacc[qb][tb], 0, 0, 0);
+          if constexpr (i + PF_KRING < NQ) {
+            constexpr int ks2 = (i + PF_KRING) / 2 + 4, tb2 = (i + PF_KRING) % 2;
+            lds_read_b128<(ks2 >> 1) * 128 + tb2 * (16 * PF_RC * 16)>(kf[i % PF_KRING], ka[ks2 & 1]);
           }
         });
       }
+
+      // the first V fragments start now, so that their LDS latency passes under the softmax arithmetic
+      u32x2 vlo[PF_VRING], vhi[PF_VRING];
+      unsigned va[4];
+  #pragma unroll
+      for (int d = 0; d < 4; ++d) va[d] = tile + v_off[d];
+      static_for<PF_VRING>([&](auto ic) {
+        constexpr int d = decltype(ic)::value;
+        lds_read_tr_b64<(d >> 2) * 128>(vlo[d], va[d & 3]);
+        lds_read_tr_b64<(d >> 2) * 128 + 16 * PF_RC * 16>(vhi[d], va[d & 3]);
+      });
 
       // ---- causal mask + online softmax (lane = one query per block; keys key0 + 16 tb + 4 q4 + i) ----
       bf16x8 pb[PF_QB];
@@ -343,27 +356,18 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
 
       // ---- output: O^T += V^T P^T, V = pieces 0..15 of the row ----
       {
-        u32x2 vlo[4], vhi[4];
-        unsigned va[4];
-  #pragma unroll
-        for (int d = 0; d < 4; ++d) va[d] = tile + v_off[d];
-        static_for<4>([&](auto ic) {
-          constexpr int d = decltype(ic)::value;
-          lds_read_tr_b64<0>(vlo[d], va[d & 3]);
-          lds_read_tr_b64<16 * PF_RC * 16>(vhi[d], va[d & 3]);
-        });
         static_for<DB>([&](auto ic) {
           constexpr int d = decltype(ic)::value;
-          constexpr int ahead = (DB - 1 - d) < 3 ? (DB - 1 - d) : 3;
-          lds_wait<2 * ahead>(vlo[d & 3], vhi[d & 3]);
-          const u32x4 v4 = {vlo[d & 3][0], vlo[d & 3][1], vhi[d & 3][0], vhi[d & 3][1]};
+          constexpr int ahead = (DB - 1 - d) < PF_VRING - 1 ? (DB - 1 - d) : PF_VRING - 1;
+          lds_wait<2 * ahead>(vlo[d % PF_VRING], vhi[d % PF_VRING]);
+          const u32x4 v4 = {vlo[d % PF_VRING][0], vlo[d % PF_VRING][1], vhi[d % PF_VRING][0], vhi[d % PF_VRING][1]};
   #pragma unroll
           for (int qb = QB0; qb < PF_QB; ++qb)
             acc[qb][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v4), pb[qb], acc[qb][d], 0, 0, 0);
-          if constexpr (d + 4 < DB) {
-            constexpr int d2 = d + 4;
-            lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d & 3], va[d2 & 3]);
-            lds_read_tr_b64<(d2 >> 2) * 128 + 16 * PF_RC * 16>(vhi[d & 3], va[d2 & 3]);
+          if constexpr (d + PF_VRING < DB) {
+            constexpr int d2 = d + PF_VRING;
+            lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d % PF_VRING], va[d2 & 3]);
+            lds_read_tr_b64<(d2 >> 2) * 128 + 16 * PF_RC * 16>(vhi[d % PF_VRING], va[d2 & 3]);
           }
         });
       }
