@@ -91,6 +91,22 @@ def test_other_entry_points_argument_checks():
     assert _code(tp.tpla_append_token_sliced, s, A, A, [2.0, -1.0], 1e-6, A, [A, A]) == -2
     assert _code(tp.tpla_append_token_sliced, s, A, A, None, -1.0, A, [A, A]) == -2
     assert _code(tp.tpla_append_token_sliced, s, A, A, None, 1e-6, A, [A, A + 4]) == -3
+    # output projection, PCA moments, prefill
+    assert _code(tp.tpla_output_projection, s, A, None, 64, A, 1 << 20, A) == -1
+    assert _code(tp.tpla_output_projection, s, A, A, 0, A, 1 << 20, A) == -2
+    assert tp.tpla_latent_moments_workspace_bytes(s, 0) == 0 and tp.tpla_latent_moments_workspace_bytes(s, 40) > 0
+    assert _code(tp.tpla_latent_moments, s, None, None, None, 4, A, 1 << 30, A, A) == -1
+    assert _code(tp.tpla_latent_moments, s, A, None, None, 0, A, 1 << 30, A, A) == -2
+    assert _code(tp.tpla_latent_moments, s, A, None, None, 4, A, 16, A, A) == -4
+    assert _code(tp.tpla_latent_moments, s, A, None, None, 4, A + 4, 1 << 30, A, A) == -3
+    sp = _shape(d_n=128, d_v=128)
+    assert tp.tpla_prefill_workspace_bytes(sp, 100) == 100 * 64 * 256 * 2 and tp.tpla_prefill_workspace_bytes(sp, 0) == 0
+    assert _code(tp.tpla_prefill_attention, sp, A, A, A, A, A, A, None, 8, 8, A, 1 << 30, A) == -1
+    assert _code(tp.tpla_prefill_attention, sp, A, A, A, A, A, A, A, 0, 8, A, 1 << 30, A) == -2
+    assert _code(tp.tpla_prefill_attention, sp, A, A, A, A, A, A, A, 8, 0, A, 1 << 30, A) == -2
+    assert _code(tp.tpla_prefill_attention, sp, A, A, A, A, A, A, A, 8, 8, A, 64, A) == -4
+    assert _code(tp.tpla_prefill_attention, sp, A, A + 2, A, A, A, A, A, 8, 8, A, 1 << 30, A) == -3
+    assert _code(tp.tpla_prefill_attention, _shape(d_n=64), A, A, A, A, A, A, A, 8, 8, A, 1 << 30, A) == -7
     # empty work is accepted without a launch
     tp.tpla_transform_latent(s, tp.TPLA_U_IDENTITY, 0, None, None, A, A, 0, 1)
     tp.tpla_transform_latent_paged(s, tp.TPLA_U_IDENTITY, None, None, A, [A, A], None, 0)
