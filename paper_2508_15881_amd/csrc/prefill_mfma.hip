@@ -174,9 +174,11 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
   const int j16 = lane & 15, q4 = lane >> 4;
 
   // ---- direct-to-LDS bookkeeping: instruction k of a tile fills pieces [64k, 64k+64) ----
+  // Tiles are issued in order, each exactly once, so every lane keeps a running source pointer per
+  // instruction (two VALU adds per load) instead of multiplying the key index out every time.
   int ld_tok[PF_CPT];
-  const char* ld_ptr[PF_CPT];    // source of the piece for key ld_tok of tile 0 ...
-  unsigned ld_step[PF_CPT];      // ... plus this many bytes per tile, and per key (clamped last tile)
+  const char* ld_cur[PF_CPT];    // source of this lane's piece in the next tile to be issued
+  unsigned ld_step[PF_CPT];      // bytes from one key to the next in that source
   const char* kv_base = reinterpret_cast<const char*>(a.kv) + ((size_t)t0 * a.H + h) * 512;
   const char* kpe_base = reinterpret_cast<const char*>(a.k_pe) + (size_t)t0 * 128;
   const unsigned kv_pitch = (unsigned)a.H * 512u;
@@ -188,19 +190,28 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
     ld_tok[j] = tok;
     const bool from_kv = cg < 32;                          // V and no-RoPE K; else the shared RoPE key
     ld_step[j] = from_kv ? kv_pitch : 128u;
-    ld_ptr[j] = from_kv ? kv_base + cg * 16 : kpe_base + (cg - 32) * 16;
+    ld_cur[j] = (from_kv ? kv_base + cg * 16 : kpe_base + (cg - 32) * 16) + (size_t)tok * ld_step[j];
   }
   auto issue = [&](int t) {
     char* dst = reinterpret_cast<char*>(smem) + (t % PF_NSTAGE) * PF_TILE_BYTES;
-    const bool whole = (t + 1) * PF_TOK <= L;
+    if ((t + 1) * PF_TOK <= L) {                           // scalar: every key of the tile exists
 #pragma unroll
-    for (int j = 0; j < PF_CPT; ++j) {
-      // keys past the end of the sequence repeat its last key: finite values, masked below
-      const int key = whole ? t * PF_TOK + ld_tok[j] : min(t * PF_TOK + ld_tok[j], L - 1);
-      const char* src = ld_ptr[j] + (size_t)key * ld_step[j];
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)(dst + (wave + j * PF_NW) * 1024),
-                                       16, 0, 0);
+      for (int j = 0; j < PF_CPT; ++j) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ld_cur[j],
+                                         (__attribute__((address_space(3))) void*)(dst + (wave + j * PF_NW) * 1024),
+                                         16, 0, 0);
+        ld_cur[j] += (size_t)PF_TOK * ld_step[j];
+      }
+    } else {
+      // last tile of the sequence: keys past its end repeat the last key (finite values, masked below)
+#pragma unroll
+      for (int j = 0; j < PF_CPT; ++j) {
+        const int over = max(0, t * PF_TOK + ld_tok[j] - (L - 1));
+        const char* src = ld_cur[j] - (size_t)over * ld_step[j];
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(dst + (wave + j * PF_NW) * 1024),
+                                         16, 0, 0);
+      }
     }
   };
 
