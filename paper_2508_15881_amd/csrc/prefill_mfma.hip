@@ -253,11 +253,15 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[qb][ks]));   // complete before the loop
 
   f32x4 acc[PF_QB][DB];
-  float m_run[PF_QB], l_run[PF_QB];
+  // lsum: the softmax denominators, accumulated on the matrix cores as one more output row block
+  // whose A operand is all ones (every row of it holds sum_key P[key, query]): the weights that
+  // reach the output are the bf16-rounded ones, and these are the ones summed
+  float m_run[PF_QB];
+  f32x4 lsum[PF_QB];
 #pragma unroll
   for (int qb = 0; qb < PF_QB; ++qb) {
     m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
+    lsum[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int d = 0; d < DB; ++d) acc[qb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
@@ -343,21 +347,18 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
           mx = fmaxf(mx, __shfl_xor(mx, 32));
           const float m_new = fmaxf(m_run[qb], mx);
           const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);   // 0 on the first tile
-          l_run[qb] *= alpha;
+          lsum[qb] *= alpha;
           m_run[qb] = m_new;
   #pragma unroll
           for (int d = 0; d < DB; ++d) acc[qb][d] *= alpha;
         }
-        float psum = 0.f;
   #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
   #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][tb][i], a.scale_log2, -m_run[qb]));
             sacc[qb][tb][i] = p;
-            psum += p;
           }
-        l_run[qb] += psum;
   #pragma unroll
         for (int i = 0; i < 4; ++i) {
           pb[qb][i] = (bf16_t)sacc[qb][0][i];
@@ -381,6 +382,10 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
             lds_read_tr_b64<(d2 >> 2) * 128 + 16 * PF_RC * 16>(vhi[d % PF_VRING], va[d2 & 3]);
           }
         });
+        const u32x4 one4 = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  #pragma unroll
+        for (int qb = QB0; qb < PF_QB; ++qb)
+          lsum[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, one4), pb[qb], lsum[qb], 0, 0, 0);
       }
     };
     static_for<PF_QB>([&](auto ic) {
@@ -391,8 +396,7 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
   // ---- normalise and store: lane holds query qbase + j16, dims 16 d + 4 q4 .. +4 ----
 #pragma unroll
   for (int qb = 0; qb < PF_QB; ++qb) {
-    float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 16);
-    l_tot += __shfl_xor(l_tot, 32);
+    const float l_tot = lsum[qb][0];
     const int query = qbase[qb] + j16;
     if (query < L) {
       const float inv = 1.0f / l_tot;
