@@ -91,6 +91,11 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_page
     int n_wg = device_cu_count() * per_cu;
     if (n_wg > 1024) n_wg = 1024;     // the merge handles at most 1024 partial results per sequence
     const long long most = (long long)n_shards * sh.B * max_pages;
+    // Small batches: a workgroup's fixed costs (queries, first tiles, partial result) want at least
+    // 8 pages behind them, but never fewer workgroups than compute units (measured at 16 x 4096
+    // tokens: 256 workgroups of 8 pages 26 us, 512 of 4 pages 31 us, 128 of 16 pages 38 us).
+    const int cus = device_cu_count();
+    if (most / 8 < n_wg) n_wg = most / 8 > cus ? (int)(most / 8) : (cus < n_wg ? cus : n_wg);
     if (n_wg > most) n_wg = (int)most;
     p.balanced = 1;
     p.n_wg = n_wg;
