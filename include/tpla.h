@@ -169,6 +169,8 @@ size_t tpla_workspace_bytes(const tpla_shape_t* shape, int32_t max_pages_per_seq
  * q_lat_i [B,H,d_c/g], q_pe [B,H,d_r] in shape->dtype; block_table int32
  * [B, max_pages_per_seq]; seq_lens int32 [B]; o_lat_i float [B,H,d_c/g];
  * lse_i float [B,H] or NULL.
+ * A length below 0 or beyond max_pages_per_seq * page_tokens is clipped to that range by the kernels
+ * (the result is then that of the clipped length; the block table is never read past its row).
  */
 int tpla_decode_shard(const tpla_shape_t* shape,
                       const void* q_lat_i, const void* q_pe, const void* shard_pool,
@@ -231,7 +233,7 @@ int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void
  * normalised latent, as cached), k_pe [T, d_r], W_UK [H, d_n, d_c],
  * W_UV [H, d_c, d_v] in shape->dtype (original basis: no U); o float
  * [T, H, d_v].  max_seq_len: an upper bound of the longest sequence (queries
- * beyond it are not computed).  workspace:
+ * beyond it are not computed).  Row ranges are clipped to [0, T) by the kernel.  workspace:
  * tpla_prefill_workspace_bytes() bytes (the projected keys and values, bf16).
  * shape->g, page_tokens are not used.  Implemented for bf16 with d_n = d_v =
  * 128, d_r = 64, d_c a multiple of 128 up to 512 (TPLA_ERR_UNSUPPORTED

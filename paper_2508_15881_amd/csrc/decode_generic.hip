@@ -23,7 +23,7 @@ __global__ void __launch_bounds__(GEN_THREADS) decode_generic_kernel(DecodeArgs 
   const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
   const int shard = vb / a.B, b = vb % a.B;
   const int h = blockIdx.y;
-  const int L = a.seq_lens[b];
+  const int L = seq_len_clipped(a, b);
   const int pt = a.page_tokens;
   const int n_pages = (L + pt - 1) / pt;
   const int p0 = s * a.pages_per_split;
@@ -115,7 +115,7 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
   __shared__ int cnt_sh;
   const int vb = blockIdx.x / a.H, h = blockIdx.x % a.H;   // vb = slice * B + sequence
   const int b = vb % a.B;
-  const int L = a.seq_lens[b];
+  const int L = seq_len_clipped(a, b);
   const int n_pages = (L + a.page_tokens - 1) / a.page_tokens;
   const int dl = a.dl;
   float* out = a.o_lat + ((size_t)vb * a.H + h) * dl;

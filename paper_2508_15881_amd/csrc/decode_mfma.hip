@@ -288,7 +288,7 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
   extern __shared__ u32x4 smem[];        // NSTAGE tiles
   const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
   const int shard = vb / a.B, b = vb % a.B;
-  const int L = a.seq_lens[b];
+  const int L = seq_len_clipped(a, b);
   const int n_pages = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
   const int p0 = s * a.pages_per_split;
   if (p0 >= n_pages) return;
@@ -312,7 +312,7 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
   int total = 0;
   for (int v0 = 0; v0 < n_v; v0 += 64) {
     const int v = v0 + lane;
-    int pg = (v < n_v) ? (a.seq_lens[v % a.B] + PAGE_TOKENS - 1) / PAGE_TOKENS : 0;
+    int pg = (v < n_v) ? (seq_len_clipped(a, v % a.B) + PAGE_TOKENS - 1) / PAGE_TOKENS : 0;
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) pg += __shfl_xor(pg, m);
     total += pg;
@@ -321,7 +321,7 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
   int base = 0;
   for (int v0 = 0; v0 < n_v; v0 += 64) {
     const int v = v0 + lane;
-    const int L = (v < n_v) ? a.seq_lens[v % a.B] : 0;
+    const int L = (v < n_v) ? seq_len_clipped(a, v % a.B) : 0;
     const int pg = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
     int incl = pg;                               // inclusive prefix sum over the wave
 #pragma unroll

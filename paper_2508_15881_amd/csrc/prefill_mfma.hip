@@ -145,6 +145,7 @@ struct PrefillArgs {
   const int32_t* cu;      // [B + 1]
   float* o;               // [T, H, 128]
   int H;
+  int T;           // packed tokens in all
   int n_qt;        // query tiles of the longest sequence
   int head_group;  // divides H
   float scale_log2;
@@ -161,7 +162,8 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
   const int hg = blockIdx.x / per_group, rem = blockIdx.x - hg * per_group;
   const int h = hg * a.head_group + rem % a.head_group;
   const int qt = a.n_qt - 1 - rem / a.head_group;          // long key ranges first
-  const int t0 = a.cu[seq], L = a.cu[seq + 1] - t0;
+  // row ranges are clipped to [0, T): a malformed cu_seqlens gives wrong numbers, never an access outside the buffers
+  const int t0 = min(max(a.cu[seq], 0), a.T), L = min(max(a.cu[seq + 1], t0), a.T) - t0;
   if (qt * PF_QT >= L) return;
   const int q0 = qt * PF_QT;
   const int kend = min(L, q0 + PF_QT);                     // keys 0 .. kend-1 are needed
@@ -449,6 +451,7 @@ int launch_prefill_attention(const tpla_shape_t& sh, const void* q_nope, const v
   a.cu = cu_seqlens;
   a.o = o;
   a.H = sh.H;
+  a.T = T;
   a.scale_log2 = sh.sm_scale * 1.4426950408889634f;
   a.n_qt = (max_seq_len + PF_QT - 1) / PF_QT;
   a.head_group = sh.H % 8 == 0 ? 8 : (sh.H % 4 == 0 ? 4 : (sh.H % 2 == 0 ? 2 : 1));

@@ -57,6 +57,15 @@ bool decode_mfma_supported(const tpla_shape_t& sh);
 // unit (0 = unknown).
 int decode_mfma_blocks_per_cu(const tpla_shape_t& sh);
 int launch_decode_mfma(const DecodeArgs& a, hipStream_t st);
+// Length of sequence b as every decode kernel uses it: clipped to what its block-table row can
+// address, so a length that disagrees with max_pages_per_seq gives wrong numbers, never a read
+// past the table.
+__device__ __forceinline__ int seq_len_clipped(const DecodeArgs& a, int b) {
+  const long long cap = (long long)a.max_pages * a.page_tokens;
+  const long long L = a.seq_lens[b];
+  return (int)(L < 0 ? 0 : (L > cap ? cap : L));
+}
+
 int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st);
 int launch_decode_merge(const DecodeArgs& a, hipStream_t st);
 

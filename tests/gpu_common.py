@@ -49,7 +49,7 @@ def build_shard_problem(w, lens, seed_model=None, permute=True, slack_pages=3, p
             "max_pages": max_pages, "rows64": rows64}
 
 
-def run_decode_shard(prob, n_splits=0):
+def run_decode_shard(prob, n_splits=0, lens_override=None):
     w = prob["w"]
     shape = pl.make_shape(w)
     dev = "cuda"
@@ -57,7 +57,7 @@ def run_decode_shard(prob, n_splits=0):
     q_pe = pl.to_device(prob["q_pe"], w.dtype)
     pool = pl.to_device(prob["pool"], w.dtype)
     bt = torch.from_numpy(prob["bt"]).to(dev)
-    lens = torch.from_numpy(prob["lens"]).to(dev)
+    lens = torch.from_numpy(prob["lens"] if lens_override is None else np.asarray(lens_override, dtype=np.int32)).to(dev)
     # host-side sanity before any launch: ids inside the pool, lengths inside the table
     assert prob["bt"].min() >= 0 and prob["bt"].max() < prob["pool"].shape[0]
     assert int(prob["lens"].max()) <= prob["max_pages"] * w.page_tokens

@@ -150,6 +150,25 @@ def test_decode_shard_paging_is_bit_invariant():
     assert np.all(np.isfinite(oa))                                     # NaN tails / spare pages never leak
 
 
+def test_lengths_beyond_the_table_are_clipped_not_followed():
+    """A length that disagrees with max_pages_per_seq (or cu_seqlens that run past T) is clipped by
+    the kernels to what the tables can address: same result as the clipped input, no stray read."""
+    _say("lengths beyond the tables are clipped")
+    for dtype in ("bf16", "f32"):
+        w = wl.scaled(wl.CONFIGS["dsv3_4k"], dtype=dtype, H=16)
+        prob = build_shard_problem(w, [256, 128], permute=True)          # table rows hold 4 pages
+        good = run_decode_shard(prob)
+        wild = run_decode_shard(prob, lens_override=[1 << 20, 128])
+        neg = run_decode_shard(prob, lens_override=[256, -7])
+        assert np.array_equal(good[0], wild[0]) and np.array_equal(good[1], wild[1])
+        assert np.array_equal(good[0][0], neg[0][0]) and np.all(neg[0][1] == 0) and np.all(np.isneginf(neg[1][1]))
+    p = _prefill_problem(3, [40, 24], 2, 128)
+    ref, _ = _run_prefill(p, 2, 128, 2, 40)
+    p2 = dict(p); p2["cu"] = np.array([0, 40, 9999], dtype=np.int32)      # second range runs past T = 64
+    got, _ = _run_prefill(p2, 2, 128, 2, 40)
+    assert np.array_equal(ref, got)
+
+
 def test_decode_shard_softmax_properties_at_long_context():
     # one long sequence (spans many tiles and splits): weights sum to one and
     # the output stays inside the rows' column range
