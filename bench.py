@@ -209,6 +209,22 @@ def main():
         wo_out = torch.empty((w.B, w.d_model), dtype=torch.float32, device=dev)
         us_wo = timed(lambda: tp.tpla_output_projection(shape, step.o, W_O, w.d_model, wo_ws, wo_ws_b, wo_out))
 
+    # the same step replayed from a HIP graph (launch overhead of its four kernels removed);
+    # informational: the timed region above launches eagerly so that its kernels can be bracketed
+    us_graph = float("nan")
+    if not args.skip_extras:
+        graph = step.capture(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt, lens, mu)
+        for _ in range(20):
+            graph.replay()
+        torch.cuda.synchronize()
+        n_rep = min(args.steps, 300)
+        tg = time.perf_counter()
+        for _ in range(n_rep):
+            graph.replay()
+        torch.cuda.synchronize()
+        us_graph = (time.perf_counter() - tg) * 1e6 / n_rep
+        del graph
+
     # PCA calibration path (Sec. 4.3.2), not part of the step: moments of the cached latents on
     # the GPU, eigen-solve on the host, cache turned into the dense basis on the matrix cores
     pca = None
@@ -289,7 +305,8 @@ def main():
         "stages_us": {"absorb": us_absorb, "decode_shards(all slices, split+merge)": us_decode_all,
                       "decode_shard(one slice, split+merge)": us_decode, "combine": us_combine,
                       "output_projection(W_O, not in the step)": us_wo,
-                      "one_device_share": us_absorb / w.g + us_decode + us_combine},
+                      "one_device_share": us_absorb / w.g + us_decode + us_combine,
+                      "layer_step_replayed_from_hip_graph": us_graph},
         "pca_calibration": pca,
         "prefill_mla": prefill,
         "transform": {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9},

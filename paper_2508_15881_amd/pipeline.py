@@ -85,6 +85,19 @@ class DecodeStep:
         return self.o
 
 
+    def capture(self, q_nope, q_pe, W_UK_t, W_UV_t, shard_pools, block_table, seq_lens, mu=None, fused=True):
+        """The layer-step as a HIP graph (torch.cuda.CUDAGraph): one eager run first (kernel
+        attributes are set on first use), then the capture.  Replaying it reads the same input
+        tensors and writes self.o, self.o_lat, self.lse; the library allocates nothing and records
+        no memset, so the step is capturable as it is.  tpla_profile_enable must be off."""
+        self.run(q_nope, q_pe, W_UK_t, W_UV_t, shard_pools, block_table, seq_lens, mu, fused)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.run(q_nope, q_pe, W_UK_t, W_UV_t, shard_pools, block_table, seq_lens, mu, fused)
+        return graph
+
+
 def transform_weights(shape, mode, signs, U, W_UK, W_UV):
     """W_UK [H,d_n,d_c] -> W_UK U (last axis); W_UV [H,d_c,d_v] -> U^T W_UV (middle axis)."""
     W_UK_t = torch.empty_like(W_UK)

@@ -486,6 +486,44 @@ def test_output_projection(dtype, Bn, H, d_v, D):
     assert rel_err(out.cpu().numpy(), ref) <= 1e-5
 
 
+def test_layer_step_as_hip_graph_replays_like_eager():
+    """The step captured in a HIP graph: several replays, eager work and synchronisations between
+    them, new inputs written into the same tensors; every replay equals the eager result bit for bit."""
+    _say("layer step as HIP graph")
+    w = wl.scaled(wl.CONFIGS["dsv3_4k"], B=3, H=16, context=0)
+    lens = [200, 64, 1000]
+    dev = "cuda"
+    rng = np.random.default_rng(5)
+    shape = pl.make_shape(w)
+    pages = (np.asarray(lens) + 63) // 64
+    P = int(pages.sum())
+    bt = np.zeros((w.B, int(pages.max())), dtype=np.int32); k = 0
+    for b in range(w.B):
+        bt[b, :pages[b]] = np.arange(k, k + pages[b]); k += pages[b]
+    pools = [torch.randn((P, 64, w.dl + w.d_r), device=dev).to(torch.bfloat16) for _ in range(w.g)]
+    W_UK_t = (torch.randn((w.H, w.d_n, w.d_c), device=dev) * 0.02).to(torch.bfloat16)
+    W_UV_t = (torch.randn((w.H, w.d_c, w.d_v), device=dev) * 0.02).to(torch.bfloat16)
+    q_nope = torch.randn((w.B, w.H, w.d_n), device=dev).to(torch.bfloat16)
+    q_pe = torch.randn((w.B, w.H, w.d_r), device=dev).to(torch.bfloat16)
+    bt_t, lens_t = torch.from_numpy(bt).to(dev), torch.tensor(lens, dtype=torch.int32, device=dev)
+    mu = [2.0, 2.0]
+    step = pl.DecodeStep(shape, int(pages.max()))
+    graph = step.capture(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt_t, lens_t, mu)
+    eager = pl.DecodeStep(shape, int(pages.max()))
+    for it in range(4):
+        if it:      # new queries and a shorter third sequence, written into the captured tensors
+            q_nope.copy_(torch.randn_like(q_nope, dtype=torch.float32).to(torch.bfloat16))
+            q_pe.copy_(torch.randn_like(q_pe, dtype=torch.float32).to(torch.bfloat16))
+            lens_t.copy_(torch.tensor([200, 64, 1000 - 100 * it], dtype=torch.int32))
+        ref = eager.run(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt_t, lens_t, mu).clone()
+        torch.cuda.synchronize()
+        step.o.fill_(float("nan")); step.o_lat.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(step.o, ref), it
+        assert torch.equal(step.o_lat, eager.o_lat) and torch.equal(step.lse, eager.lse)
+
+
 # ------------------------------------------------------------ PCA calibration (Sec. 4.3.2)
 @pytest.mark.parametrize("dtype,d_c,d_r,pt,P", [("bf16", 512, 64, 64, 40), ("bf16", 256, 64, 16, 9), ("bf16", 128, 8, 64, 3),
                                                 ("bf16", 96, 16, 8, 5), ("f32", 64, 16, 64, 4)])
