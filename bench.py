@@ -291,6 +291,27 @@ def main():
         tp.tpla_profile_enable(0)
     mla_bytes = wl.algorithmic_bytes_per_shard(w1, lens_np)
 
+    # How far TPLA's per-slice softmaxes move the block output away from MLA's (Sec. 4.2: the
+    # slices' scores only approximate the global ones), with the cache left in its own basis and
+    # in the Hadamard basis (Sec. 4.3.1).  Information only: the paper gives no per-tensor figure.
+    gap = None
+    if not args.skip_extras and w.g > 1 and (w.d_c & (w.d_c - 1)) == 0:
+        W_UK0, W_UV0 = pl.to_device(model["W_UK"], w.dtype), pl.to_device(model["W_UV"], w.dtype)
+        step1.absorb(q_nope, W_UK0, None)
+        step1.decode(0, q_pe, mla_pool, bt, lens)
+        step1.combine(W_UV0)
+        o_mla = step1.o.double()
+        scratch = [torch.empty_like(p) for p in pools]
+        stepx = pl.DecodeStep(shape, model["max_pages"], 0)
+        gap = {"what": "|o_TPLA - o_MLA|_F / |o_MLA|_F over the batch, mu_i = g"}
+        sg = torch.from_numpy(model["signs"]).to(dev)
+        for name, codex, sx in (("identity", tp.TPLA_U_IDENTITY, None), ("hadamard", tp.TPLA_U_HADAMARD, sg)):
+            Wk, Wv = pl.transform_weights(shape, codex, sx, None, W_UK0, W_UV0)
+            tp.tpla_transform_latent_paged(shape, codex, sx, None, mla_pool, scratch, used, len(used_np))
+            ox = stepx.run(q_nope, q_pe, Wk, Wv, scratch, bt, lens, mu).double()
+            gap[name] = float(torch.linalg.norm(ox - o_mla) / torch.linalg.norm(o_mla))
+        del scratch, stepx
+
     out = {
         "metric": "latent-KV decode GB/s and % HBM roofline; µs per layer-step at 32K ctx",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -307,6 +328,7 @@ def main():
                       "output_projection(W_O, not in the step)": us_wo,
                       "one_device_share": us_absorb / w.g + us_decode + us_combine,
                       "layer_step_replayed_from_hip_graph": us_graph},
+        "tpla_vs_mla_output_gap": gap,
         "pca_calibration": pca,
         "prefill_mla": prefill,
         "transform": {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9},

@@ -724,3 +724,52 @@ def test_whole_path_bf16_scaled_configs(name, lens):
     assert rel_err(step.o_lat.cpu().numpy(), ref["O_lat"]) <= TOL["bf16"]
     assert rel_err(o.cpu().numpy(), ref["o"]) <= TOL["bf16"]
     assert np.max(np.abs(step.lse.cpu().numpy() - ref["lse"])) <= 2e-2
+
+
+def test_tpla_vs_mla_gap_matches_the_oracles_gap():
+    """TPLA (g = 2) is not MLA: its per-slice softmaxes see only part of the score.  The size of
+    that difference, with the cache in its own basis and in the Hadamard basis, measured through
+    the library equals the one the oracle finds (heavy-channel latents as in the Kimi-shaped config)."""
+    _say("TPLA vs MLA output gap")
+    w = wl.scaled(wl.CONFIGS["kimi_32k"], B=3, context=0)
+    lens = [500, 130, 64]
+    dev = "cuda"
+    m = wl.draw_model_side(wl.scaled(w, context=max(lens)))
+    pages = (np.asarray(lens) + 63) // 64
+    P = int(pages.sum())
+    bt = np.zeros((w.B, int(pages.max())), dtype=np.int32); k = 0
+    for b in range(w.B):
+        bt[b, :pages[b]] = np.arange(k, k + pages[b]); k += pages[b]
+    shape, shape1 = pl.make_shape(w), pl.make_shape(wl.scaled(w, g=1))
+    mla_pool = torch.full((P, 64, w.d_c + w.d_r), float("nan"), dtype=torch.bfloat16, device=dev)
+    c64, k64 = [], []
+    for b in range(w.B):
+        c, kp = wl.draw_sequence(w, b, lens[b], heavy=m["heavy"])
+        slots = torch.from_numpy(wl.slot_mapping(bt[b, :pages[b]], lens[b], 64)).to(dev)
+        tp.tpla_write_mla_cache(shape, pl.to_device(c, "bf16"), pl.to_device(kp, "bf16"), slots, lens[b], -1.0, mla_pool)
+        c64.append(wl.as_f64(c, "bf16")); k64.append(wl.as_f64(kp, "bf16"))
+    q_nope, q_pe = pl.to_device(m["q_nope"], "bf16"), pl.to_device(m["q_pe"], "bf16")
+    W_UK, W_UV = pl.to_device(m["W_UK"], "bf16"), pl.to_device(m["W_UV"], "bf16")
+    bt_t, lens_t = torch.from_numpy(bt).to(dev), torch.tensor(lens, dtype=torch.int32, device=dev)
+    used = torch.arange(P, dtype=torch.int32, device=dev)
+    step1 = pl.DecodeStep(shape1, int(pages.max()))
+    step1.absorb(q_nope, W_UK, None); step1.decode(0, q_pe, mla_pool, bt_t, lens_t); step1.combine(W_UV)
+    o_mla = step1.o.double().cpu().numpy()
+    f64 = {k_: wl.as_f64(m[k_], "bf16") for k_ in ("q_nope", "q_pe", "W_UK", "W_UV")}
+    ref_mla = orc.mla_absorbed(f64["q_nope"], f64["q_pe"], f64["W_UK"], f64["W_UV"], c64, k64, w.sm_scale)
+    assert rel_err(o_mla, ref_mla) <= TOL["bf16"]
+    mu = [2.0, 2.0]
+    gaps = {}
+    for name, code, signs_np in (("identity", tp.TPLA_U_IDENTITY, None), ("hadamard", tp.TPLA_U_HADAMARD, m["signs"])):
+        signs = None if signs_np is None else torch.from_numpy(signs_np).to(dev)
+        Wk, Wv = pl.transform_weights(shape, code, signs, None, W_UK, W_UV)
+        pools = [torch.full((P, 64, w.dl + w.d_r), float("nan"), dtype=torch.bfloat16, device=dev) for _ in range(w.g)]
+        tp.tpla_transform_latent_paged(shape, code, signs, None, mla_pool, pools, used, P)
+        o = pl.DecodeStep(shape, int(pages.max())).run(q_nope, q_pe, Wk, Wv, pools, bt_t, lens_t, mu).double().cpu().numpy()
+        U64 = None if signs_np is None else orc.hadamard_U(w.d_c, signs_np)
+        ref = orc.tpla_decode(f64["q_nope"], f64["q_pe"], f64["W_UK"], f64["W_UV"], c64, k64, w.g, w.sm_scale, U=U64, mu=mu)["o"]
+        got_gap = np.linalg.norm(o - o_mla) / np.linalg.norm(o_mla)
+        ref_gap = np.linalg.norm(ref - ref_mla) / np.linalg.norm(ref_mla)
+        gaps[name] = (got_gap, ref_gap)
+        assert abs(got_gap - ref_gap) <= 0.05 * ref_gap + 5e-3, (name, got_gap, ref_gap)
+    print("  gap (library, oracle):", gaps, flush=True)
