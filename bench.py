@@ -68,7 +68,7 @@ def cpu_baseline(w, model, budget_s=12.0):
             break
     esz = 4 if w.dtype == "f32" else 2
     gbs = done_tokens * w.g * (w.dl + w.d_r) * esz / t_total / 1e9
-    return {"value": gbs, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+    return {"value": gbs, "unit": "GB/s", "cores": int(threads), "host_cpu_count": os.cpu_count(), "kind": "oracle",
             "sample": "%d of %d sequences (%d tokens), whole oracle step incl. its dense U products, %.1f s"
                       % (n_seq, w.B, done_tokens, t_total)}
 
@@ -185,6 +185,23 @@ def main():
     achieved = launch_bytes / (kern_avg_ms * 1e-3) / 1e9
     one_avg_ms = float(np.mean(one_ms))
     one_achieved = shard_bytes / (one_avg_ms * 1e-3) / 1e9
+
+    # what this machine delivers to a kernel that only reads (same pool, 128-bit streaming loads):
+    # boxes differ by several per cent, and so does this ceiling
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    ceil_ms = []
+    if not args.skip_extras:
+        nb = pools[0].numel() * pools[0].element_size()
+        for i in range(12):
+            ev0.record(); tp.tpla_stream_read(pools[i % w.g], nb, sink); ev1.record()
+            torch.cuda.synchronize()
+            if i >= 2:
+                ceil_ms.append(ev0.elapsed_time(ev1))
+    ceiling = (pools[0].numel() * pools[0].element_size()) / (float(np.median(ceil_ms)) * 1e-3) / 1e9 if ceil_ms else None
+    # modelled traffic of one split launch beyond the cache rows: queries, page table, lengths
+    # (read by every workgroup's item) and the float partial results (written once)
+    n_items = step.ws_bytes // (w.H * (w.dl + 2) * 4)          # partial-result slots of the plan
+    all_traffic = launch_bytes + n_items * w.H * ((w.dl + w.d_r) * esz + (w.dl + 2) * 4) + w.g * w.B * model["max_pages"] * 4
 
     # stage breakdown (untimed region, events on torch's current stream = the launch stream)
     def timed(fn, reps=20):
@@ -338,7 +355,9 @@ def main():
                      "launch_us": kern_avg_ms * 1e3, "launches": len(kern_ms),
                      "launch_us_min": float(np.min(kern_ms)) * 1e3, "launch_us_median": float(np.median(kern_ms)) * 1e3,
                      "launch_us_first10": float(np.mean(kern_ms[:10])) * 1e3, "launch_us_last10": float(np.mean(kern_ms[-10:])) * 1e3,
-                     "algorithmic_bytes_per_launch": launch_bytes},
+                     "algorithmic_bytes_per_launch": launch_bytes, "modelled_all_traffic_bytes": all_traffic,
+                     "streaming_read_ceiling_GB/s": ceiling,
+                     "frac_of_streaming_read_ceiling": (achieved / ceiling) if ceiling else None},
         "roofline_one_slice": {"bound": "hbm", "kernel": "decode split kernel, one slice per launch (tpla_decode_shard)",
                                "achieved": one_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                "frac": one_achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_ONE_SLICE.get(w.name),

@@ -292,6 +292,15 @@ int tpla_pca_basis(int32_t d_c, int32_t g, int64_t n_rows, const double* sum, co
 int tpla_profile_enable(int32_t max_records);
 int tpla_profile_collect(float* ms, int32_t capacity, int32_t* n_records);
 
+/*
+ * Measurement aid for the memory-bound decode of Sec. 4.5: reads the first
+ * bytes - bytes % 20480 bytes of the DEVICE buffer buf once, with 128-bit
+ * streaming loads and nothing else, so that a caller can time what the box
+ * delivers to a pure reader and set the decode kernel's rate against it.
+ * sink: 4 writable device bytes (never written in practice).
+ */
+int tpla_stream_read(const void* buf, size_t bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ EXPORTS = (
     "tpla_combine_shards", "tpla_profile_enable", "tpla_profile_collect", "tpla_workspace_bytes_all",
     "tpla_decode_shards", "tpla_append_token_sliced", "tpla_output_projection",
     "tpla_output_projection_workspace_bytes", "tpla_latent_moments_workspace_bytes", "tpla_latent_moments",
-    "tpla_pca_basis", "tpla_prefill_workspace_bytes", "tpla_prefill_attention",
+    "tpla_pca_basis", "tpla_prefill_workspace_bytes", "tpla_prefill_attention", "tpla_stream_read",
 )
 
 
@@ -102,6 +102,8 @@ def load_library():
     lib.tpla_prefill_workspace_bytes.argtypes = [shp, i64]
     lib.tpla_prefill_attention.restype = ctypes.c_int
     lib.tpla_prefill_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, ctypes.c_size_t, vp, vp]
+    lib.tpla_stream_read.restype = ctypes.c_int
+    lib.tpla_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.tpla_pca_basis.restype = ctypes.c_int
     lib.tpla_pca_basis.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp]
     _lib = lib
@@ -268,6 +270,10 @@ def tpla_pca_basis(d_c, g, n_rows, sum_host, gram_host):
     _check(load_library().tpla_pca_basis(d_c, g, n_rows, sum_host.ctypes.data, gram_host.ctypes.data,
                                          U.ctypes.data, eig.ctypes.data, frac.ctypes.data))
     return U, eig, frac
+
+
+def tpla_stream_read(buf, nbytes, sink, stream=None):
+    _check(load_library().tpla_stream_read(_ptr(buf), nbytes, _ptr(sink), _stream(stream)))
 
 
 def tpla_profile_enable(max_records):

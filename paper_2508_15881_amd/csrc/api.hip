@@ -491,5 +491,11 @@ int tpla_profile_collect(float* ms, int32_t capacity, int32_t* n_records) {
   return TPLA_OK;
 }
 
+int tpla_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink) return fail(TPLA_ERR_NULL, "buf/sink is NULL");
+  if (!aligned16(buf) || !aligned16(sink)) return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  return launch_stream_read(buf, bytes, sink, (hipStream_t)stream);
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

@@ -220,4 +220,35 @@ int launch_decode_merge(const DecodeArgs& a, hipStream_t st) {
   return check_launch("decode_merge_kernel");
 }
 
+// ---------------------------------------------------------------------------
+// Measurement aid: the plainest possible pass over a buffer -- every lane reads
+// 16 bytes per step with the streaming hint, chunks of 20 KB dealt to the
+// workgroups round-robin, five loads in flight per lane -- so that the decode
+// kernel's rate can be set against what the same box delivers to a reader that
+// does nothing else.  The XOR of everything read is stored only if it matches
+// a value it cannot have, which keeps the loads alive.
+__global__ void __launch_bounds__(256) stream_read_kernel(const u32x4* __restrict__ p, size_t n_chunks,
+                                                          unsigned* __restrict__ sink) {
+  constexpr int CH = 5;
+  unsigned acc = 0;
+  for (size_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const u32x4* s = p + c * (CH * 256) + threadIdx.x;
+    u32x4 v[CH];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) v[j] = __builtin_nontemporal_load(s + j * 256);
+#pragma unroll
+    for (int j = 0; j < CH; ++j) acc += v[j][0] ^ v[j][1] ^ v[j][2] ^ v[j][3];
+  }
+  if (acc == 0x9E3779B9u && n_chunks == ~(size_t)0) sink[0] = acc;
+}
+
+int launch_stream_read(const void* buf, size_t bytes, void* sink, hipStream_t st) {
+  const size_t n_chunks = bytes / (5 * 256 * 16);
+  if (n_chunks == 0) return TPLA_OK;
+  const int grid = device_cu_count() * 2;
+  hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)grid), dim3(256), 0, st, static_cast<const u32x4*>(buf),
+                     n_chunks, static_cast<unsigned*>(sink));
+  return check_launch("stream_read_kernel");
+}
+
 }  // namespace tpla

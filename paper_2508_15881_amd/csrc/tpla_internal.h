@@ -110,6 +110,8 @@ int launch_prefill_attention(const tpla_shape_t& sh, const void* q_nope, const v
                              const void* k_pe, const void* W_UK, const void* W_UV, const int32_t* cu_seqlens,
                              int T, int max_seq_len, void* kv_workspace, float* o, hipStream_t st);
 
+int launch_stream_read(const void* buf, size_t bytes, void* sink, hipStream_t st);
+
 // PCA calibration: see pca.hip.
 int latent_moments_splits(const tpla_shape_t& sh, int64_t n_pages);
 size_t latent_moments_workspace(const tpla_shape_t& sh, int64_t n_pages);
