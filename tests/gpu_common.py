@@ -17,6 +17,14 @@ def rel_err(x, r):
     return float(np.max(np.abs(x - r)) / (den if den > 0 else 1.0))
 
 
+def elementwise_err(x, r):
+    """max over elements of |x - r| / (|r| + rms(r)): the per-element companion of rel_err."""
+    x = np.asarray(x, dtype=np.float64)
+    r = np.asarray(r, dtype=np.float64)
+    rms = np.sqrt(np.mean(r * r))
+    return float(np.max(np.abs(x - r) / (np.abs(r) + (rms if rms > 0 else 1.0))))
+
+
 def build_shard_problem(w, lens, seed_model=None, permute=True, slack_pages=3, poison=True, rng_extra=0):
     """Seeded inputs of one shard's decode at widths of workload `w` with the
     given sequence lengths: queries, a paged pool holding the shard's rows and

@@ -9,7 +9,7 @@ import paper_2508_15881_amd as tp
 from paper_2508_15881_amd import pipeline as pl
 from paper_2508_15881_amd import workloads as wl
 from oracle import tpla_oracle as orc
-from gpu_common import TOL, build_shard_problem, oracle_decode_shard, rel_err, run_decode_shard
+from gpu_common import elementwise_err, TOL, build_shard_problem, oracle_decode_shard, rel_err, run_decode_shard
 
 pytestmark = pytest.mark.gpu
 
@@ -42,6 +42,7 @@ def test_decode_shard_bf16_matches_oracle(name, w, lens, n_splits):
     ro, rl = oracle_decode_shard(prob)
     nz = np.asarray(lens) > 0
     assert rel_err(o, ro) <= TOL["bf16"]
+    assert elementwise_err(o, ro) <= TOL["bf16"]         # |x - r| <= tol (|r| + rms(r)) for every element
     assert np.max(np.abs(lse[nz] - rl[nz])) <= 1e-2
     assert np.all(o[~nz] == 0) and np.all(np.isneginf(lse[~nz]))
 
