@@ -151,6 +151,28 @@ def test_decode_shard_paging_is_bit_invariant():
     assert np.all(np.isfinite(oa))                                     # NaN tails / spare pages never leak
 
 
+def test_peaky_softmax_exercises_the_rescale_path():
+    """Queries 16x larger: scores spread over hundreds of log2 units, the running reference of the
+    online softmax moves on most tiles and almost all weight sits on a few tokens."""
+    _say("peaky softmax (decode and prefill)")
+    for w, lens in ((DSV3, [700, 65]), (wl.scaled(DSV3, g=1), [300])):
+        prob = build_shard_problem(w, lens)
+        prob["q_lat"] = wl.to_storage(wl.as_f64(prob["q_lat"], "bf16") * 16.0, "bf16")
+        prob["q_pe"] = wl.to_storage(wl.as_f64(prob["q_pe"], "bf16") * 16.0, "bf16")
+        for n_splits in (0, 2):
+            o, lse = run_decode_shard(prob, n_splits)
+            ro, rl = oracle_decode_shard(prob)
+            assert rel_err(o, ro) <= TOL["bf16"]
+            assert np.max(np.abs(lse - rl) / np.maximum(1.0, np.abs(rl))) <= 1e-2
+    p = _prefill_problem(9, [300, 77], 2, 256)
+    p["q_nope"] = wl.to_storage(wl.as_f64(p["q_nope"], "bf16") * 16.0, "bf16")
+    p["q_pe"] = wl.to_storage(wl.as_f64(p["q_pe"], "bf16") * 16.0, "bf16")
+    f64 = {k: wl.as_f64(p[k], "bf16") for k in ("q_nope", "q_pe", "c", "k_pe", "W_UK", "W_UV")}
+    ref = orc.mla_prefill(f64["q_nope"], f64["q_pe"], f64["W_UK"], f64["W_UV"], f64["c"], f64["k_pe"], p["cu"], 1.0 / np.sqrt(192.0))
+    o, _ = _run_prefill(p, 2, 256, 2, 300)
+    assert rel_err(o, ref) <= TOL["bf16"]
+
+
 def test_lengths_beyond_the_table_are_clipped_not_followed():
     """A length that disagrees with max_pages_per_seq (or cu_seqlens that run past T) is clipped by
     the kernels to what the tables can address: same result as the clipped input, no stray read."""
