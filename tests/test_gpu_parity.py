@@ -796,3 +796,90 @@ def test_tpla_vs_mla_gap_matches_the_oracles_gap():
         gaps[name] = (got_gap, ref_gap)
         assert abs(got_gap - ref_gap) <= 0.05 * ref_gap + 5e-3, (name, got_gap, ref_gap)
     print("  gap (library, oracle):", gaps, flush=True)
+
+
+def test_prefill_then_decode_end_to_end():
+    """The two phases of Sec. 4.5 in sequence, every stage through the library: prompt latents
+    normalised and written to the MLA cache, causal MLA prefill over the prompts, the cache turned
+    into the Hadamard basis and sliced, the first generated token appended with the per-slice
+    RMSNorm, one TPLA decode step and the output projection -- against the oracle doing the same
+    (it rounds to bf16 wherever the library stores bf16)."""
+    _say("prefill -> cache -> transform -> append -> decode -> W_O, end to end")
+    w = wl.scaled(wl.CONFIGS["dsv3_32k"], B=2, H=16, context=0, rms_prefill=True, d_model=256)
+    lens, pt, dev, eps = [150, 70], 64, "cuda", 1e-6
+    m = wl.draw_model_side(wl.scaled(w, context=max(lens) + 1))
+    shape = pl.make_shape(w)
+    rng = np.random.default_rng([w.seed, 77])
+    pages = (np.asarray(lens) + 1 + pt - 1) // pt                      # room for one more token
+    P = int(pages.sum())
+    bt = np.zeros((w.B, int(pages.max())), dtype=np.int32); k = 0
+    for b in range(w.B):
+        bt[b, :pages[b]] = np.arange(k, k + pages[b]); k += pages[b]
+    # ---- prompt: raw latents -> MLA cache (global RMSNorm), packed normalised rows for the prefill
+    mla_pool = torch.full((P, pt, w.d_c + w.d_r), float("nan"), dtype=torch.bfloat16, device=dev)
+    packed_c, packed_k, c64, k64, all_slots = [], [], [], [], []
+    for b in range(w.B):
+        c_raw, kp = wl.draw_sequence(w, b, lens[b])
+        slots = wl.slot_mapping(bt[b, :pages[b]], lens[b], pt)
+        tp.tpla_write_mla_cache(shape, pl.to_device(c_raw, "bf16"), pl.to_device(kp, "bf16"),
+                                torch.from_numpy(slots).to(dev), lens[b], eps, mla_pool)
+        c64.append(orc.round_to_bf16(orc.rms_norm_unit(wl.as_f64(c_raw, "bf16"), eps)))
+        k64.append(wl.as_f64(kp, "bf16"))
+        all_slots.append(slots)
+    torch.cuda.synchronize()
+    flat = mla_pool.view(P * pt, w.d_c + w.d_r)[torch.from_numpy(np.concatenate(all_slots)).long().to(dev)]
+    got_c, ref_c = wl.as_f64(pl.from_device_bits(flat[:, :w.d_c].contiguous()), "bf16"), np.concatenate(c64)
+    assert np.all(np.abs(got_c - ref_c) <= 2.0 ** -8 * np.abs(ref_c))          # float RMSNorm vs float64: at most one bf16 step
+    T = sum(lens)
+    qn_p = wl.to_storage(rng.standard_normal((T, w.H, w.d_n)), "bf16")
+    qp_p = wl.to_storage(rng.standard_normal((T, w.H, w.d_r)), "bf16")
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    shape_p = pl.make_shape(wl.scaled(w, g=1))
+    ws_b = tp.tpla_prefill_workspace_bytes(shape_p, T)
+    ws = torch.empty(ws_b, dtype=torch.uint8, device=dev)
+    o_p = torch.full((T, w.H, w.d_v), float("nan"), dtype=torch.float32, device=dev)
+    W_UK, W_UV = pl.to_device(m["W_UK"], "bf16"), pl.to_device(m["W_UV"], "bf16")
+    tp.tpla_prefill_attention(shape_p, pl.to_device(qn_p, "bf16"), pl.to_device(qp_p, "bf16"), flat[:, :w.d_c].contiguous(),
+                              flat[:, w.d_c:].contiguous(), W_UK, W_UV, torch.from_numpy(cu).to(dev), T, max(lens), ws, ws_b, o_p)
+    f64 = {k_: wl.as_f64(m[k_], "bf16") for k_ in ("W_UK", "W_UV", "q_nope", "q_pe")}
+    ref_p = orc.mla_prefill(wl.as_f64(qn_p, "bf16"), wl.as_f64(qp_p, "bf16"), f64["W_UK"], f64["W_UV"],
+                            np.concatenate(c64), np.concatenate(k64), cu, w.sm_scale)
+    torch.cuda.synchronize()
+    assert rel_err(o_p.cpu().numpy(), ref_p) <= TOL["bf16"]
+    # ---- hand-over to decode: Hadamard basis, slices, one appended token per sequence
+    signs_np = m["signs"]
+    signs = torch.from_numpy(signs_np).to(dev)
+    U64 = orc.hadamard_U(w.d_c, signs_np)
+    W_UK_t, W_UV_t = pl.transform_weights(shape, tp.TPLA_U_HADAMARD, signs, None, W_UK, W_UV)
+    pools = [torch.full((P, pt, w.dl + w.d_r), float("nan"), dtype=torch.bfloat16, device=dev) for _ in range(w.g)]
+    used = torch.arange(P, dtype=torch.int32, device=dev)
+    tp.tpla_transform_latent_paged(shape, tp.TPLA_U_HADAMARD, signs, None, mla_pool, pools, used, P)
+    c_new = wl.to_storage(rng.standard_normal((w.B, w.d_c)) * 3.0, "bf16")        # already in the U basis, unnormalised
+    k_new = wl.to_storage(rng.standard_normal((w.B, w.d_r)), "bf16")
+    new_slots = np.array([bt[b, lens[b] // pt] * pt + lens[b] % pt for b in range(w.B)], dtype=np.int32)
+    tp.tpla_append_token_sliced(shape, pl.to_device(c_new, "bf16"), pl.to_device(k_new, "bf16"), None, eps,
+                                torch.from_numpy(new_slots).to(dev), pools)
+    new_rows = orc.sliced_rms_rows(wl.as_f64(c_new, "bf16"), wl.as_f64(k_new, "bf16"), w.g, None, eps)
+    step = pl.DecodeStep(shape, int(pages.max()))
+    mu = [float(w.g)] * w.g
+    o = step.run(pl.to_device(m["q_nope"], "bf16"), pl.to_device(m["q_pe"], "bf16"), W_UK_t, W_UV_t, pools,
+                 torch.from_numpy(bt).to(dev), torch.tensor([L + 1 for L in lens], dtype=torch.int32, device=dev), mu)
+    W_O = wl.draw_output_weight(w)
+    wo_b = tp.tpla_output_projection_workspace_bytes(shape, w.d_model)
+    wo_ws = torch.empty(max(wo_b, 16), dtype=torch.uint8, device=dev)
+    y = torch.full((w.B, w.d_model), float("nan"), dtype=torch.float32, device=dev)
+    tp.tpla_output_projection(shape, o, pl.to_device(W_O, "bf16"), w.d_model, wo_ws, wo_b, y)
+    torch.cuda.synchronize()
+    # oracle: transformed + rounded prompt rows, then the appended row (its slices, rounded), in the U basis
+    c_dec, k_dec = [], []
+    for b in range(w.B):
+        prompt_t = orc.round_to_bf16(orc.transform_latent(c64[b], U64))
+        app = orc.round_to_bf16(np.concatenate([new_rows[i][b, :w.dl] for i in range(w.g)]))
+        c_dec.append(np.vstack([prompt_t, app[None, :]]))
+        k_dec.append(np.vstack([k64[b], wl.as_f64(k_new, "bf16")[b][None, :]]))
+    Wk_t, Wv_t = orc.reparameterize_weights(f64["W_UK"], f64["W_UV"], U64)
+    Wk_t, Wv_t = orc.round_to_bf16(Wk_t), orc.round_to_bf16(Wv_t)
+    ref = orc.tpla_decode(f64["q_nope"], f64["q_pe"], Wk_t, Wv_t, c_dec, k_dec, w.g, w.sm_scale, U=None, mu=mu)
+    assert rel_err(o.cpu().numpy(), ref["o"]) <= TOL["bf16"]
+    ref_y = orc.output_projection(ref["o"], wl.as_f64(W_O, "bf16"))
+    assert rel_err(y.cpu().numpy(), ref_y) <= TOL["bf16"]
