@@ -17,6 +17,7 @@
 #include "tpla_internal.h"
 
 #include <mutex>
+#include <utility>
 
 namespace tpla {
 
@@ -25,6 +26,16 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <int... I, typename F>
+__device__ __forceinline__ void tm_static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// Compile-time loop: f receives std::integral_constant<int, i>.
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  tm_static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
 
 __device__ __forceinline__ unsigned opaque(unsigned x) {
   asm volatile("" : "+v"(x));
@@ -215,34 +226,37 @@ int launch_transform_paged_mfma(const TransformArgs& t, const tpla_shape_t& sh, 
 
 // ---------------------------------------------------------------------------
 // Dense U (Sec. 4.3.2: the PCA basis) over MLA pages: Y = X U as a GEMM on the
-// matrix cores.  X rows are bf16 (exact operands, loaded from global memory
-// straight into the A layout, 8 consecutive k per lane).  U is float: every
-// entry is split into bf16 hi + lo and both products are accumulated in float,
-// so the result is rounded to bf16 once, from (nearly) the float product.
+// matrix cores.  X rows are bf16 (exact operands).  U is float: every entry is
+// split into bf16 hi + lo and both products are accumulated in float, so the
+// result is rounded to bf16 once, from (nearly) the float product.
 //
-// A workgroup owns 64 output columns: its slab of U (d_c x 64, hi and lo) is
-// converted once into LDS in B-operand order (one 16-byte read per operand,
-// shared by 4 row tiles), then the workgroup walks over blocks of 512 rows, 8
-// waves x 4 tiles of 16 rows.  As in the Hadamard pass, the slab's columns are
-// ordered so that a lane owns 4 adjacent output columns.  The d_c/64 workgroups
-// that read the same rows sit on one XCD (block ids congruent mod 8), so the
-// rows come from that XCD's L2 after the first touch.
+// A workgroup (8 waves) owns 64 output columns: its slab of U (d_c x 64, hi and
+// lo) is converted once into LDS in B-operand order, then the workgroup walks
+// over blocks of 256 rows.  The rows go through LDS as well, in chunks of 64
+// k: the MFMA A layout wants 16 different rows per quarter wave, which read
+// straight from global memory costs one cache access per lane; staged, every
+// global load is a full 128-byte line per 8 lanes and the operand reads are
+// 16-byte LDS reads (pieces XOR-swizzled so that 16 rows hit 16 bank groups).
+// The next chunk is in registers while the current one feeds the MFMAs.
+// As in the Hadamard pass the slab's columns are ordered so that a lane owns 4
+// adjacent output columns.  The d_c/64 workgroups that read the same rows sit
+// on one XCD (block ids congruent mod 8): the rows come from that XCD's L2
+// after the first touch.
 constexpr int DENSE_WAVES = 8;
-constexpr int DENSE_ROWS = DENSE_WAVES * 64;     // rows per workgroup pass
-constexpr int DENSE_AHEAD = 4;                   // k-steps of A operands in flight per tile
-
-// First of the 8 k indices that k group `kg` holds in k-step s.  Steps come in
-// pairs over 64 elements in which a lane owns 16 consecutive ones, 8 per step:
-// its two loads hit the same 32 bytes of a cache line back to back.
-__device__ __forceinline__ int dense_k0(int s, int kg) { return 64 * (s >> 1) + 16 * kg + 8 * (s & 1); }
+constexpr int DENSE_ROWS = DENSE_WAVES * 32;     // rows per workgroup pass: 2 tiles of 16 per wave
+constexpr int DENSE_KC = 64;                     // k per staged chunk (two MFMA k-steps)
+constexpr int DENSE_STAGE_BYTES = DENSE_ROWS * DENSE_KC * 2;
+constexpr int DENSE_LD = DENSE_ROWS * (DENSE_KC / 8) / (DENSE_WAVES * 64);   // 16-byte pieces per thread and chunk
 
 template <int NB>                                 // d_c = 64 NB
 __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_kernel(
     const bf16_t* __restrict__ mla_pool, ShardPools pools, const int32_t* __restrict__ page_ids,
     const float* __restrict__ U, int n_rows, int page_tokens, int page_shift, int d_r, int g,
     int n_row_blocks, int row_workers) {
-  extern __shared__ u32x4 panel[];                 // [2][KS][4][64] operands: hi then lo
-  constexpr int KS = 2 * NB, D_C = 64 * NB;
+  extern __shared__ u32x4 lds4[];                  // [2][KS][4][64] operands (hi, lo), then the staged rows
+  constexpr int KS = 2 * NB, D_C = 64 * NB, NCH = D_C / DENSE_KC;
+  u32x4* const panel = lds4;
+  u32x4* const stage = lds4 + 2 * KS * 256;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = lane & 15, hi = lane >> 4;
   const int id = blockIdx.x;
@@ -250,10 +264,11 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
   const int worker = (id / (8 * NB)) * 8 + (id & 7);
   const int dl = D_C / g;
 
+  // B operand of k-step s, column tile nt: lane (column 4 lo + nt, k group hi) holds k = 32 s + 8 hi + j
   for (int idx = tid; idx < KS * 256; idx += DENSE_WAVES * 64) {
     const int ln = idx & 63, nt = (idx >> 6) & 3, s = idx >> 8;
     const int col = 64 * nb + 4 * (ln & 15) + nt;
-    const int k0 = dense_k0(s, ln >> 4);
+    const int k0 = 32 * s + 8 * (ln >> 4);
     u32x4 ph, pl;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
@@ -266,7 +281,6 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
     panel[idx] = ph;
     panel[KS * 256 + idx] = pl;
   }
-  __syncthreads();
 
   const int in_pitch = D_C + d_r, out_pitch = dl + d_r;
   const int shard = (64 * nb) / dl;
@@ -278,74 +292,150 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
     const size_t page = page_ids ? (size_t)page_ids[pg] : (size_t)pg;
     return page * (size_t)page_tokens + slot;
   };
+  // staging: piece x = tid + 512 j of a chunk is row x / 8, 16-byte piece x % 8; it lives at
+  // piece position (x % 8) ^ ((row >> 1) & 7) of its row
+  int st_row[DENSE_LD];
+  unsigned st_dst[DENSE_LD];
+#pragma unroll
+  for (int j = 0; j < DENSE_LD; ++j) {
+    const int x = tid + DENSE_WAVES * 64 * j;
+    st_row[j] = x >> 3;
+    st_dst[j] = (unsigned)(st_row[j] * 8 + ((x & 7) ^ ((st_row[j] >> 1) & 7)));
+  }
+  // operand reads: row 32 wave + 16 mt + lo, piece 4 ks + hi of the chunk
+  unsigned a_off[2][2];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int r = 32 * wave + 16 * mt + lo;
+      a_off[mt][ks] = (unsigned)(r * 8 + ((4 * ks + hi) ^ ((r >> 1) & 7)));
+    }
+
+  // Physical token index of the 64-row group `grp` of row block rb.  Pages of a multiple of 64
+  // tokens hold a whole group, and the page id then comes through a scalar load: a vector load
+  // here would have to be waited for with vmcnt(0), which drains the row prefetch below.
+  const bool whole_groups = (page_tokens & 63) == 0;
+  auto group_token = [&](int rb, int grp) -> size_t {
+    int row = rb * DENSE_ROWS + 64 * grp;
+    if (row > last) row = rb * DENSE_ROWS;           // group past the end: any valid rows will do, nothing is stored
+    const int pg = __builtin_amdgcn_readfirstlane(page_shift >= 0 ? (row >> page_shift)
+                                                                   : (int)((unsigned)row / (unsigned)page_tokens));
+    const size_t page = page_ids ? (size_t)page_ids[pg] : (size_t)pg;
+    return page * (size_t)page_tokens + (row - pg * page_tokens);
+  };
+  // source of this thread's piece of chunk 0 for its DENSE_LD rows of row block rb
+  auto row_sources = [&](int rb, const bf16_t* (&src)[DENSE_LD]) {
+#pragma unroll
+    for (int j = 0; j < DENSE_LD; ++j) {
+      const size_t tok = whole_groups ? group_token(rb, j) + (st_row[j] - 64 * j)
+                                      : token_of(min(rb * DENSE_ROWS + st_row[j], last));
+      src[j] = mla_pool + tok * in_pitch + 8 * (tid & 7);
+    }
+  };
+  // A whole row block (NCH chunks) per thread in registers: chunk ch of the NEXT block is requested
+  // as soon as chunk ch of this one has been handed to LDS and is used one block later, so a
+  // memory latency has NCH chunks of MFMAs to hide behind.
+  u32x4 blk[NCH][DENSE_LD];
+  // The RoPE keys of the block are copied to every slice by all NB column-block workgroups, each
+  // taking DENSE_ROWS / NB of the rows: 8 lanes per row (a row's first 64 keys are 8 pieces),
+  // fetched one block ahead like the rows.
+  constexpr int KPE_ROWS = DENSE_ROWS / NB;
+  const int kpe_row = nb * KPE_ROWS + (tid >> 3);          // row of the block this thread copies
+  const bool kpe_thread = tid < 8 * KPE_ROWS && 8 * (tid & 7) < d_r;
+  u32x4 kpe_reg = {0u, 0u, 0u, 0u};
+  auto kpe_token = [&](int rb) -> size_t {
+    return whole_groups ? group_token(rb, kpe_row >> 6) + (kpe_row & 63) : token_of(min(rb * DENSE_ROWS + kpe_row, last));
+  };
+  const bf16_t* src[DENSE_LD];
+  if (worker < n_row_blocks) {
+    row_sources(worker, src);
+    static_for<NCH>([&](auto chc) {
+      constexpr int ch = decltype(chc)::value;
+#pragma unroll
+      for (int j = 0; j < DENSE_LD; ++j) blk[ch][j] = *reinterpret_cast<const u32x4*>(src[j] + DENSE_KC * ch);
+    });
+    if (kpe_thread) kpe_reg = *reinterpret_cast<const u32x4*>(mla_pool + kpe_token(worker) * in_pitch + D_C + 8 * (tid & 7));
+  }
 
   for (int rb = worker; rb < n_row_blocks; rb += row_workers) {
-    const int row0 = rb * DENSE_ROWS + wave * 64;
-    if (row0 <= last) {                              // whole waves skip an empty tail
-      // as holder of the data operand: row lo of each tile, k group hi
-      const bf16_t* ap[4];
+    const int row0 = rb * DENSE_ROWS;
+    const int rb_next = rb + row_workers;
+    const bool more = rb_next < n_row_blocks;
+    if (more) row_sources(rb_next, src);
+    f32x4 acc[2][4];
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) ap[mt] = mla_pool + token_of(min(row0 + 16 * mt + lo, last)) * in_pitch;
-      f32x4 acc[4][4];
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+      for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    static_for<NCH>([&](auto chc) {
+      constexpr int ch = decltype(chc)::value;
+      __syncthreads();                               // the previous chunk (and, first time, the slab) is settled
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      u32x4 a[DENSE_AHEAD][4];
+      for (int j = 0; j < DENSE_LD; ++j) stage[st_dst[j]] = blk[ch][j];
+      __syncthreads();
+      if (more) {
 #pragma unroll
-      for (int d = 0; d < DENSE_AHEAD; ++d)
+        for (int j = 0; j < DENSE_LD; ++j) blk[ch][j] = *reinterpret_cast<const u32x4*>(src[j] + DENSE_KC * ch);
+      }
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) a[d][mt] = *reinterpret_cast<const u32x4*>(ap[mt] + dense_k0(d, hi));
+      for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 av[2];
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        bf16x8 av[4];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) av[mt] = __builtin_bit_cast(bf16x8, a[s % DENSE_AHEAD][mt]);
-        if (s + DENSE_AHEAD < KS) {                  // refill this slot
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt)
-            a[s % DENSE_AHEAD][mt] = *reinterpret_cast<const u32x4*>(ap[mt] + dense_k0(s + DENSE_AHEAD, hi));
-        }
-        // keep the refill ahead of this step's MFMAs: left alone, the scheduler sinks the loads
-        // to just before their use and every k-step waits a full memory latency
-        __builtin_amdgcn_sched_barrier(0);
+        for (int mt = 0; mt < 2; ++mt) av[mt] = __builtin_bit_cast(bf16x8, stage[a_off[mt][ks]]);
+        constexpr int s0 = 2 * ch;
+        const int s = s0 + ks;
+        bf16x8 bh[4], bl[4];
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-          const bf16x8 bh = __builtin_bit_cast(bf16x8, panel[(s * 4 + nt) * 64 + lane]);
-          const bf16x8 bl = __builtin_bit_cast(bf16x8, panel[KS * 256 + (s * 4 + nt) * 64 + lane]);
+          bh[nt] = __builtin_bit_cast(bf16x8, panel[(s * 4 + nt) * 64 + lane]);
+          bl[nt] = __builtin_bit_cast(bf16x8, panel[KS * 256 + (s * 4 + nt) * 64 + lane]);
+        }
+        // all hi products first, then all lo: two MFMAs on one accumulator are never adjacent
 #pragma unroll
-          for (int mt = 0; mt < 4; ++mt) {
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], bh, acc[mt][nt], 0, 0, 0);
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], bl, acc[mt][nt], 0, 0, 0);
-          }
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], bh[nt], acc[mt][nt], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], bl[nt], acc[mt][nt], 0, 0, 0);
+      }
+    });
+    // as holder of the result: rows 32 wave + 16 mt + 4 hi + i, columns 64 nb + 4 lo + nt
+    const size_t wave_tok = whole_groups ? group_token(rb, wave >> 1) + 32 * (wave & 1) : 0;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = row0 + 32 * wave + 16 * mt + 4 * hi + i;
+        if (r <= last) {
+          const bf16x2 p0 = __builtin_convertvector(f32x2{acc[mt][0][i], acc[mt][1][i]}, bf16x2);
+          const bf16x2 p1 = __builtin_convertvector(f32x2{acc[mt][2][i], acc[mt][3][i]}, bf16x2);
+          const u32x2 out = {__builtin_bit_cast(unsigned, p0), __builtin_bit_cast(unsigned, p1)};
+          const size_t tok = whole_groups ? wave_tok + (16 * mt + 4 * hi + i) : token_of(r);
+          __builtin_nontemporal_store(out, reinterpret_cast<u32x2*>(out_base + tok * out_pitch));
         }
       }
-      // as holder of the result: rows 16 mt + 4 hi + i, columns 64 nb + 4 lo + nt
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int r = row0 + 16 * mt + 4 * hi + i;
-          if (r <= last) {
-            const bf16x2 p0 = __builtin_convertvector(f32x2{acc[mt][0][i], acc[mt][1][i]}, bf16x2);
-            const bf16x2 p1 = __builtin_convertvector(f32x2{acc[mt][2][i], acc[mt][3][i]}, bf16x2);
-            const u32x2 out = {__builtin_bit_cast(unsigned, p0), __builtin_bit_cast(unsigned, p1)};
-            __builtin_nontemporal_store(out, reinterpret_cast<u32x2*>(out_base + token_of(r) * out_pitch));
-          }
-        }
-    }
-    // the RoPE key of the block's rows goes to every slice (column block 0 only)
-    if (nb == 0) {
-      const int r = rb * DENSE_ROWS + tid;
-      if (r <= last) {
-        const size_t tok = token_of(r);
-        const bf16_t* src = mla_pool + tok * in_pitch + D_C;
-        for (int c = 0; c < d_r; c += 8) {
-          const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + c));
-          for (int i = 0; i < g; ++i)
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<bf16_t*>(pools.p[i]) + tok * out_pitch + dl + c));
-        }
+    // this workgroup's share of the block's RoPE keys, to every slice
+    if (tid < 8 * KPE_ROWS) {
+      const bool live = row0 + kpe_row <= last;
+      const size_t tok = kpe_token(rb);
+      if (live && kpe_thread) {
+        for (int i = 0; i < g; ++i)
+          __builtin_nontemporal_store(kpe_reg, reinterpret_cast<u32x4*>(static_cast<bf16_t*>(pools.p[i]) + tok * out_pitch +
+                                                                       dl + 8 * (tid & 7)));
       }
+      // RoPE widths above 64: the remaining pieces, not prefetched
+      for (int c = 64 + 8 * (tid & 7); live && c < d_r; c += 64) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(mla_pool + tok * in_pitch + D_C + c);
+        for (int i = 0; i < g; ++i)
+          __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<bf16_t*>(pools.p[i]) + tok * out_pitch + dl + c));
+      }
+      if (more && kpe_thread)
+        kpe_reg = *reinterpret_cast<const u32x4*>(mla_pool + kpe_token(rb_next) * in_pitch + D_C + 8 * (tid & 7));
     }
   }
 }
@@ -361,7 +451,7 @@ bool transform_paged_dense_mfma_supported(const TransformArgs& t, const tpla_sha
 template <int NB>
 static int launch_dense_t(const TransformArgs& t, const tpla_shape_t& sh, const void* mla_pool,
                           const ShardPools& pools, const int32_t* page_ids, int64_t n_pages, hipStream_t st) {
-  const size_t smem = (size_t)(2 * NB) * 256 * 16 * 2;
+  const size_t smem = (size_t)(2 * NB) * 256 * 16 * 2 + DENSE_STAGE_BYTES;
   static std::mutex mu;
   static bool opted_in[16] = {};
   int dev = 0;
