@@ -341,11 +341,24 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
   // taking DENSE_ROWS / NB of the rows: 8 lanes per row (a row's first 64 keys are 8 pieces),
   // fetched one block ahead like the rows.
   constexpr int KPE_ROWS = DENSE_ROWS / NB;
-  const int kpe_row = nb * KPE_ROWS + (tid >> 3);          // row of the block this thread copies
-  const bool kpe_thread = tid < 8 * KPE_ROWS && 8 * (tid & 7) < d_r;
-  u32x4 kpe_reg = {0u, 0u, 0u, 0u};
-  auto kpe_token = [&](int rb) -> size_t {
-    return whole_groups ? group_token(rb, kpe_row >> 6) + (kpe_row & 63) : token_of(min(rb * DENSE_ROWS + kpe_row, last));
+  constexpr int KPE_IT = (8 * KPE_ROWS + DENSE_WAVES * 64 - 1) / (DENSE_WAVES * 64);   // rows per thread
+  const bool kpe_piece_ok = 8 * (tid & 7) < d_r;
+  u32x4 kpe_reg[KPE_IT];
+  // row of the block that this thread copies in its it-th turn, or -1
+  auto kpe_row = [&](int it) -> int {
+    const int r = (tid >> 3) + it * (DENSE_WAVES * 8);
+    return r < KPE_ROWS ? nb * KPE_ROWS + r : -1;
+  };
+  auto kpe_token = [&](int rb, int row) -> size_t {
+    return whole_groups ? group_token(rb, row >> 6) + (row & 63) : token_of(min(rb * DENSE_ROWS + row, last));
+  };
+  auto kpe_request = [&](int rb) {
+#pragma unroll
+    for (int it = 0; it < KPE_IT; ++it) {
+      const int row = kpe_row(it);
+      if (row >= 0 && kpe_piece_ok)
+        kpe_reg[it] = *reinterpret_cast<const u32x4*>(mla_pool + kpe_token(rb, row) * in_pitch + D_C + 8 * (tid & 7));
+    }
   };
   const bf16_t* src[DENSE_LD];
   if (worker < n_row_blocks) {
@@ -355,7 +368,7 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
 #pragma unroll
       for (int j = 0; j < DENSE_LD; ++j) blk[ch][j] = *reinterpret_cast<const u32x4*>(src[j] + DENSE_KC * ch);
     });
-    if (kpe_thread) kpe_reg = *reinterpret_cast<const u32x4*>(mla_pool + kpe_token(worker) * in_pitch + D_C + 8 * (tid & 7));
+    kpe_request(worker);
   }
 
   for (int rb = worker; rb < n_row_blocks; rb += row_workers) {
@@ -420,23 +433,24 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
         }
       }
     // this workgroup's share of the block's RoPE keys, to every slice
-    if (tid < 8 * KPE_ROWS) {
-      const bool live = row0 + kpe_row <= last;
-      const size_t tok = kpe_token(rb);
-      if (live && kpe_thread) {
+#pragma unroll
+    for (int it = 0; it < KPE_IT; ++it) {
+      const int row = kpe_row(it);
+      if (row < 0 || row0 + row > last) continue;
+      const size_t tok = kpe_token(rb, row);
+      if (kpe_piece_ok) {
         for (int i = 0; i < g; ++i)
-          __builtin_nontemporal_store(kpe_reg, reinterpret_cast<u32x4*>(static_cast<bf16_t*>(pools.p[i]) + tok * out_pitch +
-                                                                       dl + 8 * (tid & 7)));
+          __builtin_nontemporal_store(kpe_reg[it], reinterpret_cast<u32x4*>(static_cast<bf16_t*>(pools.p[i]) +
+                                                                           tok * out_pitch + dl + 8 * (tid & 7)));
       }
       // RoPE widths above 64: the remaining pieces, not prefetched
-      for (int c = 64 + 8 * (tid & 7); live && c < d_r; c += 64) {
+      for (int c = 64 + 8 * (tid & 7); c < d_r; c += 64) {
         const u32x4 v = *reinterpret_cast<const u32x4*>(mla_pool + tok * in_pitch + D_C + c);
         for (int i = 0; i < g; ++i)
           __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<bf16_t*>(pools.p[i]) + tok * out_pitch + dl + c));
       }
-      if (more && kpe_thread)
-        kpe_reg = *reinterpret_cast<const u32x4*>(mla_pool + kpe_token(rb_next) * in_pitch + D_C + 8 * (tid & 7));
     }
+    if (more) kpe_request(rb_next);
   }
 }
 

@@ -350,6 +350,7 @@ def test_transform_latent_weights(dtype, mode):
     # matrix-core Hadamard pass: narrow slices, short / odd-sized pages, other RoPE widths, d_c = 256;
     # then shapes it declines (d_c = 1024, pages of 6 tokens, float storage at d_c = 512)
     ("bf16", 512, 8, 128, 16), ("bf16", 512, 1, 32, 20), ("bf16", 256, 2, 64, 128), ("bf16", 256, 4, 8, 4),
+    ("bf16", 128, 2, 64, 64), ("bf16", 128, 1, 16, 192),
     ("bf16", 1024, 2, 64, 16), ("bf16", 512, 2, 64, 6), ("f32", 512, 2, 64, 16)])
 def test_transform_latent_paged(dtype, d_c, g, d_r, pt):
     _say(f"transform_latent_paged {dtype} d_c={d_c} g={g} d_r={d_r} page_tokens={pt}")
