@@ -550,6 +550,7 @@ def test_layer_step_as_hip_graph_replays_like_eager():
 
 # ------------------------------------------------------------ PCA calibration (Sec. 4.3.2)
 @pytest.mark.parametrize("dtype,d_c,d_r,pt,P", [("bf16", 512, 64, 64, 40), ("bf16", 256, 64, 16, 9), ("bf16", 128, 8, 64, 3),
+                                                ("bf16", 1024, 64, 32, 6), ("bf16", 384, 64, 64, 5),
                                                 ("bf16", 96, 16, 8, 5), ("f32", 64, 16, 64, 4)])
 def test_latent_moments(dtype, d_c, d_r, pt, P):
     _say(f"latent_moments {dtype} d_c={d_c} d_r={d_r} page_tokens={pt} pages={P}")
@@ -684,6 +685,23 @@ def test_prefill_attention_matches_oracle(lens, H, d_c):
         # per-token check as well: early tokens have few keys and large outputs, late ones small
         den = np.max(np.abs(ref), axis=(1, 2), keepdims=True)
         assert np.max(np.abs(o - ref) / den) <= 2e-2
+
+
+def test_prefill_attention_random_shapes():
+    """Seeded random batches over the supported widths and odd head counts (groups of 8, 4, 2, 1 heads)."""
+    rng = np.random.default_rng(2025)
+    for trial, (H, d_c) in enumerate([(8, 384), (24, 128), (5, 512), (6, 256), (16, 384)]):
+        B = int(rng.integers(1, 5))
+        lens = [int(x) for x in rng.integers(0, 400, size=B)]
+        if sum(lens) == 0:
+            lens[0] = 17
+        _say(f"prefill random trial {trial}: H={H} d_c={d_c} lens={lens}")
+        p = _prefill_problem(1000 + trial, lens, H, d_c)
+        f64 = {k: wl.as_f64(p[k], "bf16") for k in ("q_nope", "q_pe", "c", "k_pe", "W_UK", "W_UV")}
+        ref = orc.mla_prefill(f64["q_nope"], f64["q_pe"], f64["W_UK"], f64["W_UV"], f64["c"], f64["k_pe"], p["cu"],
+                              1.0 / np.sqrt(192.0))
+        o, _ = _run_prefill(p, H, d_c, B, max(lens))
+        assert np.all(np.isfinite(o)) and rel_err(o, ref) <= TOL["bf16"]
 
 
 def test_prefill_attention_rejects_what_it_does_not_implement():
