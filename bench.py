@@ -238,6 +238,13 @@ def main():
     us_decode = timed(lambda: step.decode(0, q_pe, pools[0], bt, lens))
     us_decode_all = timed(lambda: step.decode_all(q_pe, pools, bt, lens))
     us_combine = timed(lambda: step.combine(W_UV_t))
+    us_decode_combine = timed(lambda: step.decode_all_combine(q_pe, pools, bt, lens, W_UV_t))
+
+    def separate_step():
+        step.absorb(q_nope, W_UK_t, mu)
+        step.decode_all(q_pe, pools, bt, lens)
+        step.combine(W_UV_t)
+    us_step_separate = timed(separate_step)
     us_wo = float("nan")
     if not args.skip_extras:
         # block output o W_O (after the timed step's last stage; weight-streaming GEMM)
@@ -358,11 +365,13 @@ def main():
         "config": {"workload": w.name, "B": w.B, "H": w.H, "d_c": w.d_c, "g": w.g, "d_r": w.d_r,
                    "context": int(lens_np.max()), "tokens": int(lens_np.sum()), "page_tokens": pt,
                    "transform": w.transform, "n_splits": args.n_splits,
-                   "step": "absorb + decode of all g slices (one split launch + one merge) + combine, on one GPU"},
+                   "step": "absorb + decode of all g slices (one split launch) + split merge and combine (one kernel), on one GPU"},
         "us_per_layer_step": ms_per_step * 1e3,
         "pct_hbm_roofline_step": 100.0 * value / HBM_PEAK_GBS,
         "stages_us": {"absorb": us_absorb, "decode_shards(all slices, split+merge)": us_decode_all,
                       "decode_shard(one slice, split+merge)": us_decode, "combine": us_combine,
+                      "decode_shards_combine(all slices, split + merge-and-combine kernel)": us_decode_combine,
+                      "layer_step_with_separate_merge_and_combine": us_step_separate,
                       "output_projection(W_O, not in the step)": us_wo,
                       "one_device_share": us_absorb / w.g + us_decode + us_combine,
                       "layer_step_replayed_from_hip_graph": us_graph},

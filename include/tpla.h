@@ -210,6 +210,26 @@ int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const voi
                         float* o, void* stream);
 
 /*
+ * tpla_decode_shards followed by tpla_combine_shards as one call (the
+ * per-slice attention, the value up-projection and the sum over slices of
+ * Sec. 4, Eq. for O_i and the all-reduce after W^{VO}_i with W_UV kept out of
+ * W_O, Sec. 3.3): the merge of the sequence chunks and the combine run as one
+ * kernel where the shape allows (bf16, d_v a multiple of 128, d_c of 512,
+ * d_c/g of 128), as two otherwise.  Arguments as in those two calls; o_lat
+ * float [g,B,H,d_c/g] is required and written (the merged per-slice outputs),
+ * lse float [g,B,H] or NULL, o float [B,H,d_v].  Same workspace size as
+ * tpla_decode_shards.  Results are bit-reproducible for fixed arguments and
+ * agree with the two separate calls up to the rounding order of the merge.
+ */
+int tpla_decode_shards_combine(const tpla_shape_t* shape,
+                               const void* q_lat, const void* q_pe, const void* const* shard_pools,
+                               const int32_t* block_table, int32_t max_pages_per_seq,
+                               const int32_t* seq_lens, int32_t n_splits,
+                               void* workspace, size_t workspace_bytes,
+                               const void* W_UV_t, float* o,
+                               float* o_lat, float* lse, void* stream);
+
+/*
  * Output projection of the attention block (Sec. 3.3: O~ = O W^O with the
  * value up-projection kept out of W^O; Sec. 4: the quantity the devices
  * all-reduce): out[b, :] = o[b, :, :] flattened to H d_v  @  W_O.

@@ -221,6 +221,270 @@ int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const
 }
 
 // ---------------------------------------------------------------------------
+// Split merge and combine in one kernel: the decode's partial results go
+// straight into  o = sum_i o_lat_i @ W_UV'[slice i]  without a pass through
+// memory and a launch in between.  Grid (H, ceil(B / 16), d_v / 128): a
+// workgroup of 8 waves owns one head, 16 (or 8) sequences and 128 output columns.
+// Its weight slab W_UV'[h][512 rows][128 columns] is fetched straight into
+// LDS while the lanes merge: lane (j16, q4) of wave w owns sequence j16 and
+// latent rows 64 w + 32 ks + 8 q4 .. +8 of the chunk (one slice per wave, as
+// d_c / g is a multiple of 64).  The slots of its (slice, sequence) are taken
+// 16 at a time: the four lanes of a sequence fetch four (reference, sum)
+// pairs each, agree on the reference through two shuffles, rescale what they
+// have so far (nothing, unless a sequence has more than 16 slots) and add
+// their 16 columns of the 16 partial rows in slot order, eight rows in
+// flight.  The merged values are written out as o_lat / lse on the way and
+// then feed the MFMAs as bf16 hi + lo parts, as in the combine kernel above.
+constexpr int MC_ROWS = 512;
+constexpr int MC_COLS = 128;
+constexpr int MC_NW = 8;
+constexpr int MC_AHEAD = 8;      // partial rows in flight per lane
+
+// Workgroup of the balanced plan whose page range [w T / W, (w+1) T / W)
+// holds page c, 0 <= c < T.  32-bit arithmetic when the products fit.
+__device__ __forceinline__ int balanced_owner(int c, int T, int W) {
+  if ((long long)T * W <= 2147483647LL) {
+    unsigned w = (unsigned)c * (unsigned)W / (unsigned)T;
+    while (w + 1 < (unsigned)W && (w + 1) * (unsigned)T / (unsigned)W <= (unsigned)c) ++w;
+    while (w > 0 && w * (unsigned)T / (unsigned)W > (unsigned)c) --w;
+    return (int)w;
+  }
+  long long w = (long long)c * W / T;
+  while (w + 1 < W && (w + 1) * T / W <= c) ++w;
+  while (w > 0 && w * T / W > c) --w;
+  return (int)w;
+}
+
+__global__ void __launch_bounds__(MC_NW * 64) merge_combine_mfma_kernel(DecodeArgs a, const bf16_t* __restrict__ W,
+                                                                        float* __restrict__ o, int d_c, int d_v,
+                                                                        int spw) {
+  extern __shared__ u32x4 slab4[];
+  char* slab = reinterpret_cast<char*>(slab4);
+  constexpr int PPR = MC_COLS / 8;     // 16 pieces per row
+  constexpr int NCB = MC_COLS / 16;    // 8 column blocks, all owned by every wave
+  constexpr int WK = MC_ROWS / MC_NW;  // 64 rows per wave and chunk
+  constexpr int KS = WK / 32;
+  const int h = blockIdx.x, mb = blockIdx.y, col0 = blockIdx.z * MC_COLS;
+  const int tid = threadIdx.x, lane = tid & 63, j16 = lane & 15, q4 = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int B = a.B, H = a.H, dl = a.dl;
+  // spw = sequences per workgroup, 16 or 8 (then rows 8..15 of the tiles stay zero: half the
+  // merge work per workgroup and twice the workgroups, for batches that would not fill the chip)
+  const int b = spw * mb + j16;
+  const bool b_valid = j16 < spw && b < B;
+  const int bc = min(b, B - 1);
+  const int L = j16 < spw ? seq_len_clipped(a, bc) : 0;
+  const int n_pages = (L + a.page_tokens - 1) / a.page_tokens;
+  const int n_v = a.n_shards * B;
+
+  f32x4 acc[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int kc = 0; kc < d_c; kc += MC_ROWS) {
+    if (kc > 0) __syncthreads();       // everybody is done with the previous chunk's slab
+    // ---- weight slab, straight into LDS: instruction k fills pieces [64k, 64k + 64)
+    {
+      const bf16_t* Wh = W + ((size_t)h * d_c + kc) * d_v + col0;
+#pragma unroll 8
+      for (int k = wave; k < MC_ROWS * PPR / 64; k += MC_NW) {
+        const int x = k * 64 + lane, r = x / PPR, p = (x % PPR) ^ wswz(r);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Wh + (size_t)r * d_v + 8 * p),
+                                         (__attribute__((address_space(3))) void*)(slab + k * 1024), 16, 0, 0);
+      }
+    }
+    // ---- this lane's (slice, sequence) and its slots ---------------------------
+    const int k_base = kc + WK * wave;
+    const int sl = k_base / dl, c_lane = k_base - sl * dl + 8 * q4;
+    const int vb = sl * B + bc;
+    int first, cnt;
+    // a balanced plan with fewer pages than workgroups leaves some page ranges empty
+    bool sparse = false;
+    int T = 1, c0 = 0, w0 = 0;
+    if (n_pages == 0) {
+      first = 0;
+      cnt = 0;
+    } else if (!a.balanced) {
+      first = vb * a.n_splits;
+      cnt = min((n_pages + a.pages_per_split - 1) / a.pages_per_split, a.n_splits);
+    } else {
+      T = a.plan[n_v];
+      c0 = a.plan[vb];
+      w0 = balanced_owner(c0, T, a.n_wg);
+      cnt = balanced_owner(c0 + n_pages - 1, T, a.n_wg) - w0 + 1;
+      first = w0 + vb;
+      sparse = T < a.n_wg;
+    }
+    auto live = [&](int s) -> bool {
+      if (s >= cnt) return false;
+      if (!sparse) return true;
+      const long long w = w0 + s, Wn = a.n_wg;
+      const long long lo = max(w * T / Wn, (long long)c0), hi = min((w + 1) * T / Wn, (long long)c0 + n_pages);
+      return hi > lo;
+    };
+
+    // ---- merged latent output of this lane: KS pieces of 8 columns -------------
+    // (the four lanes of a sequence run these loops together: same cnt, same slots)
+    float4 x[KS][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) x[ks][0] = x[ks][1] = float4{0.f, 0.f, 0.f, 0.f};
+    float M = -INFINITY, lsum = 0.f;
+    for (int base = 0; base < cnt; base += 16) {
+      float m4[4], l4[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int s = base + q4 + 4 * i;
+        m4[i] = -INFINITY;
+        l4[i] = 0.f;
+        if (live(s)) {
+          const float2 v = *reinterpret_cast<const float2*>(a.part_ml + ((size_t)(first + s) * H + h) * 2);
+          m4[i] = v.x;
+          l4[i] = v.y;
+        }
+      }
+      float Mr = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+      Mr = fmaxf(Mr, __shfl_xor(Mr, 16));
+      Mr = fmaxf(Mr, __shfl_xor(Mr, 32));
+      if (Mr == -INFINITY) continue;                 // 16 empty page ranges in a row
+      const float M_new = fmaxf(M, Mr);
+      const float alpha = exp2f(M - M_new);          // 0 the first time
+      float lr = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) lr = fmaf(l4[i], exp2f(m4[i] - M_new), lr);
+      lr += __shfl_xor(lr, 16);
+      lr += __shfl_xor(lr, 32);
+      lsum = fmaf(lsum, alpha, lr);
+      M = M_new;
+      if (alpha != 1.0f) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            x[ks][e].x *= alpha; x[ks][e].y *= alpha; x[ks][e].z *= alpha; x[ks][e].w *= alpha;
+          }
+      }
+#pragma unroll
+      for (int u0 = 0; u0 < 16; u0 += MC_AHEAD) {
+        if (base + u0 >= cnt) break;
+        float4 p[MC_AHEAD][KS][2];
+        float wg[MC_AHEAD];
+#pragma unroll
+        for (int u = 0; u < MC_AHEAD; ++u) {
+          const int s = base + u0 + u;
+          // slot u0 + u of the round sits in register (u0 + u) / 4 of lane group (u0 + u) % 4
+          const float ms = __shfl(m4[(u0 + u) >> 2], ((u0 + u) & 3) * 16 + j16);
+          wg[u] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) p[u][ks][0] = p[u][ks][1] = float4{0.f, 0.f, 0.f, 0.f};
+          if (live(s)) {
+            wg[u] = exp2f(ms - M);
+            const float* src = a.part_acc + ((size_t)(first + s) * H + h) * dl + c_lane;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+              p[u][ks][0] = *reinterpret_cast<const float4*>(src + 32 * ks);
+              p[u][ks][1] = *reinterpret_cast<const float4*>(src + 32 * ks + 4);
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < MC_AHEAD; ++u) {       // slot order
+          const float w = wg[u];
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              x[ks][e].x = fmaf(p[u][ks][e].x, w, x[ks][e].x);
+              x[ks][e].y = fmaf(p[u][ks][e].y, w, x[ks][e].y);
+              x[ks][e].z = fmaf(p[u][ks][e].z, w, x[ks][e].z);
+              x[ks][e].w = fmaf(p[u][ks][e].w, w, x[ks][e].w);
+            }
+        }
+      }
+    }
+    if (lsum > 0.f) {
+      const float inv = 1.0f / lsum;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          x[ks][e].x *= inv; x[ks][e].y *= inv; x[ks][e].z *= inv; x[ks][e].w *= inv;
+        }
+    }
+    if (b_valid && blockIdx.z == 0) {
+      if (a.lse && q4 == 0 && k_base == sl * dl)
+        a.lse[(size_t)vb * H + h] = lsum > 0.f ? (M + log2f(lsum)) * 0.6931471805599453f : -INFINITY;
+      float* dst = a.o_lat + ((size_t)vb * H + h) * dl + c_lane;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        *reinterpret_cast<float4*>(dst + 32 * ks) = x[ks][0];
+        *reinterpret_cast<float4*>(dst + 32 * ks + 4) = x[ks][1];
+      }
+    }
+    // ---- the slab has landed for every wave --------------------------------------
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const float xs[8] = {x[ks][0].x, x[ks][0].y, x[ks][0].z, x[ks][0].w,
+                           x[ks][1].x, x[ks][1].y, x[ks][1].z, x[ks][1].w};
+      bf16x8 ah, al;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const bf16_t hi16 = (bf16_t)xs[e];
+        ah[e] = hi16;
+        al[e] = (bf16_t)(xs[e] - (float)hi16);
+      }
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const bf16x8 bf = read_b_frag<PPR>(slab, WK * wave + 32 * ks, cb, j16, q4);
+        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bf, acc[cb], 0, 0, 0);
+        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bf, acc[cb], 0, 0, 0);
+      }
+    }
+  }
+  // sum the waves' tiles through LDS; wave w finishes column block w
+  static_assert(NCB == MC_NW, "one column block per wave in the final sum");
+  __syncthreads();
+  f32x4* red = reinterpret_cast<f32x4*>(slab4);    // [wave][cb][lane]
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) red[(wave * NCB + cb) * 64 + lane] = acc[cb];
+  __syncthreads();
+  f32x4 tsum = red[(0 * NCB + wave) * 64 + lane];
+#pragma unroll
+  for (int w2 = 1; w2 < MC_NW; ++w2) tsum += red[(w2 * NCB + wave) * 64 + lane];
+  // tsum[i]: sequence spw mb + 4 q4 + i, column col0 + 16 wave + j16
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int bb = spw * mb + 4 * q4 + i;
+    if (4 * q4 + i < spw && bb < B) o[((size_t)bb * H + h) * d_v + col0 + 16 * wave + j16] = tsum[i];
+  }
+}
+
+bool merge_combine_mfma_supported(const tpla_shape_t& sh) {
+  return sh.dtype == TPLA_BF16 && sh.d_v % MC_COLS == 0 && sh.d_c % MC_ROWS == 0 &&
+         (sh.d_c / sh.g) % (MC_ROWS / MC_NW) == 0 && sh.d_v / MC_COLS <= 65535 && (sh.B + 7) / 8 <= 65535;
+}
+
+int launch_merge_combine_mfma(const DecodeArgs& a, const tpla_shape_t& sh, const void* W_UV_t, float* o,
+                              hipStream_t st) {
+  constexpr size_t smem = (size_t)MC_ROWS * MC_COLS * 2;
+  // dynamic LDS above the 64 KiB default needs opting in, once
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(merge_combine_mfma_kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", smem);
+  }
+  // 16 sequences per workgroup once that gives every compute unit two workgroups, else 8
+  const long long wg16 = (long long)sh.H * ((sh.B + 15) / 16) * (sh.d_v / MC_COLS);
+  const int spw = wg16 >= 2LL * device_cu_count() ? 16 : 8;
+  hipLaunchKernelGGL(merge_combine_mfma_kernel,
+                     dim3((unsigned)sh.H, (unsigned)((sh.B + spw - 1) / spw), (unsigned)(sh.d_v / MC_COLS)),
+                     dim3(MC_NW * 64), smem, st, a, static_cast<const bf16_t*>(W_UV_t), o, sh.d_c, sh.d_v, spw);
+  return check_launch("merge_combine_mfma_kernel");
+}
+
+// ---------------------------------------------------------------------------
 // Output projection  out[b, n] = sum_k x[b, k] W[k, n]  (x = the combined
 // per-head outputs flattened to [B, H d_v], W = W_O [H d_v, D]; Sec. 3.3: the
 // value up-projection is not merged into W_O, so this runs after the combine).

@@ -133,15 +133,18 @@ static size_t workspace_for(const tpla_shape_t& sh, int n_shards, const SplitPla
 }
 
 // Validation, planning and launches shared by the one-slice and the
-// all-slices entry points.
+// all-slices entry points.  With W_UV_t and o given (all slices only) the
+// combine follows, fused with the split merge where the shape allows.
 static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_lat, const void* q_pe,
                          const void* const* pools, const int32_t* block_table, int32_t max_pages_per_seq,
                          const int32_t* seq_lens, int32_t n_splits, void* workspace,
-                         size_t workspace_bytes, float* o_lat, float* lse, void* stream) {
+                         size_t workspace_bytes, float* o_lat, float* lse, void* stream,
+                         const void* W_UV_t = nullptr, float* o = nullptr) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!q_lat || !q_pe || !pools || !block_table || !seq_lens || !workspace || !o_lat)
     return fail(TPLA_ERR_NULL, "a required pointer is NULL");
+  if (!aligned16(W_UV_t) || !aligned16(o)) return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
   if (max_pages_per_seq < 1 || n_splits < 0)
     return fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_splits=%d", max_pages_per_seq, n_splits);
   if ((int64_t)max_pages_per_seq * shape->page_tokens > (int64_t)2147483647)
@@ -197,7 +200,12 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
     rc = launch_decode_generic(a, shape->dtype, st);
   profile_mark(st, false);
   if (rc) return rc;
-  return launch_decode_merge(a, st);
+  if (!W_UV_t) return launch_decode_merge(a, st);
+  if (merge_combine_mfma_supported(*shape)) return launch_merge_combine_mfma(a, *shape, W_UV_t, o, st);
+  rc = launch_decode_merge(a, st);
+  if (rc) return rc;
+  if (combine_mfma_supported(*shape)) return launch_combine_shards_mfma(*shape, o_lat, W_UV_t, o, st);
+  return launch_combine_shards(*shape, o_lat, W_UV_t, o, st);
 }
 
 }  // namespace tpla
@@ -362,6 +370,18 @@ int tpla_decode_shards(const tpla_shape_t* shape, const void* q_lat, const void*
   if (rc) return rc;
   return decode_common(shape, shape->g, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
                        n_splits, workspace, workspace_bytes, o_lat, lse, stream);
+}
+
+int tpla_decode_shards_combine(const tpla_shape_t* shape, const void* q_lat, const void* q_pe,
+                               const void* const* shard_pools, const int32_t* block_table,
+                               int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t n_splits,
+                               void* workspace, size_t workspace_bytes, const void* W_UV_t, float* o,
+                               float* o_lat, float* lse, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!W_UV_t || !o) return fail(TPLA_ERR_NULL, "W_UV_t/o is NULL");
+  return decode_common(shape, shape->g, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
+                       n_splits, workspace, workspace_bytes, o_lat, lse, stream, W_UV_t, o);
 }
 
 int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t, float* o,

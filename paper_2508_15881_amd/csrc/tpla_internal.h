@@ -135,6 +135,10 @@ int launch_absorb_query_mfma(const tpla_shape_t& sh, const void* q_nope, const v
 bool combine_mfma_supported(const tpla_shape_t& sh);
 int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
                                hipStream_t st);
+// Split merge fused with the combine: reads the decode's partial results, writes o_lat, lse and o.
+bool merge_combine_mfma_supported(const tpla_shape_t& sh);
+int launch_merge_combine_mfma(const DecodeArgs& a, const tpla_shape_t& sh, const void* W_UV_t, float* o,
+                              hipStream_t st);
 
 // ---- small device helpers -------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(bf16_t x) { return (float)x; }

@@ -71,17 +71,23 @@ class DecodeStep:
     def combine(self, W_UV_t):
         B.tpla_combine_shards(self.shape, self.o_lat, W_UV_t, self.o)
 
+    def decode_all_combine(self, q_pe, shard_pools, block_table, seq_lens, W_UV_t):
+        """All g slices in one launch, then the split merge and the combine as one kernel."""
+        B.tpla_decode_shards_combine(self.shape, self.q_lat, q_pe, shard_pools, block_table, self.max_pages,
+                                     seq_lens, self.n_splits, self.workspace, self.ws_bytes, W_UV_t, self.o,
+                                     self.o_lat, self.lse)
+
     def run(self, q_nope, q_pe, W_UK_t, W_UV_t, shard_pools, block_table, seq_lens, mu=None, fused=True):
-        """One decode layer-step.  fused: all slices in one decode launch (how one GPU
-        runs the whole step); otherwise one tpla_decode_shard call per slice (one
-        device's share at a time)."""
+        """One decode layer-step.  fused: all slices in one decode launch with the merge and
+        the combine behind it as one kernel (how one GPU runs the whole step); otherwise one
+        tpla_decode_shard call per slice (one device's share at a time), then the combine."""
         self.absorb(q_nope, W_UK_t, mu)
         if fused:
-            self.decode_all(q_pe, shard_pools, block_table, seq_lens)
+            self.decode_all_combine(q_pe, shard_pools, block_table, seq_lens, W_UV_t)
         else:
             for i in range(self.shape.g):
                 self.decode(i, q_pe, shard_pools[i], block_table, seq_lens)
-        self.combine(W_UV_t)
+            self.combine(W_UV_t)
         return self.o
 
 

@@ -107,6 +107,13 @@ def test_other_entry_points_argument_checks():
     assert _code(tp.tpla_prefill_attention, sp, A, A, A, A, A, A, A, 8, 8, A, 64, A) == -4
     assert _code(tp.tpla_prefill_attention, sp, A, A + 2, A, A, A, A, A, 8, 8, A, 1 << 30, A) == -3
     assert _code(tp.tpla_prefill_attention, _shape(d_n=64), A, A, A, A, A, A, A, 8, 8, A, 1 << 30, A) == -7
+    # decode + merge + combine in one call: its own pointers, then the decode's checks
+    assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, A], A, 4, A, 0, A, 1 << 30, None, A, A, None) == -1
+    assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, A], A, 4, A, 0, A, 1 << 30, A, None, A, None) == -1
+    assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, A], A, 4, A, 0, A, 1 << 30, A, A, None, None) == -1
+    assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, A], A, 4, A, 0, A, 1 << 30, A + 2, A, A, None) == -3
+    assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, None], A, 4, A, 0, A, 1 << 30, A, A, A, None) == -1
+    assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, A], A, 4, A, 2, A, 16, A, A, A, None) == -4
     # empty work is accepted without a launch
     tp.tpla_transform_latent(s, tp.TPLA_U_IDENTITY, 0, None, None, A, A, 0, 1)
     tp.tpla_transform_latent_paged(s, tp.TPLA_U_IDENTITY, None, None, A, [A, A], None, 0)

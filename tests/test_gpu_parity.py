@@ -243,6 +243,89 @@ def test_decode_shards_equals_one_call_per_slice():
     assert rel_err(o_all[0].cpu().numpy(), ro) <= TOL["bf16"]
 
 
+# ------------------------------------------------------------ decode + merge + combine in one call
+COMBINE_CASES = [
+    # name, workload, lengths (B = their number), split counts
+    ("dsv3_two_seq_blocks", DSV3, [700, 65, 2048, 0, 1, 64, 3000, 129, 31, 640, 5, 900, 63, 257, 1100, 2, 333, 77, 1500], (0, 4)),
+    ("ragged_g4", RAGGED, [3000, 17, 0, 256, 4097], (0, 3)),
+    ("wide_two_chunks", wl.scaled(DSV3, d_c=1024), [500, 130, 1025], (0, 2)),
+    ("mla_g1", wl.scaled(DSV3, g=1), [333, 64, 1025], (0,)),
+    ("fewer_pages_than_workgroups", DSV3, [1, 64, 0, 33, 7, 60, 12, 64, 2, 50, 64, 31, 9, 40, 3, 64, 20], (0,)),
+    ("kimi_H32", KIMI, [129, 1000, 5, 64], (0, 1)),
+    ("generic_f32", wl.Workload("odd", B=3, H=5, d_c=80, g=2, d_r=24, d_n=16, d_v=16, dtype="f32", seed=11), [200, 0, 65], (0, 2)),
+]
+
+
+@pytest.mark.parametrize("name,w,lens,splits", COMBINE_CASES, ids=[c[0] for c in COMBINE_CASES])
+def test_decode_shards_combine_matches_oracle_and_the_separate_calls(name, w, lens, splits):
+    lens = np.asarray(lens, dtype=np.int32)
+    Bn = len(lens)
+    w = wl.scaled(w, B=Bn)
+    probs = [build_shard_problem(w, lens, rng_extra=i) for i in range(w.g)]
+    shape = pl.make_shape(w)
+    dev = "cuda"
+    dt = w.dtype
+    q_lat = pl.to_device(np.stack([p["q_lat"] for p in probs]), dt)
+    q_pe = pl.to_device(probs[0]["q_pe"], dt)
+    # the slices share one page table and one k_pe (Sec. 4.2): slice i's pool takes slice 0's paging
+    # and RoPE columns and its own latent columns
+    pools_np = []
+    for i in range(w.g):
+        pool = probs[0]["pool"].copy()
+        src = probs[i]
+        for b in range(Bn):
+            n = (int(lens[b]) + w.page_tokens - 1) // w.page_tokens
+            for j in range(n):
+                pool[probs[0]["bt"][b, j], :, :w.dl] = src["pool"][src["bt"][b, j], :, :w.dl]
+        pools_np.append(pool)
+    pools = [pl.to_device(p, dt) for p in pools_np]
+    bt = torch.from_numpy(probs[0]["bt"]).to(dev)
+    ln = torch.from_numpy(lens).to(dev)
+    mp = probs[0]["max_pages"]
+    rng = np.random.default_rng(4242)
+    Wv = wl.to_storage(rng.standard_normal((w.H, w.d_c, w.d_v)) * 0.05, dt)
+    Wv_d = pl.to_device(Wv, dt)
+    # oracle: per-slice attention, then the up-projection and the sum over slices
+    qp64 = wl.as_f64(probs[0]["q_pe"], dt)
+    kpe = [r[:, w.dl:] for r in probs[0]["rows64"]]
+    ref_lat, ref_lse = [], []
+    for i in range(w.g):
+        c = [r[:, :w.dl] for r in probs[i]["rows64"]]
+        o_i, l_i = orc.shard_attention(wl.as_f64(probs[i]["q_lat"], dt), qp64, c, kpe, w.sm_scale)
+        ref_lat.append(o_i); ref_lse.append(l_i)
+    ref_lat = np.stack(ref_lat); ref_lse = np.stack(ref_lse)
+    ref_o = orc.combine_shards(ref_lat, wl.as_f64(Wv, dt))
+    nz = lens > 0
+    for n_splits in splits:
+        _say(f"decode_shards_combine {name} B={Bn} n_splits={n_splits}")
+        ws_b = tp.tpla_workspace_bytes_all(shape, mp, n_splits)
+        ws = torch.empty(ws_b, dtype=torch.uint8, device=dev)
+        nan = float("nan")
+        o = torch.full((Bn, w.H, w.d_v), nan, dtype=torch.float32, device=dev)
+        o_lat = torch.full((w.g, Bn, w.H, w.dl), nan, dtype=torch.float32, device=dev)
+        lse = torch.full((w.g, Bn, w.H), nan, dtype=torch.float32, device=dev)
+        tp.tpla_decode_shards_combine(shape, q_lat, q_pe, pools, bt, mp, ln, n_splits, ws, ws_b, Wv_d, o, o_lat, lse)
+        torch.cuda.synchronize()
+        o_np, lat_np, lse_np = o.cpu().numpy(), o_lat.cpu().numpy(), lse.cpu().numpy()
+        assert rel_err(lat_np, ref_lat) <= TOL[dt]
+        assert rel_err(o_np, ref_o) <= TOL[dt]
+        assert np.max(np.abs(lse_np[:, nz] - ref_lse[:, nz])) <= (1e-2 if dt == "bf16" else 1e-4)
+        assert np.all(lat_np[:, ~nz] == 0) and np.all(np.isneginf(lse_np[:, ~nz])) and np.all(o_np[~nz] == 0)
+        # the two separate calls: same partial results, the merge summed in another order
+        o2 = torch.full_like(o, nan); o_lat2 = torch.full_like(o_lat, nan); lse2 = torch.full_like(lse, nan)
+        tp.tpla_decode_shards(shape, q_lat, q_pe, pools, bt, mp, ln, n_splits, ws, ws_b, o_lat2, lse2)
+        tp.tpla_combine_shards(shape, o_lat2, Wv_d, o2)
+        torch.cuda.synchronize()
+        assert rel_err(lat_np, o_lat2.cpu().numpy()) <= 1e-5
+        assert rel_err(o_np, o2.cpu().numpy()) <= 1e-5
+        assert np.max(np.abs(lse_np[:, nz] - lse2.cpu().numpy()[:, nz])) <= 1e-5
+        # reproducible bits
+        o3 = torch.full_like(o, nan); o_lat3 = torch.full_like(o_lat, nan)
+        tp.tpla_decode_shards_combine(shape, q_lat, q_pe, pools, bt, mp, ln, n_splits, ws, ws_b, Wv_d, o3, o_lat3, None)
+        torch.cuda.synchronize()
+        assert torch.equal(o, o3) and torch.equal(o_lat, o_lat3)
+
+
 # ------------------------------------------------------------ tiny config, whole path
 def _full_problem(w):
     m = wl.draw_model_side(w)
