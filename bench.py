@@ -225,26 +225,29 @@ def main():
     all_traffic = launch_bytes + n_items * w.H * ((w.dl + w.d_r) * esz + (w.dl + 2) * 4) + w.g * w.B * model["max_pages"] * 4
 
     # stage breakdown (untimed region, events on torch's current stream = the launch stream)
-    def timed(fn, reps=20):
+    def timed(fn, reps=20, warm=1):
         if args.skip_extras:
             return float("nan")
-        fn(); torch.cuda.synchronize()
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
         ev0.record()
         for _ in range(reps):
             fn()
         ev1.record(); torch.cuda.synchronize()
         return ev0.elapsed_time(ev1) / reps * 1e3
     us_absorb = timed(lambda: step.absorb(q_nope, W_UK_t, mu))
-    us_decode = timed(lambda: step.decode(0, q_pe, pools[0], bt, lens))
-    us_decode_all = timed(lambda: step.decode_all(q_pe, pools, bt, lens))
+    # the long stages get enough launches for the clocks to settle after the short ones
+    us_decode = timed(lambda: step.decode(0, q_pe, pools[0], bt, lens), reps=100, warm=30)
+    us_decode_all = timed(lambda: step.decode_all(q_pe, pools, bt, lens), reps=100, warm=30)
     us_combine = timed(lambda: step.combine(W_UV_t))
-    us_decode_combine = timed(lambda: step.decode_all_combine(q_pe, pools, bt, lens, W_UV_t))
+    us_decode_combine = timed(lambda: step.decode_all_combine(q_pe, pools, bt, lens, W_UV_t), reps=100, warm=30)
 
     def separate_step():
         step.absorb(q_nope, W_UK_t, mu)
         step.decode_all(q_pe, pools, bt, lens)
         step.combine(W_UV_t)
-    us_step_separate = timed(separate_step)
+    us_step_separate = timed(separate_step, reps=100, warm=30)
     us_wo = float("nan")
     if not args.skip_extras:
         # block output o W_O (after the timed step's last stage; weight-streaming GEMM)
