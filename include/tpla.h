@@ -321,6 +321,22 @@ int tpla_profile_collect(float* ms, int32_t capacity, int32_t* n_records);
  */
 int tpla_stream_read(const void* buf, size_t bytes, void* sink, void* stream);
 
+/*
+ * Host-side check of the paging inputs of the decode calls, for callers that
+ * want one before a launch (the kernels trust the page ids: an id outside the
+ * pool is an access outside the pool).  HOST pointers: block_table int32
+ * [B, max_pages_per_seq], seq_lens int32 [B].  Checks 0 <= seq_lens[b] <=
+ * max_pages_per_seq * page_tokens, that the ids of the pages a sequence uses
+ * (the first ceil(seq_lens[b] / page_tokens) of its row) lie in
+ * [0, n_pool_pages), and that no page is used twice (by two sequences or
+ * twice by one): a shared page is legal for reading, so this last check only
+ * runs with forbid_shared != 0.  Returns TPLA_OK or TPLA_ERR_SHAPE with the
+ * first offending entry named by tpla_last_error().  Synchronous, no GPU work.
+ */
+int tpla_validate_block_table(const tpla_shape_t* shape, const int32_t* block_table,
+                              int32_t max_pages_per_seq, const int32_t* seq_lens,
+                              int64_t n_pool_pages, int forbid_shared);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ EXPORTS = (
     "tpla_decode_shards", "tpla_append_token_sliced", "tpla_output_projection",
     "tpla_output_projection_workspace_bytes", "tpla_latent_moments_workspace_bytes", "tpla_latent_moments",
     "tpla_pca_basis", "tpla_prefill_workspace_bytes", "tpla_prefill_attention", "tpla_stream_read",
-    "tpla_decode_shards_combine",
+    "tpla_decode_shards_combine", "tpla_validate_block_table",
 )
 
 
@@ -108,6 +108,8 @@ def load_library():
     lib.tpla_prefill_attention.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, ctypes.c_size_t, vp, vp]
     lib.tpla_stream_read.restype = ctypes.c_int
     lib.tpla_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.tpla_validate_block_table.restype = ctypes.c_int
+    lib.tpla_validate_block_table.argtypes = [shp, vp, i32, vp, i64, ctypes.c_int]
     lib.tpla_pca_basis.restype = ctypes.c_int
     lib.tpla_pca_basis.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp]
     _lib = lib
@@ -288,6 +290,20 @@ def tpla_pca_basis(d_c, g, n_rows, sum_host, gram_host):
     _check(load_library().tpla_pca_basis(d_c, g, n_rows, sum_host.ctypes.data, gram_host.ctypes.data,
                                          U.ctypes.data, eig.ctypes.data, frac.ctypes.data))
     return U, eig, frac
+
+
+def tpla_validate_block_table(shape, block_table_host, max_pages_per_seq, seq_lens_host, n_pool_pages,
+                              forbid_shared=False):
+    """Host call.  block_table_host [B, max_pages_per_seq], seq_lens_host [B]: int32 numpy arrays
+    (or None, to exercise the argument checks).  Raises TplaError naming the first bad entry."""
+    import numpy as np
+    bt = None if block_table_host is None else np.ascontiguousarray(block_table_host, dtype=np.int32)
+    ln = None if seq_lens_host is None else np.ascontiguousarray(seq_lens_host, dtype=np.int32)
+    if bt is not None and ln is not None and (bt.shape != (shape.B, max_pages_per_seq) or ln.shape != (shape.B,)):
+        raise ValueError("block_table must be [B, max_pages_per_seq] and seq_lens [B]")
+    _check(load_library().tpla_validate_block_table(
+        ctypes.byref(shape), None if bt is None else bt.ctypes.data, max_pages_per_seq,
+        None if ln is None else ln.ctypes.data, n_pool_pages, 1 if forbid_shared else 0))
 
 
 def tpla_stream_read(buf, nbytes, sink, stream=None):

@@ -5,6 +5,7 @@
 #include <string.h>
 #include <math.h>
 #include "tpla_internal.h"
+#include <vector>
 
 namespace tpla {
 
@@ -515,6 +516,37 @@ int tpla_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf || !sink) return fail(TPLA_ERR_NULL, "buf/sink is NULL");
   if (!aligned16(buf) || !aligned16(sink)) return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
   return launch_stream_read(buf, bytes, sink, (hipStream_t)stream);
+}
+
+int tpla_validate_block_table(const tpla_shape_t* shape, const int32_t* block_table, int32_t max_pages_per_seq,
+                              const int32_t* seq_lens, int64_t n_pool_pages, int forbid_shared) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!block_table || !seq_lens) return fail(TPLA_ERR_NULL, "block_table/seq_lens is NULL");
+  if (max_pages_per_seq < 1 || n_pool_pages < 1)
+    return fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_pool_pages=%lld", max_pages_per_seq, (long long)n_pool_pages);
+  const int64_t cap = (int64_t)max_pages_per_seq * shape->page_tokens;
+  std::vector<bool> used;
+  if (forbid_shared) used.assign((size_t)n_pool_pages, false);
+  for (int b = 0; b < shape->B; ++b) {
+    const int64_t L = seq_lens[b];
+    if (L < 0 || L > cap)
+      return fail(TPLA_ERR_SHAPE, "seq_lens[%d]=%lld outside [0, %lld]", b, (long long)L, (long long)cap);
+    const int64_t n = (L + shape->page_tokens - 1) / shape->page_tokens;
+    for (int64_t j = 0; j < n; ++j) {
+      const int64_t id = block_table[(int64_t)b * max_pages_per_seq + j];
+      if (id < 0 || id >= n_pool_pages)
+        return fail(TPLA_ERR_SHAPE, "block_table[%d][%lld]=%lld outside the pool of %lld pages", b, (long long)j,
+                    (long long)id, (long long)n_pool_pages);
+      if (forbid_shared) {
+        if (used[(size_t)id])
+          return fail(TPLA_ERR_SHAPE, "page %lld is used twice (again at block_table[%d][%lld])", (long long)id, b,
+                      (long long)j);
+        used[(size_t)id] = true;
+      }
+    }
+  }
+  return TPLA_OK;
 }
 
 #pragma GCC visibility pop

@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2508_15881_amd as tp
@@ -118,6 +119,28 @@ def test_other_entry_points_argument_checks():
     tp.tpla_transform_latent(s, tp.TPLA_U_IDENTITY, 0, None, None, A, A, 0, 1)
     tp.tpla_transform_latent_paged(s, tp.TPLA_U_IDENTITY, None, None, A, [A, A], None, 0)
     tp.tpla_write_mla_cache(s, A, A, A, 0, 1e-6, A)
+
+
+def test_validate_block_table_names_the_first_bad_entry():
+    s = _shape(B=3)
+    bt = np.array([[0, 1, 2, 3], [4, 5, 0, 0], [6, 0, 0, 0]], dtype=np.int32)
+    ln = np.array([200, 65, 1], dtype=np.int32)               # 4, 2 and 1 pages in use
+    tp.tpla_validate_block_table(s, bt, 4, ln, 7)
+    tp.tpla_validate_block_table(s, bt, 4, ln, 7, forbid_shared=True)
+    tp.tpla_validate_block_table(s, bt, 4, np.zeros(3, dtype=np.int32), 1)     # nothing in use: ids are not looked at
+    assert _code(tp.tpla_validate_block_table, s, bt, 4, ln, 6) == -2 and "block_table[2][0]=6" in tp.tpla_last_error()
+    bad = bt.copy(); bad[1, 1] = -1
+    assert _code(tp.tpla_validate_block_table, s, bad, 4, ln, 7) == -2 and "block_table[1][1]=-1" in tp.tpla_last_error()
+    bad = bt.copy(); bad[1, 3] = 99                            # beyond the pages in use: ignored
+    tp.tpla_validate_block_table(s, bad, 4, ln, 7, forbid_shared=True)
+    assert _code(tp.tpla_validate_block_table, s, bt, 4, np.array([257, 65, 1], dtype=np.int32), 7) == -2
+    assert "seq_lens[0]=257" in tp.tpla_last_error()
+    assert _code(tp.tpla_validate_block_table, s, bt, 4, np.array([200, -1, 1], dtype=np.int32), 7) == -2
+    shared = bt.copy(); shared[2, 0] = 1
+    tp.tpla_validate_block_table(s, shared, 4, ln, 7)           # sharing a page is legal for reading
+    assert _code(tp.tpla_validate_block_table, s, shared, 4, ln, 7, True) == -2 and "page 1" in tp.tpla_last_error()
+    assert _code(tp.tpla_validate_block_table, s, None, 4, ln, 7) == -1
+    assert _code(tp.tpla_validate_block_table, s, bt, 0, ln, 7) in (-2,)
 
 
 def test_missing_library_is_a_loud_error(monkeypatch):
