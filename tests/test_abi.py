@@ -140,7 +140,9 @@ def test_validate_block_table_names_the_first_bad_entry():
     tp.tpla_validate_block_table(s, shared, 4, ln, 7)           # sharing a page is legal for reading
     assert _code(tp.tpla_validate_block_table, s, shared, 4, ln, 7, True) == -2 and "page 1" in tp.tpla_last_error()
     assert _code(tp.tpla_validate_block_table, s, None, 4, ln, 7) == -1
-    assert _code(tp.tpla_validate_block_table, s, bt, 0, ln, 7) in (-2,)
+    assert _code(tp.tpla_validate_block_table, s, bt, 4, ln, 0) == -2
+    with pytest.raises(ValueError):
+        tp.tpla_validate_block_table(s, bt, 3, ln, 7)          # the binding checks the array shapes itself
 
 
 def test_missing_library_is_a_loud_error(monkeypatch):
