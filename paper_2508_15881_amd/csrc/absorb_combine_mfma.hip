@@ -240,21 +240,6 @@ constexpr int MC_COLS = 128;
 constexpr int MC_NW = 8;
 constexpr int MC_AHEAD = 8;      // partial rows in flight per lane
 
-// Workgroup of the balanced plan whose page range [w T / W, (w+1) T / W)
-// holds page c, 0 <= c < T.  32-bit arithmetic when the products fit.
-__device__ __forceinline__ int balanced_owner(int c, int T, int W) {
-  if ((long long)T * W <= 2147483647LL) {
-    unsigned w = (unsigned)c * (unsigned)W / (unsigned)T;
-    while (w + 1 < (unsigned)W && (w + 1) * (unsigned)T / (unsigned)W <= (unsigned)c) ++w;
-    while (w > 0 && w * (unsigned)T / (unsigned)W > (unsigned)c) --w;
-    return (int)w;
-  }
-  long long w = (long long)c * W / T;
-  while (w + 1 < W && (w + 1) * T / W <= c) ++w;
-  while (w > 0 && w * T / W > c) --w;
-  return (int)w;
-}
-
 __global__ void __launch_bounds__(MC_NW * 64) merge_combine_mfma_kernel(DecodeArgs a, const bf16_t* __restrict__ W,
                                                                         float* __restrict__ o, int d_c, int d_v,
                                                                         int spw) {
@@ -317,10 +302,7 @@ __global__ void __launch_bounds__(MC_NW * 64) merge_combine_mfma_kernel(DecodeAr
     }
     auto live = [&](int s) -> bool {
       if (s >= cnt) return false;
-      if (!sparse) return true;
-      const long long w = w0 + s, Wn = a.n_wg;
-      const long long lo = max(w * T / Wn, (long long)c0), hi = min((w + 1) * T / Wn, (long long)c0 + n_pages);
-      return hi > lo;
+      return !sparse || balanced_range_meets(w0 + s, T, a.n_wg, c0, c0 + n_pages);
     };
 
     // ---- merged latent output of this lane: KS pieces of 8 columns -------------

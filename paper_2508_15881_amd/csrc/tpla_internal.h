@@ -66,6 +66,28 @@ __device__ __forceinline__ int seq_len_clipped(const DecodeArgs& a, int b) {
   return (int)(L < 0 ? 0 : (L > cap ? cap : L));
 }
 
+// Balanced plan: workgroup w of W owns the pages [w T / W, (w+1) T / W) of the T pages of all
+// (slice, sequence) pairs laid end to end.  The workgroup whose range holds page c, 0 <= c < T
+// (32-bit arithmetic when the products fit).
+__device__ __forceinline__ int balanced_owner(int c, int T, int W) {
+  if ((long long)T * W <= 2147483647LL) {
+    unsigned w = (unsigned)c * (unsigned)W / (unsigned)T;
+    while (w + 1 < (unsigned)W && (w + 1) * (unsigned)T / (unsigned)W <= (unsigned)c) ++w;
+    while (w > 0 && w * (unsigned)T / (unsigned)W > (unsigned)c) --w;
+    return (int)w;
+  }
+  long long w = (long long)c * W / T;
+  while (w + 1 < W && (w + 1) * T / W <= c) ++w;
+  while (w > 0 && w * T / W > c) --w;
+  return (int)w;
+}
+// Whether workgroup w's range meets the pages [c0, c1) (only in doubt when T < W: some ranges are empty).
+__device__ __forceinline__ bool balanced_range_meets(long long w, long long T, long long W, long long c0,
+                                                     long long c1) {
+  const long long lo = w * T / W, hi = (w + 1) * T / W;
+  return (lo > c0 ? lo : c0) < (hi < c1 ? hi : c1);
+}
+
 int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st);
 int launch_decode_merge(const DecodeArgs& a, hipStream_t st);
 
