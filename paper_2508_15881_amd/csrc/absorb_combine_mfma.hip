@@ -56,25 +56,43 @@ __global__ void __launch_bounds__(256) absorb_query_mfma_kernel(const bf16_t* __
   const int h = blockIdx.x, c0 = blockIdx.y * AQ_COLS;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j16 = lane & 15, q4 = lane >> 4;
   const bf16_t* Wh = W + (size_t)h * d_n * d_c + c0;
-  for (int x = tid; x < d_n * PPR; x += 256) {
-    const int r = x / PPR, p = x % PPR;
-    slab4[r * PPR + (p ^ wswz(r))] = *reinterpret_cast<const u32x4*>(Wh + (size_t)r * d_c + 8 * p);
+  // the slab goes straight into LDS: instruction k fills pieces [64k, 64k + 64), the swizzle is
+  // applied to the address each lane fetches from
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  for (int k = wave_s; k < d_n * PPR / 64; k += 4) {
+    const int x = k * 64 + lane, r = x / PPR, p = (x % PPR) ^ wswz(r);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Wh + (size_t)r * d_c + 8 * p),
+                                     (__attribute__((address_space(3))) void*)(slab + k * 1024), 16, 0, 0);
   }
-  __syncthreads();
   const int dl = d_c / g;
   const int KS = d_n / 32;
-  for (int mb = 0; mb < (B + 15) / 16; ++mb) {
+  constexpr int KS_MAX = 8;                    // d_n <= 256
+  const int n_mb = (B + 15) / 16;
+  // the first block's query rows are on their way while the slab lands
+  bf16x8 av[KS_MAX];
+  auto load_rows = [&](int mb) {
     const int b = 16 * mb + j16;
     const bf16_t* qrow = q_nope + ((size_t)min(b, B - 1) * H + h) * d_n + 8 * q4;
-    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-    for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(qrow + 32 * ks);
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        const bf16x8 bf = read_b_frag<PPR>(slab, 32 * ks, 2 * wave + cb, j16, q4);
-        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bf, acc[cb], 0, 0, 0);
+    for (int ks = 0; ks < KS_MAX; ++ks)
+      if (ks < KS) av[ks] = *reinterpret_cast<const bf16x8*>(qrow + 32 * ks);
+  };
+  load_rows(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  for (int mb = 0; mb < n_mb; ++mb) {
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int ks = 0; ks < KS_MAX; ++ks) {
+      if (ks < KS) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          const bf16x8 bf = read_b_frag<PPR>(slab, 32 * ks, 2 * wave + cb, j16, q4);
+          acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[ks], bf, acc[cb], 0, 0, 0);
+        }
       }
     }
+    if (mb + 1 < n_mb) load_rows(mb + 1);     // under this block's stores
     // acc[cb][i]: sequence 16 mb + 4 q4 + i, column c0 + 32 wave + 16 cb + j16
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
