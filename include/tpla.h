@@ -301,9 +301,12 @@ int tpla_pca_basis(int32_t d_c, int32_t g, int64_t n_rows, const double* sum, co
 /*
  * Measurement aid for the split kernel of tpla_decode_shard (the pass over
  * the cache of Sec. 4.5's memory-bound decode).  After
- * tpla_profile_enable(n) with n > 0, each tpla_decode_shard call on this
- * thread brackets that kernel -- not the merge that follows it -- with a pair
- * of HIP events on the call's stream, for at most n calls.
+ * tpla_profile_enable(n) with n > 0, each decode call (tpla_decode_shard,
+ * tpla_decode_shards, tpla_decode_shards_combine) on this thread times that
+ * kernel -- not the merge that follows it -- with a pair of HIP events on the
+ * call's stream, for at most n calls: the matrix-core kernel is launched with
+ * the events attached to its dispatch, so they hold its own begin and end
+ * times; the generic kernel is bracketed by two recorded events.
  * tpla_profile_collect waits for the recorded events, writes the elapsed
  * milliseconds of each bracketed kernel to the HOST array ms (capacity
  * entries), stores the count in *n_records and starts over.

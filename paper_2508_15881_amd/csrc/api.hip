@@ -194,12 +194,17 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
   a.scale_log2 = shape->sm_scale * 1.4426950408889634f;
 
   hipStream_t st = (hipStream_t)stream;
-  profile_mark(st, true);
-  if (shape->dtype == TPLA_BF16 && decode_mfma_supported(*shape))
-    rc = launch_decode_mfma(a, st);
-  else
+  if (shape->dtype == TPLA_BF16 && decode_mfma_supported(*shape)) {
+    // recording: the event pair is attached to the kernel's dispatch and takes its begin and end times
+    const bool rec = g_prof.cap > 0 && g_prof.used < g_prof.cap;
+    rc = launch_decode_mfma(a, st, rec ? g_prof.ev[2 * g_prof.used] : nullptr,
+                            rec ? g_prof.ev[2 * g_prof.used + 1] : nullptr);
+    if (rec && rc == TPLA_OK) ++g_prof.used;
+  } else {
+    profile_mark(st, true);
     rc = launch_decode_generic(a, shape->dtype, st);
-  profile_mark(st, false);
+    profile_mark(st, false);
+  }
   if (rc) return rc;
   if (!W_UV_t) return launch_decode_merge(a, st);
   if (merge_combine_mfma_supported(*shape)) return launch_merge_combine_mfma(a, *shape, W_UV_t, o, st);

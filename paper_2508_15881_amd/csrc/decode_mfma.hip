@@ -19,6 +19,7 @@
 // LDS reads of the tiles are issued from inline assembly with hand-placed
 // lgkmcnt waits: the compiler would otherwise make every LDS read wait for
 // all outstanding direct-to-LDS loads, which would serialise the prefetch.
+#include <hip/hip_ext.h>
 #include "lds_tile.h"
 
 namespace tpla {
@@ -426,14 +427,17 @@ int decode_mfma_blocks_per_cu(const tpla_shape_t& sh) {
   return k->blocks_per_cu;
 }
 
-int launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
+int launch_decode_mfma(const DecodeArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   KernelInfo* k = nullptr;
   const int rc = kernel_info_for(a.dl, a.H, &k);
   if (rc) return rc;
-  if (a.balanced)
-    hipLaunchKernelGGL(k->fn_balanced, dim3((unsigned)a.n_wg), dim3(k->threads), k->smem, st, a);
+  const dim3 grid(a.balanced ? (unsigned)a.n_wg : (unsigned)(a.n_shards * a.B * a.n_splits));
+  void (*fn)(DecodeArgs) = a.balanced ? k->fn_balanced : k->fn;
+  if (ev_start && ev_stop)
+    // the events take the kernel's own begin and end times (no marker packets around it)
+    hipExtLaunchKernelGGL(fn, grid, dim3(k->threads), (uint32_t)k->smem, st, ev_start, ev_stop, 0, a);
   else
-    hipLaunchKernelGGL(k->fn, dim3((unsigned)(a.n_shards * a.B * a.n_splits)), dim3(k->threads), k->smem, st, a);
+    hipLaunchKernelGGL(fn, grid, dim3(k->threads), k->smem, st, a);
   return check_launch("decode_mfma_kernel");
 }
 

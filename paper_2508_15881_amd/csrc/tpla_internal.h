@@ -56,7 +56,9 @@ bool decode_mfma_supported(const tpla_shape_t& sh);
 // Workgroups of the matrix-core kernel for this shape that fit on one compute
 // unit (0 = unknown).
 int decode_mfma_blocks_per_cu(const tpla_shape_t& sh);
-int launch_decode_mfma(const DecodeArgs& a, hipStream_t st);
+// ev_start / ev_stop (both or neither): events that receive the kernel's begin and end times.
+int launch_decode_mfma(const DecodeArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr,
+                       hipEvent_t ev_stop = nullptr);
 // Length of sequence b as every decode kernel uses it: clipped to what its block-table row can
 // address, so a length that disagrees with max_pages_per_seq gives wrong numbers, never a read
 // past the table.
