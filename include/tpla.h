@@ -286,8 +286,8 @@ int tpla_latent_moments(const tpla_shape_t* shape, const void* mla_pool, const i
 /*
  * PCA calibration, step 2 (Sec. 4.3.2), on the HOST and synchronous: all
  * pointers are host memory.  From the moments of n_rows latents forms the
- * covariance gram/n - mean mean^T, diagonalises it (cyclic Jacobi rotations in
- * double) and writes U float [d_c, d_c] row-major whose COLUMN k is the
+ * covariance gram/n - mean mean^T, diagonalises it (Householder tridiagonal form,
+ * then implicit QR steps, in double) and writes U float [d_c, d_c] row-major whose COLUMN k is the
  * eigenvector of the k-th largest eigenvalue (sign: its largest component is
  * positive) -- the dense U of tpla_transform_latent --, eig double [d_c]
  * descending, and frac double [g]: the share of the total variance in each

@@ -7,8 +7,8 @@
 //   * latent_gram_generic_kernel: any storage type / width (plain FMA).
 //   * latent_moments_reduce_kernel: sums the per-split partials in double, in
 //     split order (deterministic), and mirrors the triangle.
-//   * pca_basis_host: covariance = G/n - m m^T, cyclic Jacobi rotations in
-//     double, eigenvalues sorted descending; the variance fractions of the g
+//   * pca_basis_host: covariance = G/n - m m^T, Householder tridiagonalisation
+//     and implicit QR steps in double, eigenvalues sorted descending; the variance fractions of the g
 //     slices (the alpha, beta of Sec. 4.3.2).
 #include "tpla_internal.h"
 
@@ -251,58 +251,107 @@ int launch_latent_moments(const tpla_shape_t& sh, const void* mla_pool, const in
 }
 
 // ---------------------------------------------------------------------------
-// Host: eigen-decomposition of the covariance by cyclic Jacobi rotations.
-// A is symmetric d x d (row-major, overwritten); V gets the eigenvectors as ROWS.
-static int jacobi_eigen(std::vector<double>& A, std::vector<double>& V, int d, int max_sweeps) {
+// Host: eigen-decomposition of the symmetric covariance in two textbook steps:
+// Householder reflections bring A to tridiagonal form T = Q^T A Q, then
+// implicit QR steps with Wilkinson's shift diagonalise T.  A is d x d row-major
+// (overwritten); V gets the eigenvectors as ROWS (every rotation and reflection
+// then works on contiguous rows); lam gets the eigenvalues, unsorted.  Returns
+// false if the QR iteration does not converge.
+static bool symmetric_eigen(std::vector<double>& A, std::vector<double>& V, std::vector<double>& lam, int d) {
+  std::vector<double> off((size_t)std::max(d, 1), 0.0), v((size_t)d), p((size_t)d), u((size_t)d);
   std::fill(V.begin(), V.end(), 0.0);
   for (int i = 0; i < d; ++i) V[(size_t)i * d + i] = 1.0;
-  double diag2 = 0.0;
-  for (int i = 0; i < d; ++i) diag2 += A[(size_t)i * d + i] * A[(size_t)i * d + i];
-  for (int sweep = 0; sweep < max_sweeps; ++sweep) {
-    double off2 = 0.0;
-    for (int p = 0; p < d; ++p)
-      for (int q = p + 1; q < d; ++q) off2 += A[(size_t)p * d + q] * A[(size_t)p * d + q];
-    if (off2 <= 1e-30 * (diag2 + off2) || off2 == 0.0) return sweep;
-    for (int p = 0; p < d - 1; ++p)
-      for (int q = p + 1; q < d; ++q) {
-        const double apq = A[(size_t)p * d + q];
-        if (apq == 0.0) continue;
-        const double app = A[(size_t)p * d + p], aqq = A[(size_t)q * d + q];
-        if (std::fabs(apq) < 1e-300 || std::fabs(apq) <= 1e-18 * std::sqrt(std::fabs(app * aqq))) {
-          A[(size_t)p * d + q] = A[(size_t)q * d + p] = 0.0;   // negligible against both diagonal entries
-          continue;
-        }
-        // rotation that zeroes A[p][q]: tan(2 theta) = 2 apq / (aqq - app), smaller root
-        const double theta = (aqq - app) / (2.0 * apq);
-        const double t = (theta >= 0.0 ? 1.0 : -1.0) / (std::fabs(theta) + std::sqrt(theta * theta + 1.0));
-        const double c = 1.0 / std::sqrt(t * t + 1.0), s = t * c;
-        double* Ap = &A[(size_t)p * d];
-        double* Aq = &A[(size_t)q * d];
-        // rows p and q of J^T A, then the mirrored columns (A stays symmetric)
-        for (int k = 0; k < d; ++k) {
-          const double akp = Ap[k], akq = Aq[k];
-          Ap[k] = c * akp - s * akq;
-          Aq[k] = s * akp + c * akq;
-        }
-        for (int k = 0; k < d; ++k) {
-          A[(size_t)k * d + p] = Ap[k];
-          A[(size_t)k * d + q] = Aq[k];
-        }
-        Ap[p] = app - t * apq;
-        Aq[q] = aqq + t * apq;
-        Ap[q] = Aq[p] = 0.0;
-        double* Vp = &V[(size_t)p * d];
-        double* Vq = &V[(size_t)q * d];
-        for (int k = 0; k < d; ++k) {
-          const double vp = Vp[k], vq = Vq[k];
-          Vp[k] = c * vp - s * vq;
-          Vq[k] = s * vp + c * vq;
-        }
-      }
-    diag2 = 0.0;
-    for (int i = 0; i < d; ++i) diag2 += A[(size_t)i * d + i] * A[(size_t)i * d + i];
+  // ---- tridiagonal form: step k clears row/column k beyond its first off-diagonal entry ----
+  for (int k = 0; k + 2 < d; ++k) {
+    const int m = d - k - 1;                       // size of the trailing block, indices k+1 .. d-1
+    const double* x = &A[(size_t)k * d + k + 1];   // row k right of the diagonal (= column k below it)
+    double norm2 = 0.0;
+    for (int i = 0; i < m; ++i) norm2 += x[i] * x[i];
+    double tail2 = norm2 - x[0] * x[0];
+    if (tail2 <= 0.0) {                            // already tridiagonal here
+      off[k] = x[0];
+      continue;
+    }
+    const double sigma = std::sqrt(norm2);
+    const double alpha = x[0] > 0.0 ? -sigma : sigma;          // the entry that replaces x
+    for (int i = 0; i < m; ++i) v[i] = x[i];
+    v[0] -= alpha;
+    const double vnorm2 = tail2 + v[0] * v[0];
+    const double beta = 2.0 / vnorm2;                          // H = I - beta v v^T
+    // trailing block B <- H B H = B - v w^T - w v^T with p = beta B v, w = p - (beta/2)(v.p) v
+    double vp = 0.0;
+    for (int i = 0; i < m; ++i) {
+      const double* Bi = &A[(size_t)(k + 1 + i) * d + k + 1];
+      double acc = 0.0;
+      for (int j = 0; j < m; ++j) acc += Bi[j] * v[j];
+      p[i] = beta * acc;
+      vp += v[i] * p[i];
+    }
+    const double half = 0.5 * beta * vp;
+    for (int i = 0; i < m; ++i) p[i] -= half * v[i];           // p is w from here on
+    for (int i = 0; i < m; ++i) {
+      double* Bi = &A[(size_t)(k + 1 + i) * d + k + 1];
+      const double vi = v[i], wi = p[i];
+      for (int j = 0; j < m; ++j) Bi[j] -= vi * p[j] + wi * v[j];
+    }
+    off[k] = alpha;
+    // V = Q^T: rows k+1.. of V <- H (rows k+1.. of V)
+    std::fill(u.begin(), u.end(), 0.0);
+    for (int i = 0; i < m; ++i) {
+      const double* Vi = &V[(size_t)(k + 1 + i) * d];
+      const double vi = v[i];
+      for (int j = 0; j < d; ++j) u[j] += vi * Vi[j];
+    }
+    for (int i = 0; i < m; ++i) {
+      double* Vi = &V[(size_t)(k + 1 + i) * d];
+      const double bv = beta * v[i];
+      for (int j = 0; j < d; ++j) Vi[j] -= bv * u[j];
+    }
   }
-  return max_sweeps;
+  for (int i = 0; i < d; ++i) lam[i] = A[(size_t)i * d + i];
+  if (d >= 2) off[d - 2] = A[(size_t)(d - 2) * d + d - 1];
+  // ---- QR steps on the unreduced block [lo, hi] at the bottom, deflating as off-diagonals vanish ----
+  const double eps = 2.220446049250313e-16;
+  int hi = d - 1;
+  long budget = 60L * d;
+  while (hi > 0) {
+    if (std::fabs(off[hi - 1]) <= eps * (std::fabs(lam[hi - 1]) + std::fabs(lam[hi]))) {
+      off[hi - 1] = 0.0;
+      --hi;
+      continue;
+    }
+    if (--budget < 0) return false;
+    int lo = hi - 1;
+    while (lo > 0 && std::fabs(off[lo - 1]) > eps * (std::fabs(lam[lo - 1]) + std::fabs(lam[lo]))) --lo;
+    if (lo > 0) off[lo - 1] = 0.0;
+    // Wilkinson's shift: the eigenvalue of the last 2 x 2 block closer to its last entry
+    const double delta = 0.5 * (lam[hi - 1] - lam[hi]), b = off[hi - 1];
+    const double mu = lam[hi] - b * b / (delta + (delta >= 0.0 ? 1.0 : -1.0) * std::hypot(delta, b));
+    double x = lam[lo] - mu, z = off[lo];
+    for (int k = lo; k < hi; ++k) {
+      // rotation in the (k, k+1) plane that sends (x, z) to (r, 0); T <- G^T T G chases the bulge down
+      const double r = std::hypot(x, z);
+      const double c = r != 0.0 ? x / r : 1.0, sn = r != 0.0 ? -z / r : 0.0;
+      if (k > lo) off[k - 1] = r;
+      const double a = lam[k], e = off[k], cc = lam[k + 1];
+      lam[k] = a * c * c - 2.0 * e * c * sn + cc * sn * sn;
+      lam[k + 1] = a * sn * sn + 2.0 * e * c * sn + cc * c * c;
+      off[k] = (a - cc) * c * sn + e * (c * c - sn * sn);
+      x = off[k];
+      if (k + 1 < hi) {
+        z = -sn * off[k + 1];
+        off[k + 1] *= c;
+      }
+      double* Vk = &V[(size_t)k * d];
+      double* Vk1 = &V[(size_t)(k + 1) * d];
+      for (int j = 0; j < d; ++j) {
+        const double p0 = Vk[j], p1 = Vk1[j];
+        Vk[j] = c * p0 - sn * p1;
+        Vk1[j] = sn * p0 + c * p1;
+      }
+    }
+  }
+  return true;
 }
 
 int pca_basis_host(int d, int g, double n_rows, const double* sum, const double* gram, float* U, double* eig,
@@ -313,16 +362,15 @@ int pca_basis_host(int d, int g, double n_rows, const double* sum, const double*
       A[(size_t)i * d + j] = gram[(size_t)i * d + j] / n_rows - (sum[i] / n_rows) * (sum[j] / n_rows);
   for (int i = 0; i < d; ++i)                            // exact symmetry whatever the caller passed
     for (int j = i + 1; j < d; ++j) A[(size_t)j * d + i] = A[(size_t)i * d + j] = 0.5 * (A[(size_t)i * d + j] + A[(size_t)j * d + i]);
-  const int sweeps = jacobi_eigen(A, V, d, 60);
-  if (sweeps >= 60) return fail(TPLA_ERR_UNSUPPORTED, "Jacobi iteration did not converge in 60 sweeps");
+  std::vector<double> lam((size_t)d);
+  if (!symmetric_eigen(A, V, lam, d)) return fail(TPLA_ERR_UNSUPPORTED, "the QR iteration did not converge");
   std::vector<int> order(d);
   std::iota(order.begin(), order.end(), 0);
-  std::stable_sort(order.begin(), order.end(),
-                   [&](int a, int b) { return A[(size_t)a * d + a] > A[(size_t)b * d + b]; });
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return lam[a] > lam[b]; });
   double total = 0.0;
   for (int k = 0; k < d; ++k) {
     const int src = order[k];
-    eig[k] = A[(size_t)src * d + src];
+    eig[k] = lam[src];
     total += eig[k];
     // sign convention: the largest-magnitude component of every eigenvector is positive
     int big = 0;

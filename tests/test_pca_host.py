@@ -1,4 +1,4 @@
-"""Host-side PCA entry point (no GPU needed): the library's Jacobi eigen-solver
+"""Host-side PCA entry point (no GPU needed): the library's eigen-solver
 against the oracle's eigen-decomposition (numpy's LAPACK routine)."""
 import numpy as np
 import pytest
@@ -24,6 +24,37 @@ def test_pca_basis_matches_oracle(d, g):
     assert np.all(U64[np.argmax(np.abs(U64), axis=0), np.arange(d)] > 0)
     assert np.allclose(frac, orc.variance_fractions(lam, g), rtol=1e-12)
     assert abs(frac.sum() - 1.0) <= 1e-12
+
+
+def test_pca_basis_full_width_and_repeated_eigenvalues():
+    # the width of the benchmark configurations, in well under a second ...
+    import time
+    d = 512
+    F = wl.draw_anisotropic_latents(3, 4 * d, d).astype(np.float64)
+    s, G = orc.latent_moments(F)
+    t0 = time.perf_counter()
+    U, eig, frac = tp.tpla_pca_basis(d, 2, F.shape[0], s, G)
+    dt = time.perf_counter() - t0
+    _, lam = orc.pca_U(F)
+    assert np.max(np.abs(eig - lam)) <= 1e-12 * lam[0]
+    U64 = U.astype(np.float64)
+    assert np.max(np.abs(U64.T @ U64 - np.eye(d))) <= 1e-5
+    cov = np.cov(F.T, bias=True)
+    assert np.max(np.abs(U64.T @ cov @ U64 - np.diag(eig))) <= 1e-5 * lam[0]
+    assert dt < 5.0
+    # ... and a spectrum with repeated values: the eigenvectors are no longer unique, the
+    # decomposition still is one (orthonormal U, U^T C U diagonal, the right values)
+    rng = np.random.default_rng(8)
+    q, _ = np.linalg.qr(rng.standard_normal((48, 48)))
+    vals = np.repeat([5.0, 2.0, 2.0, 0.5], 12)
+    C = (q * vals) @ q.T
+    n = 1000
+    U, eig, frac = tp.tpla_pca_basis(48, 4, n, np.zeros(48), C * n)
+    assert np.allclose(eig, np.sort(vals)[::-1], atol=1e-12)
+    U64 = U.astype(np.float64)
+    assert np.max(np.abs(U64.T @ U64 - np.eye(48))) <= 1e-6
+    assert np.max(np.abs(U64.T @ C @ U64 - np.diag(eig))) <= 1e-5
+    assert np.allclose(frac, [60 / 114, 24 / 114, 24 / 114, 6 / 114])
 
 
 def test_pca_basis_diagonal_input_is_a_sorting_permutation():
