@@ -252,6 +252,9 @@ COMBINE_CASES = [
     ("mla_g1", wl.scaled(DSV3, g=1), [333, 64, 1025], (0,)),
     ("fewer_pages_than_workgroups", DSV3, [1, 64, 0, 33, 7, 60, 12, 64, 2, 50, 64, 31, 9, 40, 3, 64, 20], (0,)),
     ("kimi_H32", KIMI, [129, 1000, 5, 64], (0, 1)),
+    # every workgroup of the launch works on the one sequence: hundreds of partial results per
+    # (slice, sequence), merged 16 at a time with a moving reference
+    ("one_long_sequence", DSV3, [70000], (0, 100)),
     ("generic_f32", wl.Workload("odd", B=3, H=5, d_c=80, g=2, d_r=24, d_n=16, d_v=16, dtype="f32", seed=11), [200, 0, 65], (0, 2)),
 ]
 
