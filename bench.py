@@ -73,6 +73,33 @@ def cpu_baseline(w, model, budget_s=12.0):
                       % (n_seq, w.B, done_tokens, t_total)}
 
 
+def _shader_clock_mhz():
+    """Current shader clock from rocm-smi (None if the tool is missing or says nothing)."""
+    import re
+    import subprocess
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
+    except Exception:
+        return None
+    m = re.search(r"sclk clock level:.*?\((\d+)Mhz\)", out)
+    return int(m.group(1)) if m else None
+
+
+def _clock_while(fn, seconds=1.5, samples=3):
+    """Keeps the GPU busy with fn() for about `seconds` and samples the shader clock meanwhile."""
+    import torch
+    clocks, t0 = [], time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(50):
+            fn()
+        if (time.perf_counter() - t0) > seconds * (len(clocks) + 1) / (samples + 1) and len(clocks) < samples:
+            clocks.append(_shader_clock_mhz())          # the queue holds work for the time the tool takes
+            for _ in range(400):
+                fn()
+    torch.cuda.synchronize()
+    return clocks
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,6 +246,16 @@ def main():
             if i >= 2:
                 ceil_ms.append(ev0.elapsed_time(ev1))
     ceiling = (pools[0].numel() * pools[0].element_size()) / (float(np.median(ceil_ms)) * 1e-3) / 1e9 if ceil_ms else None
+    # shader clock under load: the decode step runs at the chip's power limit, the pure reader does not
+    power_state = None
+    if not args.skip_extras:
+        nb0 = pools[0].numel() * pools[0].element_size()
+        power_state = {
+            "what": "shader clock (MHz, rocm-smi) sampled while the GPU runs the named work back to back",
+            "decode_steps": _clock_while(lambda: step.run(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt, lens, mu)),
+            "pure_reader": _clock_while(lambda: tp.tpla_stream_read(pools[0], nb0, sink)),
+        }
+
     # modelled traffic of one split launch beyond the cache rows: queries, page table, lengths
     # (read by every workgroup's item) and the float partial results (written once)
     n_items = step.ws_bytes // (w.H * (w.dl + 2) * 4)          # partial-result slots of the plan
@@ -380,6 +417,7 @@ def main():
                       "layer_step_replayed_from_hip_graph": us_graph},
         "pool_copies_rotated": n_sets, "cache_resident": cache_resident,
         "tpla_vs_mla_output_gap": gap,
+        "power_state": power_state,
         "pca_calibration": pca,
         "prefill_mla": prefill,
         "transform": {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9},
