@@ -85,16 +85,28 @@ def _shader_clock_mhz():
     return int(m.group(1)) if m else None
 
 
-def _clock_while(fn, seconds=1.5, samples=3):
-    """Keeps the GPU busy with fn() for about `seconds` and samples the shader clock meanwhile."""
+def _socket_power_w():
+    """Current socket power from amd-smi (None if the tool is missing or says nothing)."""
+    import re
+    import subprocess
+    try:
+        out = subprocess.run(["amd-smi", "metric", "-p"], capture_output=True, text=True, timeout=10).stdout
+    except Exception:
+        return None
+    m = re.search(r"SOCKET_POWER:\s*(\d+)\s*W", out)
+    return int(m.group(1)) if m else None
+
+
+def _clock_while(fn, seconds=2.0, samples=3):
+    """Keeps the GPU busy with fn() for about `seconds`; samples (shader clock MHz, socket power W) meanwhile."""
     import torch
     clocks, t0 = [], time.perf_counter()
     while time.perf_counter() - t0 < seconds:
         for _ in range(50):
             fn()
         if (time.perf_counter() - t0) > seconds * (len(clocks) + 1) / (samples + 1) and len(clocks) < samples:
-            clocks.append(_shader_clock_mhz())          # the queue holds work for the time the tool takes
-            for _ in range(400):
+            clocks.append((_shader_clock_mhz(), _socket_power_w()))   # the queue holds work for the time the tools take
+            for _ in range(800):
                 fn()
     torch.cuda.synchronize()
     return clocks
@@ -251,7 +263,7 @@ def main():
     if not args.skip_extras:
         nb0 = pools[0].numel() * pools[0].element_size()
         power_state = {
-            "what": "shader clock (MHz, rocm-smi) sampled while the GPU runs the named work back to back",
+            "what": "[shader clock MHz (rocm-smi), socket power W (amd-smi)] sampled while the GPU runs the named work back to back",
             "decode_steps": _clock_while(lambda: step.run(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt, lens, mu)),
             "pure_reader": _clock_while(lambda: tp.tpla_stream_read(pools[0], nb0, sink)),
         }
