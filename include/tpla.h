@@ -230,6 +230,29 @@ int tpla_decode_shards_combine(const tpla_shape_t* shape,
                                float* o_lat, float* lse, void* stream);
 
 /*
+ * For callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): tpla_decode_shards_combine with the partial results of the
+ * sequence chunks kept in a device array built into the library instead of a
+ * caller's workspace.  Same arguments otherwise, same kernels, same plan, hence
+ * the same bits as tpla_decode_shards_combine.  The call allocates and frees
+ * nothing.  The array is TPLA_STATIC_SCRATCH_BYTES large on every GPU the
+ * library runs on and stays until the process ends; a call that would need
+ * more (tpla_workspace_bytes_all() tells) returns TPLA_ERR_WORKSPACE and
+ * launches nothing.  All calls on one GPU share that GPU's array: calls that
+ * overlap there (two streams, two threads) race; calls on one stream do not.
+ * Nothing in the array has to be cleared between calls: every partial result a
+ * call reads, it has written before.
+ */
+#define TPLA_STATIC_SCRATCH_BYTES (64u << 20)
+int tpla_decode_shards_combine_static(const tpla_shape_t* shape,
+                                      const void* q_lat, const void* q_pe, const void* const* shard_pools,
+                                      const int32_t* block_table, int32_t max_pages_per_seq,
+                                      const int32_t* seq_lens, int32_t n_splits,
+                                      const void* W_UV_t, float* o,
+                                      float* o_lat, float* lse, void* stream);
+
+/*
  * Output projection of the attention block (Sec. 3.3: O~ = O W^O with the
  * value up-projection kept out of W^O; Sec. 4: the quantity the devices
  * all-reduce): out[b, :] = o[b, :, :] flattened to H d_v  @  W_O.

@@ -22,7 +22,7 @@ EXPORTS = (
     "tpla_decode_shards", "tpla_append_token_sliced", "tpla_output_projection",
     "tpla_output_projection_workspace_bytes", "tpla_latent_moments_workspace_bytes", "tpla_latent_moments",
     "tpla_pca_basis", "tpla_prefill_workspace_bytes", "tpla_prefill_attention", "tpla_stream_read",
-    "tpla_decode_shards_combine", "tpla_validate_block_table",
+    "tpla_decode_shards_combine", "tpla_validate_block_table", "tpla_decode_shards_combine_static",
 )
 
 
@@ -92,6 +92,9 @@ def load_library():
     lib.tpla_decode_shards_combine.restype = ctypes.c_int
     lib.tpla_decode_shards_combine.argtypes = [shp, vp, vp, ctypes.POINTER(vp), vp, i32, vp, i32, vp, ctypes.c_size_t,
                                                vp, vp, vp, vp, vp]
+    lib.tpla_decode_shards_combine_static.restype = ctypes.c_int
+    lib.tpla_decode_shards_combine_static.argtypes = [shp, vp, vp, ctypes.POINTER(vp), vp, i32, vp, i32,
+                                                      vp, vp, vp, vp, vp]
     lib.tpla_combine_shards.restype = ctypes.c_int
     lib.tpla_combine_shards.argtypes = [shp, vp, vp, vp, vp]
     lib.tpla_profile_enable.restype = ctypes.c_int
@@ -238,6 +241,19 @@ def tpla_decode_shards_combine(shape, q_lat, q_pe, shard_pools, block_table, max
         ctypes.byref(shape), _ptr(q_lat), _ptr(q_pe), arr, _ptr(block_table), max_pages_per_seq,
         _ptr(seq_lens), n_splits, _ptr(workspace), workspace_bytes, _ptr(W_UV_t), _ptr(o), _ptr(o_lat), _ptr(lse),
         _stream(stream)))
+
+
+def tpla_decode_shards_combine_static(shape, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
+                                      n_splits, W_UV_t, o, o_lat, lse, stream=None):
+    if shard_pools is None:
+        arr = None
+    else:
+        arr = (ctypes.c_void_p * max(TPLA_MAX_G, len(shard_pools)))()
+        for i, p in enumerate(shard_pools):
+            arr[i] = _ptr(p)
+    _check(load_library().tpla_decode_shards_combine_static(
+        ctypes.byref(shape), _ptr(q_lat), _ptr(q_pe), arr, _ptr(block_table), max_pages_per_seq,
+        _ptr(seq_lens), n_splits, _ptr(W_UV_t), _ptr(o), _ptr(o_lat), _ptr(lse), _stream(stream)))
 
 
 def tpla_combine_shards(shape, o_lat, W_UV_t, o, stream=None):

@@ -5,6 +5,7 @@
 #include <string.h>
 #include <math.h>
 #include "tpla_internal.h"
+#include <mutex>
 #include <vector>
 
 namespace tpla {
@@ -214,6 +215,36 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
   return launch_combine_shards(*shape, o_lat, W_UV_t, o, st);
 }
 
+// ---- scratch of the entry point that takes no workspace ---------------------
+// The partial results of tpla_decode_shards_combine_static live in this array
+// instead of a caller's buffer.  Every device the library runs on holds its own
+// copy at its own address; host code never uses the array's name as an address
+// but the per-device pointer that hipGetSymbolAddress returned.
+static __device__ __align__(256) unsigned char scratch[TPLA_STATIC_SCRATCH_BYTES];
+
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[64] = {nullptr};   // per device, filled on the first call there
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    (void)hipGetLastError();
+    return fail(TPLA_ERR_HIP, "no current device (or a device index above 63)");
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return fail(TPLA_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return TPLA_OK;
+}
+
 }  // namespace tpla
 
 using namespace tpla;
@@ -388,6 +419,28 @@ int tpla_decode_shards_combine(const tpla_shape_t* shape, const void* q_lat, con
   if (!W_UV_t || !o) return fail(TPLA_ERR_NULL, "W_UV_t/o is NULL");
   return decode_common(shape, shape->g, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
                        n_splits, workspace, workspace_bytes, o_lat, lse, stream, W_UV_t, o);
+}
+
+int tpla_decode_shards_combine_static(const tpla_shape_t* shape, const void* q_lat, const void* q_pe,
+                                      const void* const* shard_pools, const int32_t* block_table,
+                                      int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t n_splits,
+                                      const void* W_UV_t, float* o, float* o_lat, float* lse, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!W_UV_t || !o) return fail(TPLA_ERR_NULL, "W_UV_t/o is NULL");
+  if (max_pages_per_seq < 1 || n_splits < 0)
+    return fail(TPLA_ERR_SHAPE, "max_pages_per_seq=%d n_splits=%d", max_pages_per_seq, n_splits);
+  const size_t need = workspace_for(*shape, shape->g, plan_splits(*shape, shape->g, max_pages_per_seq, n_splits));
+  if (need > (size_t)TPLA_STATIC_SCRATCH_BYTES)
+    return fail(TPLA_ERR_WORKSPACE,
+                "this call needs %zu bytes of partial results, the built-in scratch holds %zu: use "
+                "tpla_decode_shards_combine with a workspace of the caller",
+                need, (size_t)TPLA_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  return decode_common(shape, shape->g, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
+                       n_splits, ws, (size_t)TPLA_STATIC_SCRATCH_BYTES, o_lat, lse, stream, W_UV_t, o);
 }
 
 int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t, float* o,
