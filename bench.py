@@ -2,43 +2,67 @@
 """Benchmark of the TPLA shard-decode path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dsv3_32k]
+    python bench.py --traffic-calibration        (copy of known size, for scaling rocprofv3's byte counters)
 
 A step is one decode layer-step over one batch that is already resident in
 HBM: absorb the query, run the attention of all g latent slices one after the
 other on this GPU, and sum the slices through the value up-projection (the
 stand-in for the all-reduce).  The cache transform that produces the shard
 pools runs once before the timed region (it is cache-write-side work; its own
-rate is reported as `transform`).  Prints ONE JSON line.
+rate is reported as `transform`).  Before the W warm-up steps the GPU is held
+under the same step until the kernel time has settled (`settle`): the chip
+runs this step at its power limit and the first few hundred milliseconds of
+load are a clock transient.  After the headline workload the other
+model-shaped workloads run the same way and are reported under
+`other_workloads`.  Prints ONE JSON line.
 """
 import argparse
+import hashlib
 import json
 import os
+import re
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+OTHER_WORKLOADS = ("kimi_32k", "dsv3_4k", "ragged_g4")
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "decode_split_kernel_hbm_traffic.txt")
 
-# HBM traffic of one split-kernel launch measured with rocprofv3 --pmc
-# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), bytes per
-# launch; see profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC = {
-    # profiles/decode_split_kernel_dsv3_32k_hbm_traffic.txt: 1361.2 MB read + 33.8 MB written
-    "dsv3_32k": 1395.0e6,
-}
-MEASURED_TRAFFIC_ONE_SLICE = {
-    # same counters on a one-slice launch with 16 chunks per sequence: 681.8 MB read + 33.8 MB written
-    "dsv3_32k": 715.6e6,
-}
+
+def kernel_source_digest():
+    """Digest of the sources that decide the split kernel's memory traffic.  The measured-traffic
+    figures under profiles/ carry the digest they were measured at; bench.py only quotes them
+    while it still matches."""
+    h = hashlib.sha256()
+    for name in ("decode_mfma.hip", "lds_tile.h", "tpla_internal.h", "api.hip"):
+        with open(os.path.join(ROOT, "paper_2508_15881_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, launch):
+    """HBM bytes per launch of the split kernel from the rocprofv3 counter summary under profiles/
+    (`launch` = "all_slices" | "one_slice"), or None when there is no figure for this workload or
+    the kernel sources have changed since it was taken."""
+    try:
+        text = open(TRAFFIC_SUMMARY).read()
+    except OSError:
+        return None
+    m = re.search(r"^sources_digest\s*=\s*(\w+)", text, flags=re.M)
+    if not m or m.group(1) != kernel_source_digest():
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\[%s,%s\]\s*=\s*(\d+)" % (re.escape(workload), launch), text, flags=re.M)
+    return float(m.group(1)) if m else None
 
 
 def cpu_baseline(w, model, budget_s=12.0):
     """The float64 oracle, as it stands, on a bounded sample of the same workload:
     whole sequences of the batch, one at a time, until the time budget is used."""
-    import numpy as np
     from oracle import tpla_oracle as orc
     from paper_2508_15881_amd import workloads as wl
     try:
@@ -75,7 +99,6 @@ def cpu_baseline(w, model, budget_s=12.0):
 
 def _shader_clock_mhz():
     """Current shader clock from rocm-smi (None if the tool is missing or says nothing)."""
-    import re
     import subprocess
     try:
         out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
@@ -87,7 +110,6 @@ def _shader_clock_mhz():
 
 def _socket_power_w():
     """Current socket power from amd-smi (None if the tool is missing or says nothing)."""
-    import re
     import subprocess
     try:
         out = subprocess.run(["amd-smi", "metric", "-p"], capture_output=True, text=True, timeout=10).stdout
@@ -97,19 +119,207 @@ def _socket_power_w():
     return int(m.group(1)) if m else None
 
 
-def _clock_while(fn, seconds=2.0, samples=3):
+def _clock_while(fn, seconds=2.0, samples=3, burst=800):
     """Keeps the GPU busy with fn() for about `seconds`; samples (shader clock MHz, socket power W) meanwhile."""
     import torch
     clocks, t0 = [], time.perf_counter()
     while time.perf_counter() - t0 < seconds:
-        for _ in range(50):
+        for _ in range(max(1, burst // 16)):
             fn()
         if (time.perf_counter() - t0) > seconds * (len(clocks) + 1) / (samples + 1) and len(clocks) < samples:
-            clocks.append((_shader_clock_mhz(), _socket_power_w()))   # the queue holds work for the time the tools take
-            for _ in range(800):
-                fn()
+            for _ in range(burst):
+                fn()                      # the queue holds work for the time the tools take
+            clocks.append((_shader_clock_mhz(), _socket_power_w()))
     torch.cuda.synchronize()
     return clocks
+
+
+class Prepared:
+    """One workload resident in HBM: MLA pool written through S6, shard pools through S1, weights in
+    the U basis, queries, page table, and the DecodeStep buffers."""
+
+    def __init__(self, w, n_splits, dev="cuda"):
+        import numpy as np
+        import torch
+        import paper_2508_15881_amd as tp
+        from paper_2508_15881_amd import pipeline as pl
+        from paper_2508_15881_amd import workloads as wl
+        self.w = w
+        self.shape = pl.make_shape(w)
+        self.model = model = wl.draw_model_side(w)
+        self.lens_np = lens_np = model["seq_lens"]
+        P, pt = model["n_pool_pages"], w.page_tokens
+        tdt = pl.torch_dtype(w.dtype)
+        self.mla_pool = torch.full((P, pt, w.d_c + w.d_r), float("nan"), dtype=tdt, device=dev)
+
+        def draw(b):
+            return wl.draw_sequence(w, b, int(lens_np[b]), heavy=model["heavy"])
+
+        # the host draws dominate the set-up: a few sequences at a time on worker threads
+        with ThreadPoolExecutor(max_workers=6) as ex:
+            for b0 in range(0, w.B, 6):
+                for b, (c, k) in zip(range(b0, min(b0 + 6, w.B)), ex.map(draw, range(b0, min(b0 + 6, w.B)))):
+                    L = int(lens_np[b])
+                    n = (L + pt - 1) // pt
+                    slots = torch.from_numpy(wl.slot_mapping(model["block_table"][b, :n], L, pt)).to(dev)
+                    tp.tpla_write_mla_cache(self.shape, pl.to_device(c, w.dtype), pl.to_device(k, w.dtype), slots, L,
+                                            1e-6 if w.rms_prefill else -1.0, self.mla_pool)
+        hadamard = w.transform == "hadamard"
+        self.code = tp.TPLA_U_HADAMARD if hadamard else tp.TPLA_U_IDENTITY
+        self.signs = torch.from_numpy(model["signs"]).to(dev) if hadamard else None
+        self.W_UK_t, self.W_UV_t = pl.transform_weights(self.shape, self.code, self.signs, None,
+                                                        pl.to_device(model["W_UK"], w.dtype),
+                                                        pl.to_device(model["W_UV"], w.dtype))
+        self.pools = [torch.full((P, pt, w.dl + w.d_r), float("nan"), dtype=tdt, device=dev) for _ in range(w.g)]
+        pages = (lens_np.astype(np.int64) + pt - 1) // pt
+        self.used_np = np.unique(np.concatenate([model["block_table"][b, :pages[b]] for b in range(w.B)])).astype(np.int32)
+        self.used = torch.from_numpy(self.used_np).to(dev)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_tr = []
+        for _ in range(4):
+            ev0.record()
+            tp.tpla_transform_latent_paged(self.shape, self.code, self.signs, None, self.mla_pool, self.pools, self.used,
+                                           len(self.used_np))
+            ev1.record()
+            torch.cuda.synchronize()
+            t_tr.append(ev0.elapsed_time(ev1))
+        self.esz = esz = 4 if w.dtype == "f32" else 2
+        tr_bytes = len(self.used_np) * pt * ((w.d_c + w.d_r) + w.g * (w.dl + w.d_r)) * esz
+        self.transform = {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9}
+        self.q_nope = pl.to_device(model["q_nope"], w.dtype)
+        self.q_pe = pl.to_device(model["q_pe"], w.dtype)
+        self.bt = torch.from_numpy(model["block_table"]).to(dev)
+        self.lens = torch.from_numpy(lens_np).to(dev)
+        self.mu = [float(w.g)] * w.g
+        self.step = pl.DecodeStep(self.shape, model["max_pages"], n_splits)
+        # A cache that fits the 256 MB last-level cache would be re-read from there step after step:
+        # small workloads rotate over enough copies of the pools (>= 8, >= 2 GiB in all) that every
+        # step reads from HBM; the cache-resident figure is reported beside it.
+        pool_bytes = sum(p.numel() * p.element_size() for p in self.pools)
+        self.n_sets = 1 if pool_bytes >= (1 << 30) else max(8, -(-(2 << 30) // pool_bytes))
+        self.pool_sets = [self.pools] + [[p.clone() for p in self.pools] for _ in range(self.n_sets - 1)]
+        self.shard_bytes = wl.algorithmic_bytes_per_shard(w, lens_np)
+        self._i = 0
+
+    def run_step(self, pools=None):
+        """One layer-step; rotates over the pool copies unless `pools` pins one."""
+        if pools is None:
+            pools = self.pool_sets[self._i % self.n_sets]
+            self._i += 1
+        self.step.run(self.q_nope, self.q_pe, self.W_UK_t, self.W_UV_t, pools, self.bt, self.lens, self.mu)
+
+
+def settle(p, min_s, max_s, batch=40):
+    """Holds the GPU under the decode step until the split kernel's time has settled: batches of
+    `batch` event-timed steps, at least min_s, until three batch means in a row agree to 2 %
+    (at most max_s).  Returns what happened; nothing of it enters the timed region."""
+    import numpy as np
+    import torch
+    import paper_2508_15881_amd as tp
+    means, t0 = [], time.perf_counter()
+    while True:
+        tp.tpla_profile_enable(batch)
+        for _ in range(batch):
+            p.run_step()
+        torch.cuda.synchronize()
+        means.append(float(np.mean(tp.tpla_profile_collect(batch))) * 1e3)
+        el = time.perf_counter() - t0
+        agreed = len(means) >= 3 and max(means[-3:]) <= 1.02 * min(means[-3:])
+        if (el >= min_s and agreed) or el >= max_s:
+            break
+    tp.tpla_profile_enable(0)
+    return {"settle_s": el, "steps": batch * len(means), "agreed_to_2pct": bool(agreed),
+            "launch_us_first_batch": means[0], "launch_us_slowest_batch": max(means), "launch_us_last_batch": means[-1]}
+
+
+def timed_region(p, warmup, steps, pools=None):
+    """W untimed warm-up steps, then exactly K steps between two synchronisations, the split kernel of
+    every step bracketed by HIP events on the launch stream.  Returns (ms_per_step, kernel ms list)."""
+    import torch
+    import paper_2508_15881_amd as tp
+    for _ in range(warmup):
+        p.run_step(pools)
+    torch.cuda.synchronize()
+    tp.tpla_profile_enable(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        p.run_step(pools)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern_ms = tp.tpla_profile_collect(steps)
+    tp.tpla_profile_enable(0)
+    return (t1 - t0) * 1e3 / steps, kern_ms
+
+
+def launch_stats(kern_ms):
+    import numpy as np
+    k = np.asarray(kern_ms, dtype=np.float64) * 1e3
+    return {"launch_us": float(k.mean()), "launches": int(len(k)), "launch_us_min": float(k.min()),
+            "launch_us_median": float(np.median(k)), "launch_us_first10": float(k[:10].mean()),
+            "launch_us_last10": float(k[-10:].mean())}
+
+
+def one_slice_launches(p, n):
+    """The same kernel on one device's share: one slice per launch (tpla_decode_shard), event-timed."""
+    import torch
+    import paper_2508_15881_amd as tp
+    w = p.w
+    tp.tpla_profile_enable(n * w.g)
+    for _ in range(n):
+        for i in range(w.g):
+            p.step.decode(i, p.q_pe, p.pools[i], p.bt, p.lens)
+    torch.cuda.synchronize()
+    ms = tp.tpla_profile_collect(n * w.g)
+    tp.tpla_profile_enable(0)
+    return ms
+
+
+def measure_other(name, args):
+    """Settle + warm-up + timed steps of another model-shaped workload."""
+    import numpy as np
+    from paper_2508_15881_amd import workloads as wl
+    w = wl.CONFIGS[name]
+    p = Prepared(w, 0)
+    st = settle(p, min(args.settle_s, 0.5), max(1.5, args.settle_s))
+    steps = max(args.steps, 50)
+    ms_per_step, kern_ms = timed_region(p, args.warmup, steps)
+    ls = launch_stats(kern_ms)
+    launch_bytes = w.g * p.shard_bytes
+    achieved = launch_bytes / (ls["launch_us"] * 1e-6) / 1e9
+    one = one_slice_launches(p, 30)
+    one_us = float(np.mean(one)) * 1e3
+    out = {"config": {"B": w.B, "H": w.H, "d_c": w.d_c, "g": w.g, "context_max": int(p.lens_np.max()),
+                      "tokens": int(p.lens_np.sum()), "transform": w.transform, "pages_permuted": bool(w.permute_pages)},
+           "ms_per_step": ms_per_step, "value_GB/s": launch_bytes / (ms_per_step * 1e-3) / 1e9,
+           "steps": steps, "settle": st, "pool_copies_rotated": p.n_sets,
+           "roofline": dict({"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": achieved / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": launch_bytes,
+                             "traffic": measured_traffic(name, "all_slices")}, **ls),
+           "one_slice": {"launch_us": one_us, "frac": p.shard_bytes / (one_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
+           "transform_GB/s_read_plus_write": p.transform["GB/s_read_plus_write"]}
+    return out
+
+
+def traffic_calibration():
+    """Kernels of known HBM traffic, for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings:
+    five identity-mode tpla_transform_latent calls that copy 1 GiB each (read 1 GiB, write 1 GiB)
+    and five tpla_stream_read calls over the same 1 GiB (read only)."""
+    import torch
+    import paper_2508_15881_amd as tp
+    tp.load_library()
+    d_c, n_rows = 512, (1 << 30) // (512 * 2)
+    shape = tp.TplaShape(1, 1, d_c, 1, 64, 128, 128, 64, tp.TPLA_BF16, 1.0)
+    src = torch.ones((n_rows, d_c), dtype=torch.bfloat16, device="cuda")
+    dst = torch.empty_like(src)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    for _ in range(5):
+        tp.tpla_transform_latent(shape, tp.TPLA_U_IDENTITY, 0, None, None, src, dst, n_rows, 1)
+    for _ in range(5):
+        tp.tpla_stream_read(src, src.numel() * 2, sink)
+    torch.cuda.synchronize()
+    print(json.dumps({"copied_bytes_per_transform_axis_launch": src.numel() * 2,
+                      "read_bytes_per_stream_read_launch": src.numel() * 2 - (src.numel() * 2) % 20480, "launches_each": 5}))
 
 
 def main():
@@ -119,12 +329,18 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="dsv3_32k")
     ap.add_argument("--n-splits", type=int, default=0)
+    ap.add_argument("--settle-s", type=float, default=1.0,
+                    help="hold the GPU under the decode step for at least this long before the warm-up steps "
+                         "(until the kernel time has settled, at most three times as long); 0 = off")
+    ap.add_argument("--others", default=",".join(OTHER_WORKLOADS),
+                    help="comma-separated workloads reported under other_workloads after the headline ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--set", action="append", default=[], metavar="FIELD=VALUE",
                     help="override an integer field of the workload, e.g. --set H=128 --set B=16")
     ap.add_argument("--skip-extras", action="store_true",
-                    help="only the timed steps: no one-slice loop, stage timings or MLA reference "
+                    help="only the timed steps: no one-slice loop, stage timings, MLA reference or other workloads "
                          "(keeps every launch of the decode kernel in a profile identical)")
+    ap.add_argument("--traffic-calibration", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (all g latent slices are computed on it and "
@@ -141,106 +357,42 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     tp.load_library()           # fails loudly when the HIP library is not built
+    if args.traffic_calibration:
+        traffic_calibration()
+        return
     dev = "cuda"
     w = wl.CONFIGS[args.workload]
     if args.set:
         w = wl.scaled(w, name=w.name + "(" + ",".join(args.set) + ")",
                       **{k: int(v) for k, v in (kv.split("=") for kv in args.set)})
-    shape = pl.make_shape(w)
-    model = wl.draw_model_side(w)
-    lens_np = model["seq_lens"]
-    P = model["n_pool_pages"]
-    pt = w.page_tokens
-    tdt = pl.torch_dtype(w.dtype)
 
     # ---- inputs into HBM (untimed): MLA-style pool, then the shard pools --------
-    mla_pool = torch.full((P, pt, w.d_c + w.d_r), float("nan"), dtype=tdt, device=dev)
-    for b in range(w.B):
-        L = int(lens_np[b])
-        n = (L + pt - 1) // pt
-        c, k = wl.draw_sequence(w, b, L, heavy=model["heavy"])
-        slots = torch.from_numpy(wl.slot_mapping(model["block_table"][b, :n], L, pt)).to(dev)
-        tp.tpla_write_mla_cache(shape, pl.to_device(c, w.dtype), pl.to_device(k, w.dtype), slots, L,
-                                1e-6 if w.rms_prefill else -1.0, mla_pool)
-    hadamard = w.transform == "hadamard"
-    code = tp.TPLA_U_HADAMARD if hadamard else tp.TPLA_U_IDENTITY
-    signs = torch.from_numpy(model["signs"]).to(dev) if hadamard else None
-    W_UK_t, W_UV_t = pl.transform_weights(shape, code, signs, None, pl.to_device(model["W_UK"], w.dtype),
-                                          pl.to_device(model["W_UV"], w.dtype))
-    pools = [torch.full((P, pt, w.dl + w.d_r), float("nan"), dtype=tdt, device=dev) for _ in range(w.g)]
-    pages = (lens_np.astype(np.int64) + pt - 1) // pt
-    used_np = np.unique(np.concatenate([model["block_table"][b, :pages[b]] for b in range(w.B)])).astype(np.int32)
-    used = torch.from_numpy(used_np).to(dev)
+    p = Prepared(w, args.n_splits)
+    shape, model, lens_np, pt, tdt, esz = p.shape, p.model, p.lens_np, w.page_tokens, pl.torch_dtype(w.dtype), p.esz
+    mla_pool, pools, used, used_np = p.mla_pool, p.pools, p.used, p.used_np
+    q_nope, q_pe, W_UK_t, W_UV_t, bt, lens, mu, step = p.q_nope, p.q_pe, p.W_UK_t, p.W_UV_t, p.bt, p.lens, p.mu, p.step
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t_tr = []
-    for _ in range(6):
-        ev0.record()
-        tp.tpla_transform_latent_paged(shape, code, signs, None, mla_pool, pools, used, len(used_np))
-        ev1.record()
-        torch.cuda.synchronize()
-        t_tr.append(ev0.elapsed_time(ev1))
-    esz = 4 if w.dtype == "f32" else 2
-    tr_bytes = len(used_np) * pt * ((w.d_c + w.d_r) + w.g * (w.dl + w.d_r)) * esz
 
-    q_nope = pl.to_device(model["q_nope"], w.dtype)
-    q_pe = pl.to_device(model["q_pe"], w.dtype)
-    bt = torch.from_numpy(model["block_table"]).to(dev)
-    lens = torch.from_numpy(lens_np).to(dev)
-    mu = [float(w.g)] * w.g
-    step = pl.DecodeStep(shape, model["max_pages"], args.n_splits)
-
-    # A cache that fits the 256 MB last-level cache would be re-read from there step after step:
-    # small workloads rotate over enough copies of the pools (>= 8, >= 2 GiB in all) that every
-    # step reads from HBM; the cache-resident figure is reported beside it.
-    pool_bytes = sum(p.numel() * p.element_size() for p in pools)
-    n_sets = 1 if pool_bytes >= (1 << 30) else max(8, -(-(2 << 30) // pool_bytes))
-    pool_sets = [pools] + [[p.clone() for p in pools] for _ in range(n_sets - 1)]
-
-    for i in range(args.warmup):
-        step.run(q_nope, q_pe, W_UK_t, W_UV_t, pool_sets[i % n_sets], bt, lens, mu)
-    torch.cuda.synchronize()
-
-    # ---- timed region: exactly K steps, split kernel bracketed by HIP events ----
-    # (all g slices share one decode launch: one bracket per step)
-    tp.tpla_profile_enable(args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step.run(q_nope, q_pe, W_UK_t, W_UV_t, pool_sets[i % n_sets], bt, lens, mu)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    kern_ms = tp.tpla_profile_collect(args.steps)
+    # ---- settle, W warm-up steps, then the timed region: exactly K steps ----------
+    n_sets_rotated = p.n_sets
+    settled = settle(p, args.settle_s, 3.0 * args.settle_s) if args.settle_s > 0 else None
+    ms_per_step, kern_ms = timed_region(p, args.warmup, args.steps)
 
     cache_resident = None
-    if n_sets > 1:
-        tp.tpla_profile_enable(args.steps)
-        torch.cuda.synchronize()
-        tc0 = time.perf_counter()
-        for i in range(args.steps):
-            step.run(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt, lens, mu)
-        torch.cuda.synchronize()
-        tc1 = time.perf_counter()
-        kc = tp.tpla_profile_collect(args.steps)
-        cache_resident = {"ms_per_step": (tc1 - tc0) * 1e3 / args.steps, "split_kernel_us": float(np.mean(kc)) * 1e3,
+    if p.n_sets > 1:
+        ms_c, kc = timed_region(p, 0, args.steps, pools)
+        cache_resident = {"ms_per_step": ms_c, "split_kernel_us": float(np.mean(kc)) * 1e3,
                           "note": "same step re-reading one copy of the pools (it fits the last-level cache)"}
-        del pool_sets[1:]
+        del p.pool_sets[1:]
+        p.n_sets = 1
 
     # one device's share: the same kernel launched for one slice at a time
-    n_one = 0 if args.skip_extras else min(args.steps, 200)
-    one_ms = [float("nan")]
-    if n_one:
-        tp.tpla_profile_enable(n_one * w.g)
-        for _ in range(n_one):
-            for i in range(w.g):
-                step.decode(i, q_pe, pools[i], bt, lens)
-        torch.cuda.synchronize()
-        one_ms = tp.tpla_profile_collect(n_one * w.g)
-    tp.tpla_profile_enable(0)
+    one_ms = one_slice_launches(p, min(args.steps, 200)) if not args.skip_extras else [float("nan")]
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    shard_bytes = wl.algorithmic_bytes_per_shard(w, lens_np)
+    shard_bytes = p.shard_bytes
     value = w.g * shard_bytes / (ms_per_step * 1e-3) / 1e9
-    kern_avg_ms = float(np.mean(kern_ms))
+    ls = launch_stats(kern_ms)
+    kern_avg_ms = ls["launch_us"] * 1e-3
     launch_bytes = w.g * shard_bytes
     achieved = launch_bytes / (kern_avg_ms * 1e-3) / 1e9
     one_avg_ms = float(np.mean(one_ms))
@@ -249,24 +401,15 @@ def main():
     # what this machine delivers to a kernel that only reads (same pool, 128-bit streaming loads):
     # boxes differ by several per cent, and so does this ceiling
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    nb0 = pools[0].numel() * pools[0].element_size()
     ceil_ms = []
     if not args.skip_extras:
-        nb = pools[0].numel() * pools[0].element_size()
         for i in range(12):
-            ev0.record(); tp.tpla_stream_read(pools[i % w.g], nb, sink); ev1.record()
+            ev0.record(); tp.tpla_stream_read(pools[i % w.g], nb0, sink); ev1.record()
             torch.cuda.synchronize()
             if i >= 2:
                 ceil_ms.append(ev0.elapsed_time(ev1))
-    ceiling = (pools[0].numel() * pools[0].element_size()) / (float(np.median(ceil_ms)) * 1e-3) / 1e9 if ceil_ms else None
-    # shader clock under load: the decode step runs at the chip's power limit, the pure reader does not
-    power_state = None
-    if not args.skip_extras:
-        nb0 = pools[0].numel() * pools[0].element_size()
-        power_state = {
-            "what": "[shader clock MHz (rocm-smi), socket power W (amd-smi)] sampled while the GPU runs the named work back to back",
-            "decode_steps": _clock_while(lambda: step.run(q_nope, q_pe, W_UK_t, W_UV_t, pools, bt, lens, mu)),
-            "pure_reader": _clock_while(lambda: tp.tpla_stream_read(pools[0], nb0, sink)),
-        }
+    ceiling = nb0 / (float(np.median(ceil_ms)) * 1e-3) / 1e9 if ceil_ms else None
 
     # modelled traffic of one split launch beyond the cache rows: queries, page table, lengths
     # (read by every workgroup's item) and the float partial results (written once)
@@ -306,7 +449,7 @@ def main():
         wo_out = torch.empty((w.B, w.d_model), dtype=torch.float32, device=dev)
         us_wo = timed(lambda: tp.tpla_output_projection(shape, step.o, W_O, w.d_model, wo_ws, wo_ws_b, wo_out))
 
-    # the same step replayed from a HIP graph (launch overhead of its four kernels removed);
+    # the same step replayed from a HIP graph (launch overhead of its kernels removed);
     # informational: the timed region above launches eagerly so that its kernels can be bracketed
     us_graph = float("nan")
     if not args.skip_extras:
@@ -314,7 +457,7 @@ def main():
         for _ in range(20):
             graph.replay()
         torch.cuda.synchronize()
-        n_rep = min(args.steps, 300)
+        n_rep = min(max(args.steps, 100), 300)
         tg = time.perf_counter()
         for _ in range(n_rep):
             graph.replay()
@@ -336,7 +479,7 @@ def main():
         U_np, eig, frac = tp.tpla_pca_basis(w.d_c, w.g, n_used * pt, m_sum.cpu().numpy(), m_gram.cpu().numpy())
         eig_s = time.perf_counter() - tcpu
         U_dev = torch.from_numpy(U_np).to(dev)
-        scratch_pools = [torch.empty_like(p) for p in pools]
+        scratch_pools = [torch.empty_like(q) for q in pools]
         us_dense = timed(lambda: tp.tpla_transform_latent_paged(shape, tp.TPLA_U_DENSE, None, U_dev, mla_pool,
                                                                 scratch_pools, used, n_used), reps=3)
         del scratch_pools, ws_m
@@ -346,7 +489,7 @@ def main():
 
     # Prefill of one context-length sequence with un-absorbed MLA (the other phase of Sec. 4.5;
     # MFMA-bound, not part of the decode step): key/value up-projection + causal attention
-    prefill = None
+    prefill, prefill_fn = None, None
     if not args.skip_extras and w.dtype == "bf16" and w.d_n == 128 and w.d_v == 128 and w.d_r == 64:
         Lp = int(lens_np.max())
         shape_p = pl.make_shape(wl.scaled(w, B=1, g=1))
@@ -360,13 +503,27 @@ def main():
         pws = torch.empty(pws_b, dtype=torch.uint8, device=dev)
         po = torch.empty((Lp, w.H, w.d_v), dtype=torch.float32, device=dev)
         W_UK0, W_UV0 = pl.to_device(model["W_UK"], w.dtype), pl.to_device(model["W_UV"], w.dtype)
-        us_pf = timed(lambda: tp.tpla_prefill_attention(shape_p, pq_nope, pq_pe, pc, pk, W_UK0, W_UV0, pcu, Lp, Lp,
-                                                        pws, pws_b, po), reps=3)
+
+        def prefill_fn():
+            tp.tpla_prefill_attention(shape_p, pq_nope, pq_pe, pc, pk, W_UK0, W_UV0, pcu, Lp, Lp, pws, pws_b, po)
+        us_pf = timed(prefill_fn, reps=3)
         flop = 2.0 * (w.d_n + w.d_r + w.d_v) * w.H * (Lp * (Lp + 1) / 2) + 2.0 * Lp * w.d_c * w.H * (w.d_n + w.d_v)
         prefill = {"tokens": Lp, "heads": w.H, "ms": us_pf * 1e-3, "TFLOP/s": flop / (us_pf * 1e-6) / 1e12,
                    "bound": "mfma", "peak_TFLOP/s": 2500.0, "frac": flop / (us_pf * 1e-6) / 1e12 / 2500.0,
                    "flop_counted": "causal half of QK^T and PV plus the key/value up-projection"}
-        del pq_nope, pq_pe, pws, po
+
+    # shader clock and socket power under load: the decode step runs at the chip's power limit, the pure reader does not
+    power_state = None
+    if not args.skip_extras:
+        power_state = {
+            "what": "[shader clock MHz (rocm-smi), socket power W (amd-smi)] sampled while the GPU runs the named work back to back",
+            "decode_steps": _clock_while(lambda: p.run_step(pools)),
+            "pure_reader": _clock_while(lambda: tp.tpla_stream_read(pools[0], nb0, sink)),
+        }
+        if prefill_fn is not None:
+            power_state["prefill_attention"] = _clock_while(prefill_fn, burst=8)
+    if prefill_fn is not None:
+        del pq_nope, pq_pe, pws, po, prefill_fn
 
     # MLA under head-split tensor parallelism, one device's share: the same H heads
     # over the unsliced 576-wide cache (the MLA pool is exactly the g = 1 layout).
@@ -375,10 +532,10 @@ def main():
     shape1 = pl.make_shape(w1)
     step1 = pl.DecodeStep(shape1, model["max_pages"], 0)
     step1.absorb(q_nope, W_UK_t, None)
-    n_mla = 0 if args.skip_extras else min(args.steps, 100)
+    n_mla = 0 if args.skip_extras else min(max(args.steps, 100), 200)
     mla_ms = float("nan")
     if n_mla:
-        for _ in range(3):
+        for _ in range(100):
             step1.decode(0, q_pe, mla_pool, bt, lens)
         tp.tpla_profile_enable(n_mla)
         for _ in range(n_mla):
@@ -398,7 +555,7 @@ def main():
         step1.decode(0, q_pe, mla_pool, bt, lens)
         step1.combine(W_UV0)
         o_mla = step1.o.double()
-        scratch = [torch.empty_like(p) for p in pools]
+        scratch = [torch.empty_like(q) for q in pools]
         stepx = pl.DecodeStep(shape, model["max_pages"], 0)
         gap = {"what": "|o_TPLA - o_MLA|_F / |o_MLA|_F over the batch, mu_i = g"}
         sg = torch.from_numpy(model["signs"]).to(dev)
@@ -420,6 +577,7 @@ def main():
                    "step": "absorb + decode of all g slices (one split launch) + split merge and combine (one kernel), on one GPU"},
         "us_per_layer_step": ms_per_step * 1e3,
         "pct_hbm_roofline_step": 100.0 * value / HBM_PEAK_GBS,
+        "settle": settled,
         "stages_us": {"absorb": us_absorb, "decode_shards(all slices, split+merge)": us_decode_all,
                       "decode_shard(one slice, split+merge)": us_decode, "combine": us_combine,
                       "decode_shards_combine(all slices, split + merge-and-combine kernel)": us_decode_combine,
@@ -427,33 +585,35 @@ def main():
                       "output_projection(W_O, not in the step)": us_wo,
                       "one_device_share": us_absorb / w.g + us_decode + us_combine,
                       "layer_step_replayed_from_hip_graph": us_graph},
-        "pool_copies_rotated": n_sets, "cache_resident": cache_resident,
+        "pool_copies_rotated": n_sets_rotated, "cache_resident": cache_resident,
         "tpla_vs_mla_output_gap": gap,
         "power_state": power_state,
         "pca_calibration": pca,
         "prefill_mla": prefill,
-        "transform": {"us": min(t_tr) * 1e3, "GB/s_read_plus_write": tr_bytes / (min(t_tr) * 1e-3) / 1e9},
-        "roofline": {"bound": "hbm", "kernel": "decode split kernel, all g slices in one launch (tpla_decode_shards)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),
-                     "launch_us": kern_avg_ms * 1e3, "launches": len(kern_ms),
-                     "launch_us_min": float(np.min(kern_ms)) * 1e3, "launch_us_median": float(np.median(kern_ms)) * 1e3,
-                     "launch_us_first10": float(np.mean(kern_ms[:10])) * 1e3, "launch_us_last10": float(np.mean(kern_ms[-10:])) * 1e3,
-                     "algorithmic_bytes_per_launch": launch_bytes, "modelled_all_traffic_bytes": all_traffic,
-                     "streaming_read_ceiling_GB/s": ceiling,
-                     "frac_of_streaming_read_ceiling": (achieved / ceiling) if ceiling else None},
+        "transform": p.transform,
+        "roofline": dict({"bound": "hbm", "kernel": "decode split kernel, all g slices in one launch (tpla_decode_shards)",
+                          "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, "all_slices"),
+                          "traffic_source": "profiles/decode_split_kernel_hbm_traffic.txt (quoted only while the kernel sources match the digest recorded there)",
+                          "algorithmic_bytes_per_launch": launch_bytes, "modelled_all_traffic_bytes": all_traffic,
+                          "streaming_read_ceiling_GB/s": ceiling,
+                          "frac_of_streaming_read_ceiling": (achieved / ceiling) if ceiling else None}, **ls),
         "roofline_one_slice": {"bound": "hbm", "kernel": "decode split kernel, one slice per launch (tpla_decode_shard)",
                                "achieved": one_achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                               "frac": one_achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_ONE_SLICE.get(w.name),
+                               "frac": one_achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, "one_slice"),
                                "launch_us": one_avg_ms * 1e3, "launches": len(one_ms),
                                "algorithmic_bytes_per_launch": shard_bytes},
         "mla_tp_reference": {"what": "same kernel, g=1: H heads over the unsliced (d_c + d_r)-wide cache = one device of MLA with head-split TP",
                              "launch_us": mla_ms * 1e3, "GB/s": mla_bytes / (mla_ms * 1e-3) / 1e9,
+                             "frac": mla_bytes / (mla_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                              "time_ratio_mla_over_tpla_slice": mla_ms / one_avg_ms,
                              "bytes_ratio": mla_bytes / shard_bytes},
         "paper_context": "paper reports only ratios: TPLA vs MLA decode 1.79x (DeepSeek-V3) / 1.93x (Kimi-K2) at 32K, "
                          "2 GPUs of an unnamed model, BF16, FlashAttention-3, MoE removed (Sec. 5.4.1)",
     }
+    # the other model-shaped workloads, one after the other, each with its own pools
+    if not args.skip_extras and args.others:
+        out["other_workloads"] = {name: measure_other(name, args) for name in args.others.split(",") if name != w.name}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, model)
     print(json.dumps(out).replace("NaN", "null"))

@@ -12,9 +12,12 @@
  *     and weights: TPLA_F32 (float storage, float arithmetic) or TPLA_BF16
  *     (bfloat16 storage, float accumulation).  Softmax statistics, latent
  *     outputs and final outputs are always float.
- *   - Return value: TPLA_OK (0) or a negative TPLA_ERR_* code.  On error
- *     nothing has been launched and tpla_last_error() (thread-local, static
- *     storage, never NULL) describes the failure.  Argument validation only
+ *   - Return value: TPLA_OK (0) or a negative TPLA_ERR_* code, and
+ *     tpla_last_error() (thread-local, static storage, never NULL) describes
+ *     the failure.  When argument validation fails nothing has been launched;
+ *     TPLA_ERR_HIP (the runtime refused a launch or a kernel attribute) can
+ *     come after earlier kernels of the same call were enqueued, and the
+ *     outputs are then undefined.  Argument validation only
  *     looks at the host-visible values; page ids and sequence lengths that
  *     live in device memory are trusted (seq_lens[b] <= max_pages_per_seq *
  *     page_tokens, page ids inside the pool).

@@ -56,6 +56,36 @@ def build(verbose=True):
     return LIB_PATH
 
 
+def build_host_sanitized(driver_cpp, exe_path, verbose=False):
+    """Second build configuration, for the CPU machine only: the same sources with AddressSanitizer
+    and UndefinedBehaviorSanitizer on the HOST code (device code is compiled as usual, unsanitised),
+    linked with a C++ driver into an executable -- the sanitizer runtime is linked statically into
+    it, so nothing has to be preloaded.  Used by tests/test_host_sanitizers.py; never run on a GPU machine."""
+    obj_dir = os.path.join(OBJ_DIR, "host_sanitized")
+    os.makedirs(obj_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    flags = ["--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fno-omit-frame-pointer",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+             "-I", INCLUDE, "-I", CSRC] + san
+    objs = [os.path.join(obj_dir, s.replace(".hip", ".o")) for s in SOURCES]
+
+    def compile_one(i):
+        return _run([HIPCC] + flags + ["-c", os.path.join(CSRC, SOURCES[i]), "-o", objs[i]])
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        outs = list(ex.map(compile_one, range(len(SOURCES))))
+    drv_obj = os.path.join(obj_dir, "driver.o")
+    host_san = ["-fsanitize=address,undefined", "-fno-gpu-sanitize", "-fno-sanitize-recover=undefined",
+                "-Wno-unused-command-line-argument"]
+    outs.append(_run([HIPCC, "-O1", "-g", "-std=c++17", "-I", INCLUDE, "-I", CSRC, "--offload-arch=gfx950", "-x", "hip", driver_cpp,
+                      "-c", "-o", drv_obj] + san + ["-Wno-unused-command-line-argument"]))
+    outs.append(_run([HIPCC] + host_san + objs + [drv_obj, "-o", exe_path]))
+    if verbose:
+        print("\n".join(o for o in outs if o))
+    return exe_path
+
+
 if __name__ == "__main__":
     build()
     sys.exit(0)

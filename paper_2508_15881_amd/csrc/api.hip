@@ -559,6 +559,7 @@ int tpla_profile_enable(int32_t max_records) {
 
 int tpla_profile_collect(float* ms, int32_t capacity, int32_t* n_records) {
   if (!ms || !n_records) return fail(TPLA_ERR_NULL, "ms/n_records is NULL");
+  if (capacity < 0) return fail(TPLA_ERR_SHAPE, "capacity=%d", capacity);
   int n = g_prof.used < capacity ? g_prof.used : capacity;
   for (int i = 0; i < n; ++i) {
     if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess ||

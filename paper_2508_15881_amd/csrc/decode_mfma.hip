@@ -332,13 +332,13 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
     }
     const int excl = base + incl - pg;
     if (w == 0 && v < n_v && threadIdx.x < 64) a.plan[v] = excl;
-    unsigned long long hit = __ballot(pg > 0 && excl < end && excl + pg > start);
+    int p0l, p1l;
+    unsigned long long hit = __ballot(balanced_item(start, end, excl, pg, &p0l, &p1l));
     while (hit) {
       const int src = __builtin_ctzll(hit);
       hit &= hit - 1;
-      const int e = __shfl(excl, src), n = __shfl(pg, src), Ls = __shfl(L, src);
+      const int Ls = __shfl(L, src), p0 = __shfl(p0l, src), p1 = __shfl(p1l, src);
       const int vs = v0 + src;
-      const int p0 = max(start, e) - e, p1 = min(end, e + n) - e;
       decode_item<DL, DR, NW, TOK, NSTAGE>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
     }
     base += __shfl(incl, 63);

@@ -8,9 +8,6 @@
 
 namespace tpla {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float LAZY = 8.0f;   // log2 units: the softmax reference lags the running maximum by at most this
 

@@ -19,9 +19,7 @@
 
 namespace tpla {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int GB = 128;                  // block edge of the Gram matrix
 constexpr int GT = 32;                   // rows per staged tile (one MFMA k-step)

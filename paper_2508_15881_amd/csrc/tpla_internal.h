@@ -71,7 +71,7 @@ __device__ __forceinline__ int seq_len_clipped(const DecodeArgs& a, int b) {
 // Balanced plan: workgroup w of W owns the pages [w T / W, (w+1) T / W) of the T pages of all
 // (slice, sequence) pairs laid end to end.  The workgroup whose range holds page c, 0 <= c < T
 // (32-bit arithmetic when the products fit).
-__device__ __forceinline__ int balanced_owner(int c, int T, int W) {
+__host__ __device__ __forceinline__ int balanced_owner(int c, int T, int W) {
   if ((long long)T * W <= 2147483647LL) {
     unsigned w = (unsigned)c * (unsigned)W / (unsigned)T;
     while (w + 1 < (unsigned)W && (w + 1) * (unsigned)T / (unsigned)W <= (unsigned)c) ++w;
@@ -84,10 +84,19 @@ __device__ __forceinline__ int balanced_owner(int c, int T, int W) {
   return (int)w;
 }
 // Whether workgroup w's range meets the pages [c0, c1) (only in doubt when T < W: some ranges are empty).
-__device__ __forceinline__ bool balanced_range_meets(long long w, long long T, long long W, long long c0,
-                                                     long long c1) {
+__host__ __device__ __forceinline__ bool balanced_range_meets(long long w, long long T, long long W, long long c0,
+                                                              long long c1) {
   const long long lo = w * T / W, hi = (w + 1) * T / W;
   return (lo > c0 ? lo : c0) < (hi < c1 ? hi : c1);
+}
+// The work item of a workgroup that owns the pages [start, end) in a sequence whose n pages begin at
+// page e of the laid-out order: its pages [*p0, *p1) counted inside the sequence.  False when the two
+// ranges share no page (also for an empty workgroup range that lies inside the sequence).
+__host__ __device__ __forceinline__ bool balanced_item(int start, int end, int e, int n, int* p0, int* p1) {
+  const int lo = start > e ? start : e, hi = end < e + n ? end : e + n;
+  *p0 = lo - e;
+  *p1 = hi - e;
+  return lo < hi;
 }
 
 int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st);
@@ -172,6 +181,9 @@ __device__ __forceinline__ void store_from_f32(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_from_f32(bf16_t* p, float v) { *p = (bf16_t)v; }
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // 8 consecutive elements of a row, as floats.
 struct Vec8 {

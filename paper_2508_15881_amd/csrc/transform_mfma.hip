@@ -14,28 +14,14 @@
 //     adjacent output columns: 8-byte stores, 128 contiguous bytes per 16 lanes.
 // The cross-lane butterflies of the plain-ALU kernel (about 150 instructions
 // per row) become 4 MFMAs per row.
-#include "tpla_internal.h"
+#include "lds_tile.h"
 
 #include <mutex>
-#include <utility>
 
 namespace tpla {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-template <int... I, typename F>
-__device__ __forceinline__ void tm_static_for_impl(std::integer_sequence<int, I...>, F&& f) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-// Compile-time loop: f receives std::integral_constant<int, i>.
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  tm_static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
-}
 
 __device__ __forceinline__ unsigned opaque(unsigned x) {
   asm volatile("" : "+v"(x));

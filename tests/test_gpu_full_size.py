@@ -67,8 +67,9 @@ def _run_config(name, sample):
                               w.g, w.sm_scale, U=U64, mu=mu)
         assert rel_err(o_lat[:, b:b + 1], ref["O_lat"]) <= TOL[w.dtype], (name, b)
         assert rel_err(o[b:b + 1], ref["o"]) <= TOL[w.dtype], (name, b)
-        assert np.max(np.abs(lse[:, b:b + 1] - ref["lse"])) <= 2e-2, (name, b)
-        print(f"  sequence {b} (L={int(lens[b])}) ok", flush=True)
+        lse_err = float(np.max(np.abs(lse[:, b:b + 1] - ref["lse"])))
+        assert lse_err <= 1e-2, (name, b)
+        print(f"  sequence {b} (L={int(lens[b])}) ok, lse err {lse_err:.3g}, max |lse| {float(np.max(np.abs(ref['lse']))):.3g}", flush=True)
 
 
 @pytest.mark.timeout(300)

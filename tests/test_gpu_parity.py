@@ -725,7 +725,12 @@ def test_pca_whole_path_bf16():
     ref = orc.tpla_decode(wl.as_f64(m["q_nope"], "bf16"), wl.as_f64(m["q_pe"], "bf16"), wl.as_f64(m["W_UK"], "bf16"),
                           wl.as_f64(m["W_UV"], "bf16"), c64, k64, w.g, w.sm_scale, U=U_ref, mu=mu_ref)
     assert rel_err(o.cpu().numpy(), ref["o"]) <= TOL["bf16"]
-    assert np.max(np.abs(step.lse.cpu().numpy() - ref["lse"])) <= 2e-2
+    # lse: absolute 1e-2 as everywhere, plus what the score factors add here: mu_i = 1 / share_i reaches
+    # ~55 on the low-variance slice and multiplies the bf16 rounding of q_lat and of the stored cache (and
+    # the 2e-3 the two eigen-decompositions may differ by) into the scores
+    lse_err = float(np.max(np.abs(step.lse.cpu().numpy() - ref["lse"])))
+    print("  lse err %.3g, mu %s" % (lse_err, ["%.3g" % x for x in mu]), flush=True)
+    assert lse_err <= 1e-2 + 5e-4 * max(mu)
     # sign-invariant view of the latent-space tensors
     assert rel_err(np.abs(step.o_lat.cpu().numpy()), np.abs(ref["O_lat"])) <= TOL["bf16"]
 
@@ -851,7 +856,8 @@ def test_whole_path_bf16_scaled_configs(name, lens):
     assert rel_err(wl.as_f64(pl.from_device_bits(step.q_lat), "bf16"), ref["Q_lat"]) <= TOL["bf16"]
     assert rel_err(step.o_lat.cpu().numpy(), ref["O_lat"]) <= TOL["bf16"]
     assert rel_err(o.cpu().numpy(), ref["o"]) <= TOL["bf16"]
-    assert np.max(np.abs(step.lse.cpu().numpy() - ref["lse"])) <= 2e-2
+    print("  lse err %.3g" % np.max(np.abs(step.lse.cpu().numpy() - ref["lse"])), flush=True)
+    assert np.max(np.abs(step.lse.cpu().numpy() - ref["lse"])) <= 1e-2
 
 
 def test_tpla_vs_mla_gap_matches_the_oracles_gap():
