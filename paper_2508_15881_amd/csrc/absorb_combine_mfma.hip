@@ -311,14 +311,14 @@ __global__ void __launch_bounds__(MC_NW * 64) merge_combine_mfma_kernel(DecodeAr
     } else {
       T = a.plan[n_v];
       c0 = a.plan[vb];
-      w0 = balanced_owner(c0, T, a.n_wg);
-      cnt = balanced_owner(c0 + n_pages - 1, T, a.n_wg) - w0 + 1;
+      w0 = balanced_owner(a.geom, c0, T);
+      cnt = balanced_owner(a.geom, c0 + n_pages - 1, T) - w0 + 1;
       first = w0 + vb;
-      sparse = T < a.n_wg;
+      sparse = plan_sparse(a.geom, T);
     }
     auto live = [&](int s) -> bool {
       if (s >= cnt) return false;
-      return !sparse || balanced_range_meets(w0 + s, T, a.n_wg, c0, c0 + n_pages);
+      return !sparse || balanced_range_meets(a.geom, w0 + s, T, c0, c0 + n_pages);
     };
 
     // ---- merged latent output of this lane: KS pieces of 8 columns -------------

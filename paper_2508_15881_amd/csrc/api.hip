@@ -84,6 +84,7 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_page
   SplitPlan p;
   p.balanced = 0;
   p.n_wg = 0;
+  for (int r = 0; r < 4; ++r) p.round_wt[r] = 1;
   int32_t n = n_splits_req;
   if (n <= 0 && sh.dtype == TPLA_BF16 && decode_mfma_supported(sh)) {
     // Automatic plan of the matrix-core kernel: exactly as many workgroups as
@@ -99,6 +100,9 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_page
     const int cus = device_cu_count();
     if (most / 8 < n_wg) n_wg = most / 8 > cus ? (int)(most / 8) : (cus < n_wg ? cus : n_wg);
     if (n_wg > most) n_wg = (int)most;
+    // A full launch of long ranges: the workgroup placed first on a compute unit runs ahead of the
+    // ones placed after it, so the ranges are sized by placement round for all to end together.
+    if (n_wg == cus * per_cu && most / n_wg >= 32) decode_mfma_round_weights(sh, per_cu, p.round_wt);
     p.balanced = 1;
     p.n_wg = n_wg;
     p.n_splits = 1;
@@ -181,6 +185,9 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
   a.plan = reinterpret_cast<int32_t*>(a.part_ml + slots * shape->H * 2);
   a.balanced = plan.balanced;
   a.n_wg = plan.n_wg;
+  a.geom.W = plan.n_wg;
+  a.geom.n_cus = device_cu_count();
+  for (int r = 0; r < 4; ++r) a.geom.wt[r] = plan.round_wt[r];
   a.o_lat = o_lat;
   a.lse = lse;
   a.n_shards = n_shards;

@@ -132,20 +132,20 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
       if (cnt > a.n_splits) cnt = a.n_splits;
       for (int s = lane; s < cnt; s += 64) slot_of[s] = vb * a.n_splits + s;
     } else {
-      // workgroups whose page range [w T / W, (w+1) T / W) meets [c0, c0 + n_pages): those from the
+      // workgroups whose page range of the plan meets [c0, c0 + n_pages): those from the
       // owner of the first page to the owner of the last; when there are fewer pages than workgroups
       // some ranges in between are empty and are left out, 64 candidates at a time
       const int n_v = a.n_shards * a.B;
       const int T = a.plan[n_v], c0 = a.plan[vb];
-      const int w0 = balanced_owner(c0, T, a.n_wg), w1 = balanced_owner(c0 + n_pages - 1, T, a.n_wg);
-      if (T >= a.n_wg) {
+      const int w0 = balanced_owner(a.geom, c0, T), w1 = balanced_owner(a.geom, c0 + n_pages - 1, T);
+      if (!plan_sparse(a.geom, T)) {
         cnt = w1 - w0 + 1;
         for (int s = lane; s < cnt; s += 64) slot_of[s] = w0 + s + vb;
       } else {
         cnt = 0;
         for (int base = w0; base <= w1; base += 64) {
           const int w = base + lane;
-          const bool meets = w <= w1 && balanced_range_meets(w, T, a.n_wg, c0, c0 + n_pages);
+          const bool meets = w <= w1 && balanced_range_meets(a.geom, w, T, c0, c0 + n_pages);
           const unsigned long long mask = __ballot(meets);
           if (meets) slot_of[cnt + __popcll(mask & ((1ull << lane) - 1))] = w + vb;
           cnt += __popcll(mask);

@@ -29,7 +29,7 @@ constexpr int PAGE_TOKENS = 64;
 // One work item: pages [p0, p1) of sequence b of slice `shard` (L tokens in
 // the sequence, p1 <= its page count); the partial result goes to slot
 // `slot` of the workspace.  Called by every thread of the workgroup.
-template <int DL, int DR, int NW, int TOK, int NSTAGE>
+template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR>
 __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, int shard, int b, int L,
                                             int p0, int p1, size_t slot) {
   constexpr int RC = (DL + DR) / 8;      // 16-byte pieces per row
@@ -44,7 +44,9 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
   constexpr int TILE_BYTES = TC * 16;
   static_assert(RC % 8 == 0, "row must be a multiple of 64 elements");
   static_assert(TOK % 32 == 0 && PAGE_TOKENS % TOK == 0 && TC % 64 == 0, "tile size");
-  static_assert(NSTAGE == 3, "the wait counts below assume two tiles in flight");
+  static_assert(NSTAGE >= 2 && NSTAGE <= 4, "the wait counts below cover one to three tiles in flight");
+  constexpr int FL = NSTAGE - 1;         // tiles in flight
+  static_assert(KR >= 4 && (KR & (KR - 1)) == 0 && KR <= 16, "fragment ring depth");
 
   const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)smem);
 
@@ -126,7 +128,8 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
   float m_run = -INFINITY, l_run = 0.f;
 
   issue(0);
-  if (ntiles > 1) issue(1);
+  if (FL >= 2 && ntiles > 1) issue(1);
+  if (FL >= 3 && ntiles > 2) issue(2);
 
   // ---- this wave's 16 heads of the query, as B operands --------------------
   const int head = wave * 16 + j16;
@@ -148,15 +151,20 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
 
 
   for (int t = 0; t < ntiles; ++t) {
-    // tile t has landed once at most the loads of tile t+1 are outstanding
-    if (t + 1 < ntiles)
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(CPT));
-    else
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    // tile t has landed once only the loads of the tiles requested after it are outstanding
+    {
+      const int later = ntiles - 1 - t;      // tiles after t that exist (FL - 1 of them are in flight at most)
+      if (FL >= 3 && later >= 2)
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * CPT));
+      else if (FL >= 2 && later >= 1)
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(CPT));
+      else
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
     // all waves: tile t visible, tile t-1 no longer read.  A bare barrier:
     // __syncthreads() would add a fence that waits for the loads in flight.
     __builtin_amdgcn_s_barrier();
-    if (t + 2 < ntiles) issue(t + 2);
+    if (t + FL < ntiles) issue(t + FL);
     const unsigned tile = lds_base + (unsigned)((t % NSTAGE) * TILE_BYTES);
     const int valid = t_end - (t_begin + t * TOK);
     if (valid < TOK) {
@@ -174,9 +182,9 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
     for (int tb = 0; tb < TB; ++tb) sacc[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
     {
       constexpr int NQ = KS * TB;          // MFMAs, in order (ks, tb)
-      bf16x8 kf[4];
+      bf16x8 kf[KR];
       const unsigned ka[2] = {tile + k_off[0], tile + k_off[1]};
-      static_for<4>([&](auto ic) {
+      static_for<KR>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
         constexpr int ks = i / TB, tb = i % TB;
         lds_read_b128<(ks >> 1) * 128 + tb * (16 * RC * 16)>(kf[i], ka[ks & 1]);
@@ -184,12 +192,12 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
       static_for<NQ>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
         constexpr int ks = i / TB, tb = i % TB;
-        constexpr int ahead = (NQ - 1 - i) < 3 ? (NQ - 1 - i) : 3;
-        lds_wait<ahead>(kf[i & 3]);
-        sacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i & 3], qreg[ks], sacc[tb], 0, 0, 0);
-        if constexpr (i + 4 < NQ) {
-          constexpr int ks2 = (i + 4) / TB, tb2 = (i + 4) % TB;
-          lds_read_b128<(ks2 >> 1) * 128 + tb2 * (16 * RC * 16)>(kf[i & 3], ka[ks2 & 1]);
+        constexpr int ahead = (NQ - 1 - i) < KR - 1 ? (NQ - 1 - i) : KR - 1;
+        lds_wait<ahead>(kf[i & (KR - 1)]);
+        sacc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[i & (KR - 1)], qreg[ks], sacc[tb], 0, 0, 0);
+        if constexpr (i + KR < NQ) {
+          constexpr int ks2 = (i + KR) / TB, tb2 = (i + KR) % TB;
+          lds_read_b128<(ks2 >> 1) * 128 + tb2 * (16 * RC * 16)>(kf[i & (KR - 1)], ka[ks2 & 1]);
         }
       });
     }
@@ -241,25 +249,26 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
         pb[i] = (bf16_t)sacc[2 * s2][i];
         pb[4 + i] = (bf16_t)sacc[2 * s2 + 1][i];
       }
-      u32x2 vlo[4], vhi[4];
+      constexpr int VR = KR <= 8 ? KR : 8;     // two reads per fragment: the wait counter allows 15 outstanding
+      u32x2 vlo[VR], vhi[VR];
       unsigned va[4];
 #pragma unroll
       for (int d = 0; d < 4; ++d) va[d] = tile + v_off[d] + (unsigned)(s2 * (32 * RC * 16));
-      static_for<4>([&](auto ic) {
+      static_for<VR>([&](auto ic) {
         constexpr int d = decltype(ic)::value;
         lds_read_tr_b64<(d >> 2) * 128>(vlo[d], va[d & 3]);
         lds_read_tr_b64<(d >> 2) * 128 + 16 * RC * 16>(vhi[d], va[d & 3]);
       });
       static_for<DB>([&](auto ic) {
         constexpr int d = decltype(ic)::value;
-        constexpr int ahead = (DB - 1 - d) < 3 ? (DB - 1 - d) : 3;
-        lds_wait<2 * ahead>(vlo[d & 3], vhi[d & 3]);
-        const u32x4 v4 = {vlo[d & 3][0], vlo[d & 3][1], vhi[d & 3][0], vhi[d & 3][1]};
+        constexpr int ahead = (DB - 1 - d) < VR - 1 ? (DB - 1 - d) : VR - 1;
+        lds_wait<2 * ahead>(vlo[d & (VR - 1)], vhi[d & (VR - 1)]);
+        const u32x4 v4 = {vlo[d & (VR - 1)][0], vlo[d & (VR - 1)][1], vhi[d & (VR - 1)][0], vhi[d & (VR - 1)][1]};
         acc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v4), pb, acc[d], 0, 0, 0);
-        if constexpr (d + 4 < DB) {
-          constexpr int d2 = d + 4;
-          lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d & 3], va[d2 & 3]);
-          lds_read_tr_b64<(d2 >> 2) * 128 + 16 * RC * 16>(vhi[d & 3], va[d2 & 3]);
+        if constexpr (d + VR < DB) {
+          constexpr int d2 = d + VR;
+          lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d & (VR - 1)], va[d2 & 3]);
+          lds_read_tr_b64<(d2 >> 2) * 128 + 16 * RC * 16>(vhi[d & (VR - 1)], va[d2 & 3]);
         }
       });
     }
@@ -283,8 +292,16 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
 // fits one workgroup per compute unit in LDS, so it keeps the full budget.
 template <int DL, int NW>
 constexpr int waves_per_simd() { return DL >= 512 ? (NW >= 8 ? 2 : 1) : (NW >= 4 ? 2 : 1); }
+// Tiles in the LDS ring (one fewer in flight) and fragment ring depth (LDS reads ahead of the MFMA that
+// consumes them).  Measured: a ring of 4 tiles is no faster than 3 for any width (128-wide slices: 1144
+// against 1122 us on the ragged batch), and fragment rings of 8 or 16 change nothing even where a wave
+// has its SIMD to itself (576-wide rows: 248 / 251 / 261 us for 4 / 8 / 16).
+template <int DL>
+constexpr int ring_stages() { return 3; }
+template <int DL, int NW>
+constexpr int frag_ring() { return 4; }
 
-template <int DL, int DR, int NW, int TOK, int NSTAGE>
+template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR>
 __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mfma_kernel(DecodeArgs a) {
   extern __shared__ u32x4 smem[];        // NSTAGE tiles
   const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
@@ -294,21 +311,22 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
   const int p0 = s * a.pages_per_split;
   if (p0 >= n_pages) return;
   const int p1 = min(p0 + a.pages_per_split, n_pages);
-  decode_item<DL, DR, NW, TOK, NSTAGE>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
+  decode_item<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
 }
 
 // Balanced ranges: the pages of all (slice, sequence) pairs are laid end to
-// end (T pages) and workgroup w of W takes [w T / W, (w+1) T / W), whatever
+// end (T pages) and workgroup w of W takes range w of the plan (equal shares,
+// or shares weighted by placement round: see BalancedPlan), whatever
 // sequences that covers; every (workgroup, sequence) overlap is one work item
 // whose partial result goes to slot w + v (v = slice * B + sequence; strictly
 // increasing along the items, hence unique).  Workgroup 0 also publishes the
 // page offsets of the sequences for the merge.
-template <int DL, int DR, int NW, int TOK, int NSTAGE>
+template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR>
 __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mfma_balanced_kernel(DecodeArgs a) {
   extern __shared__ u32x4 smem[];
   const int lane = threadIdx.x & 63;
   const int n_v = a.n_shards * a.B;
-  const int w = blockIdx.x, W = gridDim.x;
+  const int w = blockIdx.x;
   // every wave scans the lengths by itself (no LDS, no barrier)
   int total = 0;
   for (int v0 = 0; v0 < n_v; v0 += 64) {
@@ -318,7 +336,7 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
     for (int m = 32; m > 0; m >>= 1) pg += __shfl_xor(pg, m);
     total += pg;
   }
-  const int start = (int)((long long)w * total / W), end = (int)((long long)(w + 1) * total / W);
+  const int start = plan_start(a.geom, total, w), end = plan_start(a.geom, total, w + 1);
   int base = 0;
   for (int v0 = 0; v0 < n_v; v0 += 64) {
     const int v = v0 + lane;
@@ -339,7 +357,7 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
       hit &= hit - 1;
       const int Ls = __shfl(L, src), p0 = __shfl(p0l, src), p1 = __shfl(p1l, src);
       const int vs = v0 + src;
-      decode_item<DL, DR, NW, TOK, NSTAGE>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
+      decode_item<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
     }
     base += __shfl(incl, 63);
   }
@@ -366,10 +384,10 @@ struct KernelInfo {
 
 template <int DL, int NW>
 static KernelInfo make_kernel_info() {
-  constexpr int TOK = 32, NSTAGE = 3;
+  constexpr int TOK = 32, NSTAGE = ring_stages<DL>(), KR = frag_ring<DL, NW>();
   KernelInfo info;
-  info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE>;
-  info.fn_balanced = decode_mfma_balanced_kernel<DL, 64, NW, TOK, NSTAGE>;
+  info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE, KR>;
+  info.fn_balanced = decode_mfma_balanced_kernel<DL, 64, NW, TOK, NSTAGE, KR>;
   info.smem = (size_t)NSTAGE * TOK * ((DL + 64) / 8) * 16;
   info.threads = NW * 64;
   // dynamic LDS above the 64 KiB default needs opting in
@@ -425,6 +443,26 @@ int decode_mfma_blocks_per_cu(const tpla_shape_t& sh) {
   KernelInfo* k = nullptr;
   if (kernel_info_for(sh.d_c / sh.g, sh.H, &k) != TPLA_OK) return 0;
   return k->blocks_per_cu;
+}
+
+// Measured with per-workgroup timestamps on full launches of equal ranges: when two or three workgroups
+// share a compute unit and their waves share its SIMDs, the workgroup placed first takes 5 - 9 % less
+// time than the average and the one placed last 5 % (two per compute unit) or 10 % (three) more,
+// whatever the wave priorities (s_setprio changes nothing).  With two per compute unit the late
+// workgroups still keep the memory system full when they are alone at the end, and sizing the ranges by
+// round made the launch slower (227 against 222 us at 32 x 32768 tokens); with three (128-wide slices:
+// 12 KB tiles, 24 KB in flight per workgroup) the lone last round does not, and weighted ranges take
+// the ragged batch from 1122 to 1073 us.  With one wave per SIMD (32 heads and fewer) the rounds run
+// alike.  Weights in units of 1/128 of the average range.
+void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]) {
+  for (int r = 0; r < 4; ++r) wt[r] = 128;
+  const int waves_per_simd_launched = (sh.H / 16) * per_cu / 4;
+  if (waves_per_simd_launched < 2) return;
+  if (per_cu == 3) {
+    wt[0] = 140;
+    wt[1] = 129;
+    wt[2] = 115;
+  }
 }
 
 int launch_decode_mfma(const DecodeArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {

@@ -26,8 +26,73 @@ struct SplitPlan {
   int32_t n_wg;              // balanced: workgroups; partial slots = n_wg + n_shards * B
   int32_t n_splits;          // static
   int32_t pages_per_split;   // static
+  int32_t round_wt[4];       // balanced: weight of the ranges of each placement round
 };
 SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_pages_per_seq, int32_t n_splits_req);
+
+// Balanced plan.  The T pages of all (slice, sequence) pairs are laid end to end and cut into W
+// ranges, one per workgroup; range w is [plan_start(w), plan_start(w + 1)).  Ranges are weighted by
+// the placement round of their workgroup (round = w / n_cus; the hardware fills every compute unit
+// once before it places a second workgroup on any): a range of round r is wt[r] / wt[0] times as
+// long as one of round 0.  All weights equal = ranges [w T / W, (w + 1) T / W).
+struct BalancedPlan {
+  int32_t W;        // ranges = workgroups
+  int32_t n_cus;    // workgroups per placement round
+  int32_t wt[4];    // weight of a range of round min(r, 3); positive
+};
+// Sum of the weights of ranges 0 .. w-1.
+__host__ __device__ __forceinline__ long long plan_cum(const BalancedPlan& p, int w) {
+  long long c = 0;
+  int r = 0, left = w;
+  while (r < 3 && left > p.n_cus) {
+    c += (long long)p.n_cus * p.wt[r];
+    left -= p.n_cus;
+    ++r;
+  }
+  return c + (long long)left * p.wt[r];
+}
+// First page of range w, 0 <= w <= W (T pages in all; T * total weight stays below 2^62).
+__host__ __device__ __forceinline__ int plan_start(const BalancedPlan& p, long long T, int w) {
+  return (int)(T * plan_cum(p, w) / plan_cum(p, p.W));
+}
+// The range that holds page c, 0 <= c < T.
+__host__ __device__ __forceinline__ int balanced_owner(const BalancedPlan& p, int c, int T) {
+  // first guess from the inverse of the piecewise linear cumulative weight, then step to the exact range
+  const long long total = plan_cum(p, p.W);
+  long long x = ((long long)c * total) / T;
+  int r = 0, base = 0;
+  while (r < 3 && base + p.n_cus < p.W && x >= (long long)p.n_cus * p.wt[r]) {
+    x -= (long long)p.n_cus * p.wt[r];
+    base += p.n_cus;
+    ++r;
+  }
+  int w = base + (int)(x / p.wt[r]);
+  if (w > p.W - 1) w = p.W - 1;
+  while (w + 1 < p.W && plan_start(p, T, w + 1) <= c) ++w;
+  while (w > 0 && plan_start(p, T, w) > c) --w;
+  return w;
+}
+// Whether some range of the plan may be empty (fewer pages than ranges; with weights, fewer than
+// about 1.1 per range): the merge then has to test every range between a sequence's first and last.
+__host__ __device__ __forceinline__ bool plan_sparse(const BalancedPlan& p, long long T) {
+  int m = p.wt[0];
+  for (int r = 1; r < 4; ++r) m = p.wt[r] < m ? p.wt[r] : m;
+  return T * m < plan_cum(p, p.W);
+}
+// Whether range w meets the pages [c0, c1) (only in doubt when plan_sparse()).
+__host__ __device__ __forceinline__ bool balanced_range_meets(const BalancedPlan& p, int w, int T, int c0, int c1) {
+  const int lo = plan_start(p, T, w), hi = plan_start(p, T, w + 1);
+  return (lo > c0 ? lo : c0) < (hi < c1 ? hi : c1);
+}
+// The work item of a workgroup that owns the pages [start, end) in a sequence whose n pages begin at
+// page e of the laid-out order: its pages [*p0, *p1) counted inside the sequence.  False when the two
+// ranges share no page (also for an empty workgroup range that lies inside the sequence).
+__host__ __device__ __forceinline__ bool balanced_item(int start, int end, int e, int n, int* p0, int* p1) {
+  const int lo = start > e ? start : e, hi = end < e + n ? end : e + n;
+  *p0 = lo - e;
+  *p1 = hi - e;
+  return lo < hi;
+}
 
 // Partial results of one (slice, sequence, split): acc [n_shards, B, S, H, dl]
 // floats, then ml [n_shards, B, S, H, 2] floats (running max in log2 units, sum of weights).
@@ -47,6 +112,7 @@ struct DecodeArgs {
   int32_t B, H, dl, d_r, page_tokens, max_pages;
   int32_t n_splits, pages_per_split;
   int32_t balanced, n_wg;
+  BalancedPlan geom;     // balanced: ranges and their weights (geom.W == n_wg)
   int32_t* plan;         // balanced: [n_shards * B + 1] first page of every sequence, then the total
   float scale_log2;      // sm_scale * log2(e)
 };
@@ -56,6 +122,9 @@ bool decode_mfma_supported(const tpla_shape_t& sh);
 // Workgroups of the matrix-core kernel for this shape that fit on one compute
 // unit (0 = unknown).
 int decode_mfma_blocks_per_cu(const tpla_shape_t& sh);
+// Range weights by placement round for a launch that puts per_cu workgroups of the matrix-core
+// kernel on every compute unit (all equal where the rounds run equally fast).
+void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]);
 // ev_start / ev_stop (both or neither): events that receive the kernel's begin and end times.
 int launch_decode_mfma(const DecodeArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr,
                        hipEvent_t ev_stop = nullptr);
@@ -66,37 +135,6 @@ __device__ __forceinline__ int seq_len_clipped(const DecodeArgs& a, int b) {
   const long long cap = (long long)a.max_pages * a.page_tokens;
   const long long L = a.seq_lens[b];
   return (int)(L < 0 ? 0 : (L > cap ? cap : L));
-}
-
-// Balanced plan: workgroup w of W owns the pages [w T / W, (w+1) T / W) of the T pages of all
-// (slice, sequence) pairs laid end to end.  The workgroup whose range holds page c, 0 <= c < T
-// (32-bit arithmetic when the products fit).
-__host__ __device__ __forceinline__ int balanced_owner(int c, int T, int W) {
-  if ((long long)T * W <= 2147483647LL) {
-    unsigned w = (unsigned)c * (unsigned)W / (unsigned)T;
-    while (w + 1 < (unsigned)W && (w + 1) * (unsigned)T / (unsigned)W <= (unsigned)c) ++w;
-    while (w > 0 && w * (unsigned)T / (unsigned)W > (unsigned)c) --w;
-    return (int)w;
-  }
-  long long w = (long long)c * W / T;
-  while (w + 1 < W && (w + 1) * T / W <= c) ++w;
-  while (w > 0 && w * T / W > c) --w;
-  return (int)w;
-}
-// Whether workgroup w's range meets the pages [c0, c1) (only in doubt when T < W: some ranges are empty).
-__host__ __device__ __forceinline__ bool balanced_range_meets(long long w, long long T, long long W, long long c0,
-                                                              long long c1) {
-  const long long lo = w * T / W, hi = (w + 1) * T / W;
-  return (lo > c0 ? lo : c0) < (hi < c1 ? hi : c1);
-}
-// The work item of a workgroup that owns the pages [start, end) in a sequence whose n pages begin at
-// page e of the laid-out order: its pages [*p0, *p1) counted inside the sequence.  False when the two
-// ranges share no page (also for an empty workgroup range that lies inside the sequence).
-__host__ __device__ __forceinline__ bool balanced_item(int start, int end, int e, int n, int* p0, int* p1) {
-  const int lo = start > e ? start : e, hi = end < e + n ? end : e + n;
-  *p0 = lo - e;
-  *p1 = hi - e;
-  return lo < hi;
 }
 
 int launch_decode_generic(const DecodeArgs& a, int dtype, hipStream_t st);

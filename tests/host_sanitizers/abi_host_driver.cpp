@@ -208,57 +208,81 @@ static void pca_checks() {
   EXPECT(tpla_pca_basis(4, 2, 10, NULL, z.data(), zf.data(), z.data(), z.data()) == TPLA_ERR_NULL);
 }
 
-// Balanced plan: workgroup w of W owns pages [w T / W, (w+1) T / W) of the T pages of all sequences laid
-// end to end.  The split kernel derives its work items with balanced_item, the merge kernels find the
-// slots of a sequence with balanced_owner / balanced_range_meets: for every (T, W, lengths) both sides must
-// name the same (workgroup, sequence) pairs, every page exactly once.
+// Balanced plan: range w of W is [plan_start(w), plan_start(w + 1)) of the T pages of all sequences laid
+// end to end, with equal or round-weighted shares.  The split kernel derives its work items with
+// balanced_item, the merge kernels find the slots of a sequence with balanced_owner /
+// balanced_range_meets: for every (T, W, weights, lengths) both sides must name the same (workgroup,
+// sequence) pairs, every page exactly once.
 static void plan_checks() {
   uint64_t st = 99;
-  const int Ws[] = {1, 2, 3, 7, 16, 40, 256, 512};
-  for (int W : Ws)
-    for (int trial = 0; trial < 60; ++trial) {
-      const int n_seq = 1 + (int)((lcg(st) + 1.0) * 6.0);
-      std::vector<int> pages((size_t)n_seq), excl((size_t)n_seq);
-      int T = 0;
-      for (int v = 0; v < n_seq; ++v) {
-        // short batches (T < W: empty workgroup ranges), empty sequences, and long ones
-        const double u = lcg(st);
-        pages[v] = u < -0.6 ? 0 : (trial % 3 == 0 ? (int)((u + 1.0) * 3.0) : (int)((u + 1.0) * 0.8 * W));
-        excl[v] = T;
-        T += pages[v];
-      }
-      if (T == 0) continue;
-      for (int c = 0; c < T; ++c) {
-        const int w = tpla::balanced_owner(c, T, W);
-        EXPECT(w >= 0 && w < W && (long long)w * T / W <= c && c < (long long)(w + 1) * T / W);
-      }
-      std::vector<int> covered((size_t)T, 0);
-      for (int v = 0; v < n_seq; ++v) {
-        int n_items = 0, w_first = -1, w_last = -1;
-        for (int w = 0; w < W; ++w) {
-          const int start = (int)((long long)w * T / W), end = (int)((long long)(w + 1) * T / W);
-          int p0 = -1, p1 = -1;
-          const bool item = pages[v] > 0 && tpla::balanced_item(start, end, excl[v], pages[v], &p0, &p1);
-          EXPECT(item == (pages[v] > 0 && tpla::balanced_range_meets(w, T, W, excl[v], excl[v] + pages[v])));
-          if (!item) continue;
-          EXPECT(0 <= p0 && p0 < p1 && p1 <= pages[v]);
-          for (int p = p0; p < p1; ++p) ++covered[(size_t)(excl[v] + p)];
-          if (w_first < 0) w_first = w;
-          w_last = w;
-          ++n_items;
+  const int Ws[] = {1, 2, 3, 7, 16, 40, 256, 512, 768};
+  const int wts[][4] = {{1, 1, 1, 1}, {135, 121, 128, 128}, {140, 129, 115, 128}, {128, 128, 128, 128}, {3, 1, 1, 7}};
+  const int cus[] = {256, 8, 5};
+  for (const auto& wt : wts)
+    for (int n_cus : cus)
+      for (int W : Ws)
+        for (int trial = 0; trial < 12; ++trial) {
+          tpla::BalancedPlan p;
+          p.W = W;
+          p.n_cus = n_cus;
+          for (int r = 0; r < 4; ++r) p.wt[r] = wt[r];
+          const int n_seq = 1 + (int)((lcg(st) + 1.0) * 6.0);
+          std::vector<int> pages((size_t)n_seq), excl((size_t)n_seq);
+          int T = 0;
+          for (int v = 0; v < n_seq; ++v) {
+            // short batches (T < W: empty ranges), empty sequences, and long ones
+            const double u = lcg(st);
+            pages[v] = u < -0.6 ? 0 : (trial % 3 == 0 ? (int)((u + 1.0) * 3.0) : (int)((u + 1.0) * 0.8 * W));
+            excl[v] = T;
+            T += pages[v];
+          }
+          if (T == 0) continue;
+          EXPECT(tpla::plan_start(p, T, 0) == 0 && tpla::plan_start(p, T, W) == T);
+          for (int w = 0; w < W; ++w) EXPECT(tpla::plan_start(p, T, w) <= tpla::plan_start(p, T, w + 1));
+          if (wt[0] == wt[1] && wt[1] == wt[2] && wt[2] == wt[3])      // equal weights: the plain equal shares
+            for (int w = 0; w <= W; ++w) EXPECT(tpla::plan_start(p, T, w) == (int)((long long)w * T / W));
+          for (int c = 0; c < T; ++c) {
+            const int w = tpla::balanced_owner(p, c, T);
+            EXPECT(w >= 0 && w < W && tpla::plan_start(p, T, w) <= c && c < tpla::plan_start(p, T, w + 1));
+          }
+          std::vector<int> covered((size_t)T, 0);
+          for (int v = 0; v < n_seq; ++v) {
+            int n_items = 0, w_first = -1, w_last = -1;
+            for (int w = 0; w < W; ++w) {
+              const int start = tpla::plan_start(p, T, w), end = tpla::plan_start(p, T, w + 1);
+              int p0 = -1, p1 = -1;
+              const bool item = pages[v] > 0 && tpla::balanced_item(start, end, excl[v], pages[v], &p0, &p1);
+              EXPECT(item == (pages[v] > 0 && tpla::balanced_range_meets(p, w, T, excl[v], excl[v] + pages[v])));
+              if (!item) continue;
+              EXPECT(0 <= p0 && p0 < p1 && p1 <= pages[v]);
+              for (int q = p0; q < p1; ++q) ++covered[(size_t)(excl[v] + q)];
+              if (w_first < 0) w_first = w;
+              w_last = w;
+              ++n_items;
+            }
+            if (pages[v] > 0) {
+              // what the merge computes: first and last owner of the sequence's pages
+              EXPECT(w_first == tpla::balanced_owner(p, excl[v], T));
+              EXPECT(w_last == tpla::balanced_owner(p, excl[v] + pages[v] - 1, T));
+              EXPECT(n_items >= 1 && n_items <= w_last - w_first + 1);
+              if (!tpla::plan_sparse(p, T)) EXPECT(n_items == w_last - w_first + 1);   // no empty range in between
+            } else {
+              EXPECT(n_items == 0);
+            }
+          }
+          for (int c = 0; c < T; ++c) EXPECT(covered[(size_t)c] == 1);
         }
-        if (pages[v] > 0) {
-          // what the merge computes from two divisions: first and last owner of the sequence's pages
-          EXPECT(w_first == tpla::balanced_owner(excl[v], T, W));
-          EXPECT(w_last == tpla::balanced_owner(excl[v] + pages[v] - 1, T, W));
-          EXPECT(n_items >= 1 && n_items <= w_last - w_first + 1);
-          if (T >= W) EXPECT(n_items == w_last - w_first + 1);      // no empty ranges: the slots are contiguous
-        } else {
-          EXPECT(n_items == 0);
-        }
-      }
-      for (int c = 0; c < T; ++c) EXPECT(covered[(size_t)c] == 1);
-    }
+  // the weighted plans of the library's own launches leave no range empty (the merge relies on it:
+  // it only looks for empty ranges when there are fewer pages than ranges)
+  const int full[][6] = {{512, 256, 135, 121, 128, 128}, {768, 256, 140, 129, 115, 128}};
+  for (const auto& f : full) {
+    tpla::BalancedPlan p;
+    p.W = f[0];
+    p.n_cus = f[1];
+    for (int r = 0; r < 4; ++r) p.wt[r] = f[2 + r];
+    for (int T : {32 * f[0], 32 * f[0] + 17, 100000, 2000000})
+      for (int w = 0; w < p.W; ++w) EXPECT(tpla::plan_start(p, T, w) < tpla::plan_start(p, T, w + 1));
+  }
 }
 
 int main() {
