@@ -440,7 +440,7 @@ def main():
         step.decode_all(q_pe, pools, bt, lens)
         step.combine(W_UV_t)
     us_step_separate = timed(separate_step, reps=100, warm=30)
-    us_wo = float("nan")
+    us_wo = us_block = float("nan")
     if not args.skip_extras:
         # block output o W_O (after the timed step's last stage; weight-streaming GEMM)
         W_O = pl.to_device(wl.draw_output_weight(w), w.dtype)
@@ -448,6 +448,14 @@ def main():
         wo_ws = torch.empty(max(wo_ws_b, 16), dtype=torch.uint8, device=dev)
         wo_out = torch.empty((w.B, w.d_model), dtype=torch.float32, device=dev)
         us_wo = timed(lambda: tp.tpla_output_projection(shape, step.o, W_O, w.d_model, wo_ws, wo_ws_b, wo_out))
+        # the whole attention block after the query projections: absorb + one tpla_decode_shards_project call
+        step_p = pl.DecodeStep(shape, model["max_pages"], args.n_splits, d_model=w.d_model)
+
+        def block_step():
+            step_p.absorb(q_nope, W_UK_t, mu)
+            step_p.decode_all_project(q_pe, pools, bt, lens, W_UV_t, W_O)
+        us_block = timed(block_step, reps=100, warm=30)
+        del step_p
 
     # the same step replayed from a HIP graph (launch overhead of its kernels removed);
     # informational: the timed region above launches eagerly so that its kernels can be bracketed
@@ -583,6 +591,7 @@ def main():
                       "decode_shards_combine(all slices, split + merge-and-combine kernel)": us_decode_combine,
                       "layer_step_with_separate_merge_and_combine": us_step_separate,
                       "output_projection(W_O, not in the step)": us_wo,
+                      "layer_step_with_output_projection(absorb + tpla_decode_shards_project, bf16 block output)": us_block,
                       "one_device_share": us_absorb / w.g + us_decode + us_combine,
                       "layer_step_replayed_from_hip_graph": us_graph},
         "pool_copies_rotated": n_sets_rotated, "cache_resident": cache_resident,

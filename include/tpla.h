@@ -211,6 +211,10 @@ int tpla_decode_shards(const tpla_shape_t* shape,
  */
 int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t,
                         float* o, void* stream);
+/* The same with the output type chosen by the caller: o is float (o_dtype = TPLA_F32) or bfloat16
+ * (TPLA_BF16, one rounding to nearest even of the float result) [B, H, d_v]. */
+int tpla_combine_shards_to(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t,
+                           void* o, int32_t o_dtype, void* stream);
 
 /*
  * tpla_decode_shards followed by tpla_combine_shards as one call (the
@@ -231,6 +235,15 @@ int tpla_decode_shards_combine(const tpla_shape_t* shape,
                                void* workspace, size_t workspace_bytes,
                                const void* W_UV_t, float* o,
                                float* o_lat, float* lse, void* stream);
+
+/* tpla_decode_shards_combine with o written as float (o_dtype = TPLA_F32) or bfloat16 (TPLA_BF16). */
+int tpla_decode_shards_combine_to(const tpla_shape_t* shape,
+                                  const void* q_lat, const void* q_pe, const void* const* shard_pools,
+                                  const int32_t* block_table, int32_t max_pages_per_seq,
+                                  const int32_t* seq_lens, int32_t n_splits,
+                                  void* workspace, size_t workspace_bytes,
+                                  const void* W_UV_t, void* o, int32_t o_dtype,
+                                  float* o_lat, float* lse, void* stream);
 
 /*
  * For callers that cannot allocate device memory or hand over a workspace
@@ -267,6 +280,31 @@ int tpla_decode_shards_combine_static(const tpla_shape_t* shape,
 size_t tpla_output_projection_workspace_bytes(const tpla_shape_t* shape, int32_t D);
 int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void* W_O, int32_t D,
                            void* workspace, size_t workspace_bytes, float* out, void* stream);
+/* The same with out [B, D] written as float (out_dtype = TPLA_F32) or bfloat16 (TPLA_BF16). */
+int tpla_output_projection_to(const tpla_shape_t* shape, const float* o, const void* W_O, int32_t D,
+                              void* workspace, size_t workspace_bytes, void* out, int32_t out_dtype, void* stream);
+
+/*
+ * The attention block's output from the cache in one call (Sec. 4: O~_i = O_i W^{VO}_i summed over
+ * the devices, with W^{VO} kept as its two factors W_UV and W_O, Sec. 3.3): tpla_decode_shards_combine
+ * followed by tpla_output_projection_to,
+ *     out[b, :] = ( sum_i o_lat[i, b, :, :] @ W_UV_t[:, slice i, :] ) flattened to H d_v  @  W_O.
+ * Arguments as in those calls.  o float [B, H, d_v], o_lat float [g, B, H, d_c/g] are required and
+ * written (the intermediate results); lse float [g, B, H] or NULL; out [B, D] in out_dtype.  One
+ * workspace of tpla_attention_block_workspace_bytes() bytes serves the decode's partial results and then
+ * the projection's partial tiles.  Every argument check of both stages runs before the first launch.
+ * Bit-reproducible for fixed arguments; the same bits as the two calls made one after the other.
+ */
+size_t tpla_attention_block_workspace_bytes(const tpla_shape_t* shape, int32_t max_pages_per_seq,
+                                            int32_t n_splits, int32_t D);
+int tpla_decode_shards_project(const tpla_shape_t* shape,
+                               const void* q_lat, const void* q_pe, const void* const* shard_pools,
+                               const int32_t* block_table, int32_t max_pages_per_seq,
+                               const int32_t* seq_lens, int32_t n_splits,
+                               void* workspace, size_t workspace_bytes,
+                               const void* W_UV_t, const void* W_O, int32_t D,
+                               void* out, int32_t out_dtype,
+                               float* o, float* o_lat, float* lse, void* stream);
 
 /*
  * Prefill attention with MLA in its un-absorbed form (Sec. 4.5: the prefill

@@ -13,4 +13,6 @@ from .binding import (  # noqa: F401
     tpla_workspace_bytes, tpla_write_mla_cache, tpla_profile_enable, tpla_profile_collect, tpla_decode_shards, tpla_workspace_bytes_all, tpla_append_token_sliced, tpla_output_projection, tpla_output_projection_workspace_bytes,
     tpla_latent_moments, tpla_latent_moments_workspace_bytes, tpla_pca_basis, tpla_prefill_attention, tpla_prefill_workspace_bytes, tpla_stream_read,
     tpla_decode_shards_combine, tpla_validate_block_table, tpla_decode_shards_combine_static,
+    tpla_combine_shards_to, tpla_decode_shards_combine_to, tpla_output_projection_to,
+    tpla_attention_block_workspace_bytes, tpla_decode_shards_project,
 )

@@ -23,6 +23,8 @@ EXPORTS = (
     "tpla_output_projection_workspace_bytes", "tpla_latent_moments_workspace_bytes", "tpla_latent_moments",
     "tpla_pca_basis", "tpla_prefill_workspace_bytes", "tpla_prefill_attention", "tpla_stream_read",
     "tpla_decode_shards_combine", "tpla_validate_block_table", "tpla_decode_shards_combine_static",
+    "tpla_combine_shards_to", "tpla_decode_shards_combine_to", "tpla_output_projection_to",
+    "tpla_attention_block_workspace_bytes", "tpla_decode_shards_project",
 )
 
 
@@ -95,6 +97,18 @@ def load_library():
     lib.tpla_decode_shards_combine_static.restype = ctypes.c_int
     lib.tpla_decode_shards_combine_static.argtypes = [shp, vp, vp, ctypes.POINTER(vp), vp, i32, vp, i32,
                                                       vp, vp, vp, vp, vp]
+    lib.tpla_combine_shards_to.restype = ctypes.c_int
+    lib.tpla_combine_shards_to.argtypes = [shp, vp, vp, vp, i32, vp]
+    lib.tpla_decode_shards_combine_to.restype = ctypes.c_int
+    lib.tpla_decode_shards_combine_to.argtypes = [shp, vp, vp, ctypes.POINTER(vp), vp, i32, vp, i32, vp, ctypes.c_size_t,
+                                                  vp, vp, i32, vp, vp, vp]
+    lib.tpla_output_projection_to.restype = ctypes.c_int
+    lib.tpla_output_projection_to.argtypes = [shp, vp, vp, i32, vp, ctypes.c_size_t, vp, i32, vp]
+    lib.tpla_attention_block_workspace_bytes.restype = ctypes.c_size_t
+    lib.tpla_attention_block_workspace_bytes.argtypes = [shp, i32, i32, i32]
+    lib.tpla_decode_shards_project.restype = ctypes.c_int
+    lib.tpla_decode_shards_project.argtypes = [shp, vp, vp, ctypes.POINTER(vp), vp, i32, vp, i32, vp, ctypes.c_size_t,
+                                               vp, vp, i32, vp, i32, vp, vp, vp, vp]
     lib.tpla_combine_shards.restype = ctypes.c_int
     lib.tpla_combine_shards.argtypes = [shp, vp, vp, vp, vp]
     lib.tpla_profile_enable.restype = ctypes.c_int
@@ -254,6 +268,46 @@ def tpla_decode_shards_combine_static(shape, q_lat, q_pe, shard_pools, block_tab
     _check(load_library().tpla_decode_shards_combine_static(
         ctypes.byref(shape), _ptr(q_lat), _ptr(q_pe), arr, _ptr(block_table), max_pages_per_seq,
         _ptr(seq_lens), n_splits, _ptr(W_UV_t), _ptr(o), _ptr(o_lat), _ptr(lse), _stream(stream)))
+
+
+def _pool_array(shard_pools):
+    if shard_pools is None:
+        return None
+    arr = (ctypes.c_void_p * max(TPLA_MAX_G, len(shard_pools)))()
+    for i, p in enumerate(shard_pools):
+        arr[i] = _ptr(p)
+    return arr
+
+
+def tpla_combine_shards_to(shape, o_lat, W_UV_t, o, o_dtype, stream=None):
+    _check(load_library().tpla_combine_shards_to(
+        ctypes.byref(shape), _ptr(o_lat), _ptr(W_UV_t), _ptr(o), o_dtype, _stream(stream)))
+
+
+def tpla_decode_shards_combine_to(shape, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
+                                  n_splits, workspace, workspace_bytes, W_UV_t, o, o_dtype, o_lat, lse, stream=None):
+    _check(load_library().tpla_decode_shards_combine_to(
+        ctypes.byref(shape), _ptr(q_lat), _ptr(q_pe), _pool_array(shard_pools), _ptr(block_table), max_pages_per_seq,
+        _ptr(seq_lens), n_splits, _ptr(workspace), workspace_bytes, _ptr(W_UV_t), _ptr(o), o_dtype, _ptr(o_lat),
+        _ptr(lse), _stream(stream)))
+
+
+def tpla_output_projection_to(shape, o, W_O, D, workspace, workspace_bytes, out, out_dtype, stream=None):
+    _check(load_library().tpla_output_projection_to(
+        ctypes.byref(shape), _ptr(o), _ptr(W_O), D, _ptr(workspace), workspace_bytes, _ptr(out), out_dtype,
+        _stream(stream)))
+
+
+def tpla_attention_block_workspace_bytes(shape, max_pages_per_seq, n_splits, D):
+    return int(load_library().tpla_attention_block_workspace_bytes(ctypes.byref(shape), max_pages_per_seq, n_splits, D))
+
+
+def tpla_decode_shards_project(shape, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens, n_splits,
+                               workspace, workspace_bytes, W_UV_t, W_O, D, out, out_dtype, o, o_lat, lse, stream=None):
+    _check(load_library().tpla_decode_shards_project(
+        ctypes.byref(shape), _ptr(q_lat), _ptr(q_pe), _pool_array(shard_pools), _ptr(block_table), max_pages_per_seq,
+        _ptr(seq_lens), n_splits, _ptr(workspace), workspace_bytes, _ptr(W_UV_t), _ptr(W_O), D, _ptr(out), out_dtype,
+        _ptr(o), _ptr(o_lat), _ptr(lse), _stream(stream)))
 
 
 def tpla_combine_shards(shape, o_lat, W_UV_t, o, stream=None):

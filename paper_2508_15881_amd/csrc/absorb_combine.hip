@@ -161,10 +161,10 @@ int launch_absorb_query(const tpla_shape_t& sh, const void* q_nope, const void* 
 // grid (H, ceil(d_v / 128), ceil(B / BT)); thread = one value column.
 // The latent axis is walked in chunks of CK staged through LDS.
 constexpr int CK = 128;
-template <typename T>
+template <typename T, typename OT>
 __global__ void __launch_bounds__(128) combine_shards_kernel(const float* __restrict__ o_lat,
                                                              const T* __restrict__ W,
-                                                             float* __restrict__ o, int B, int H, int d_c,
+                                                             OT* __restrict__ o, int B, int H, int d_c,
                                                              int d_v, int g) {
   __shared__ float os[BT][CK];
   const int h = blockIdx.x;
@@ -201,17 +201,17 @@ __global__ void __launch_bounds__(128) combine_shards_kernel(const float* __rest
   if (col < d_v)
 #pragma unroll
     for (int bb = 0; bb < BT; ++bb)
-      if (bb < nb) o[((size_t)(b0 + bb) * H + h) * d_v + col] = acc[bb];
+      if (bb < nb) store_from_f32(o + ((size_t)(b0 + bb) * H + h) * d_v + col, acc[bb]);
 }
 
 
 // Vectorised variant (d_v a multiple of 8): workgroup = (head, 128-column
 // slab, 8 sequences).  Thread (cg, kg): 8 consecutive value columns, latent
 // rows kg, kg+16, ... (16 lanes read one 256-byte piece of a weight row).
-template <typename T>
+template <typename T, typename OT>
 __global__ void __launch_bounds__(256) combine_shards_vec_kernel(const float* __restrict__ o_lat,
                                                                  const T* __restrict__ W,
-                                                                 float* __restrict__ o, int B, int H,
+                                                                 OT* __restrict__ o, int B, int H,
                                                                  int d_c, int d_v, int g) {
   extern __shared__ float sm[];          // [AB][d_c] latent outputs, then [4][AB][128] partial sums
   float* os = sm;
@@ -273,24 +273,25 @@ __global__ void __launch_bounds__(256) combine_shards_vec_kernel(const float* __
     for (int c = 0; c < 4; ++c) {
       const int cc = c4 + c;
       if (col0 + cc < d_v)
-        o[((size_t)(b0 + bb) * H + h) * d_v + col0 + cc] =
-            red[(0 * AB + bb) * 128 + cc] + red[(1 * AB + bb) * 128 + cc] +
-            red[(2 * AB + bb) * 128 + cc] + red[(3 * AB + bb) * 128 + cc];
+        store_from_f32(o + ((size_t)(b0 + bb) * H + h) * d_v + col0 + cc,
+                       red[(0 * AB + bb) * 128 + cc] + red[(1 * AB + bb) * 128 + cc] +
+                           red[(2 * AB + bb) * 128 + cc] + red[(3 * AB + bb) * 128 + cc]);
     }
   }
 }
 
-int launch_combine_shards(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
-                          hipStream_t st) {
+template <typename OT>
+static int launch_combine_shards_to(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, OT* o,
+                                    hipStream_t st) {
   if (sh.d_v % 8 == 0) {
     const size_t vsm = ((size_t)AB * sh.d_c + 4u * AB * 128) * sizeof(float);
     const dim3 vgrid((unsigned)sh.H, (unsigned)((sh.d_v + 127) / 128), (unsigned)((sh.B + AB - 1) / AB));
     if (vsm <= 64 * 1024 && vgrid.y <= 65535 && vgrid.z <= 65535) {
       if (sh.dtype == TPLA_F32)
-        hipLaunchKernelGGL(combine_shards_vec_kernel<float>, vgrid, dim3(256), vsm, st, o_lat,
+        hipLaunchKernelGGL((combine_shards_vec_kernel<float, OT>), vgrid, dim3(256), vsm, st, o_lat,
                            static_cast<const float*>(W_UV_t), o, sh.B, sh.H, sh.d_c, sh.d_v, sh.g);
       else
-        hipLaunchKernelGGL(combine_shards_vec_kernel<bf16_t>, vgrid, dim3(256), vsm, st, o_lat,
+        hipLaunchKernelGGL((combine_shards_vec_kernel<bf16_t, OT>), vgrid, dim3(256), vsm, st, o_lat,
                            static_cast<const bf16_t*>(W_UV_t), o, sh.B, sh.H, sh.d_c, sh.d_v, sh.g);
       return check_launch("combine_shards_vec_kernel");
     }
@@ -298,12 +299,18 @@ int launch_combine_shards(const tpla_shape_t& sh, const float* o_lat, const void
   const dim3 grid((unsigned)sh.H, (unsigned)((sh.d_v + 127) / 128), (unsigned)((sh.B + BT - 1) / BT));
   if (grid.y > 65535 || grid.z > 65535) return fail(TPLA_ERR_UNSUPPORTED, "grid too large");
   if (sh.dtype == TPLA_F32)
-    hipLaunchKernelGGL(combine_shards_kernel<float>, grid, dim3(128), 0, st, o_lat,
+    hipLaunchKernelGGL((combine_shards_kernel<float, OT>), grid, dim3(128), 0, st, o_lat,
                        static_cast<const float*>(W_UV_t), o, sh.B, sh.H, sh.d_c, sh.d_v, sh.g);
   else
-    hipLaunchKernelGGL(combine_shards_kernel<bf16_t>, grid, dim3(128), 0, st, o_lat,
+    hipLaunchKernelGGL((combine_shards_kernel<bf16_t, OT>), grid, dim3(128), 0, st, o_lat,
                        static_cast<const bf16_t*>(W_UV_t), o, sh.B, sh.H, sh.d_c, sh.d_v, sh.g);
   return check_launch("combine_shards_kernel");
+}
+
+int launch_combine_shards(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, void* o, int o_dtype,
+                          hipStream_t st) {
+  if (o_dtype == TPLA_BF16) return launch_combine_shards_to(sh, o_lat, W_UV_t, static_cast<bf16_t*>(o), st);
+  return launch_combine_shards_to(sh, o_lat, W_UV_t, static_cast<float*>(o), st);
 }
 
 }  // namespace tpla

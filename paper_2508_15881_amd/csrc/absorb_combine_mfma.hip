@@ -127,9 +127,10 @@ int launch_absorb_query_mfma(const tpla_shape_t& sh, const void* q_nope, const v
 // 64 columns; the four waves' partial sums meet in LDS at the end.
 constexpr int CB_COLS = 64;
 constexpr int CK_ROWS = 512;
+template <typename OT>
 __global__ void __launch_bounds__(256) combine_shards_mfma_kernel(const float* __restrict__ o_lat,
                                                                   const bf16_t* __restrict__ W,
-                                                                  float* __restrict__ o, int B, int H,
+                                                                  OT* __restrict__ o, int B, int H,
                                                                   int d_c, int d_v, int g) {
   extern __shared__ u32x4 slab4[];
   char* slab = reinterpret_cast<char*>(slab4);
@@ -217,7 +218,7 @@ __global__ void __launch_bounds__(256) combine_shards_mfma_kernel(const float* _
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int bb = 16 * (mb0 + m) + 4 * q4 + i;
-        if (bb < B) o[((size_t)bb * H + h) * d_v + c0 + 16 * wave + j16] = t[i];
+        if (bb < B) store_from_f32(o + ((size_t)bb * H + h) * d_v + c0 + 16 * wave + j16, t[i]);
       }
     }
   }
@@ -228,11 +229,16 @@ bool combine_mfma_supported(const tpla_shape_t& sh) {
          sh.d_v / CB_COLS <= 65535;
 }
 
-int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
+int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, void* o, int o_dtype,
                                hipStream_t st) {
   const size_t smem = (size_t)CK_ROWS * CB_COLS * 2;
-  hipLaunchKernelGGL(combine_shards_mfma_kernel, dim3((unsigned)sh.H, (unsigned)(sh.d_v / CB_COLS)), dim3(256),
-                     smem, st, o_lat, static_cast<const bf16_t*>(W_UV_t), o, sh.B, sh.H, sh.d_c, sh.d_v, sh.g);
+  const dim3 grid((unsigned)sh.H, (unsigned)(sh.d_v / CB_COLS));
+  if (o_dtype == TPLA_BF16)
+    hipLaunchKernelGGL(combine_shards_mfma_kernel<bf16_t>, grid, dim3(256), smem, st, o_lat,
+                       static_cast<const bf16_t*>(W_UV_t), static_cast<bf16_t*>(o), sh.B, sh.H, sh.d_c, sh.d_v, sh.g);
+  else
+    hipLaunchKernelGGL(combine_shards_mfma_kernel<float>, grid, dim3(256), smem, st, o_lat,
+                       static_cast<const bf16_t*>(W_UV_t), static_cast<float*>(o), sh.B, sh.H, sh.d_c, sh.d_v, sh.g);
   return check_launch("combine_shards_mfma_kernel");
 }
 
@@ -256,8 +262,9 @@ constexpr int MC_COLS = 128;
 constexpr int MC_NW = 8;
 constexpr int MC_AHEAD = 8;      // partial rows in flight per lane
 
+template <typename OT>
 __global__ void __launch_bounds__(MC_NW * 64) merge_combine_mfma_kernel(DecodeArgs a, const bf16_t* __restrict__ W,
-                                                                        float* __restrict__ o, int d_c, int d_v,
+                                                                        OT* __restrict__ o, int d_c, int d_v,
                                                                         int spw) {
   extern __shared__ u32x4 slab4[];
   char* slab = reinterpret_cast<char*>(slab4);
@@ -454,7 +461,7 @@ __global__ void __launch_bounds__(MC_NW * 64) merge_combine_mfma_kernel(DecodeAr
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int bb = spw * mb + 4 * q4 + i;
-    if (4 * q4 + i < spw && bb < B) o[((size_t)bb * H + h) * d_v + col0 + 16 * wave + j16] = tsum[i];
+    if (4 * q4 + i < spw && bb < B) store_from_f32(o + ((size_t)bb * H + h) * d_v + col0 + 16 * wave + j16, tsum[i]);
   }
 }
 
@@ -463,12 +470,18 @@ bool merge_combine_mfma_supported(const tpla_shape_t& sh) {
          (sh.d_c / sh.g) % (MC_ROWS / MC_NW) == 0 && sh.d_v / MC_COLS <= 65535 && (sh.B + 7) / 8 <= 65535;
 }
 
-int launch_merge_combine_mfma(const DecodeArgs& a, const tpla_shape_t& sh, const void* W_UV_t, float* o,
+int launch_merge_combine_mfma(const DecodeArgs& a, const tpla_shape_t& sh, const void* W_UV_t, void* o, int o_dtype,
                               hipStream_t st) {
   constexpr size_t smem = (size_t)MC_ROWS * MC_COLS * 2;
   // dynamic LDS above the 64 KiB default needs opting in, once
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(merge_combine_mfma_kernel),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static const hipError_t attr = [] {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(merge_combine_mfma_kernel<float>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(merge_combine_mfma_kernel<bf16_t>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    return e;
+  }();
   if (attr != hipSuccess) {
     (void)hipGetLastError();
     return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", smem);
@@ -476,9 +489,13 @@ int launch_merge_combine_mfma(const DecodeArgs& a, const tpla_shape_t& sh, const
   // 16 sequences per workgroup once that gives every compute unit two workgroups, else 8
   const long long wg16 = (long long)sh.H * ((sh.B + 15) / 16) * (sh.d_v / MC_COLS);
   const int spw = wg16 >= 2LL * device_cu_count() ? 16 : 8;
-  hipLaunchKernelGGL(merge_combine_mfma_kernel,
-                     dim3((unsigned)sh.H, (unsigned)((sh.B + spw - 1) / spw), (unsigned)(sh.d_v / MC_COLS)),
-                     dim3(MC_NW * 64), smem, st, a, static_cast<const bf16_t*>(W_UV_t), o, sh.d_c, sh.d_v, spw);
+  const dim3 grid((unsigned)sh.H, (unsigned)((sh.B + spw - 1) / spw), (unsigned)(sh.d_v / MC_COLS));
+  if (o_dtype == TPLA_BF16)
+    hipLaunchKernelGGL(merge_combine_mfma_kernel<bf16_t>, grid, dim3(MC_NW * 64), smem, st, a,
+                       static_cast<const bf16_t*>(W_UV_t), static_cast<bf16_t*>(o), sh.d_c, sh.d_v, spw);
+  else
+    hipLaunchKernelGGL(merge_combine_mfma_kernel<float>, grid, dim3(MC_NW * 64), smem, st, a,
+                       static_cast<const bf16_t*>(W_UV_t), static_cast<float*>(o), sh.d_c, sh.d_v, spw);
   return check_launch("merge_combine_mfma_kernel");
 }
 
@@ -593,26 +610,27 @@ __global__ void __launch_bounds__(256) output_projection_mfma_kernel(const float
   }
 }
 
+template <typename OT>
 __global__ void __launch_bounds__(256) output_projection_reduce_kernel(const float* __restrict__ part,
-                                                                       float* __restrict__ out, size_t n,
+                                                                       OT* __restrict__ out, size_t n,
                                                                        int ksplit) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
   float v = part[i];
   for (int z = 1; z < ksplit; ++z) v += part[(size_t)z * n + i];
-  out[i] = v;
+  store_from_f32(out + i, v);
 }
 
 // Any storage type and width: one thread per output element.
-template <typename T>
+template <typename T, typename OT>
 __global__ void __launch_bounds__(256) output_projection_simple_kernel(const float* __restrict__ x,
                                                                        const T* __restrict__ W,
-                                                                       float* __restrict__ out, int K, int N) {
+                                                                       OT* __restrict__ out, int K, int N) {
   const int n = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
   if (n >= N) return;
   float v = 0.f;
   for (int k = 0; k < K; ++k) v = fmaf(x[(size_t)b * K + k], load_as_f32(W + (size_t)k * N + n), v);
-  out[(size_t)b * N + n] = v;
+  store_from_f32(out + (size_t)b * N + n, v);
 }
 
 // k-range split of the matrix-core path (0 = that path does not apply).
@@ -628,30 +646,48 @@ int output_projection_ksplit(const tpla_shape_t& sh, int D) {
   return ks;
 }
 
-int launch_output_projection(const tpla_shape_t& sh, const float* x, const void* W_O, int D, float* part,
-                             float* out, hipStream_t st) {
+template <typename OT>
+static int launch_output_projection_to(const tpla_shape_t& sh, const float* x, const void* W_O, int D, float* part,
+                                       OT* out, hipStream_t st) {
   const int K = sh.H * sh.d_v;
   const int ks = output_projection_ksplit(sh, D);
+  constexpr bool direct_ok = sizeof(OT) == sizeof(float);     // the matrix-core kernel writes float tiles
   if (ks == 0) {
     const dim3 grid((unsigned)((D + 255) / 256), (unsigned)sh.B);
     if (sh.dtype == TPLA_F32)
-      hipLaunchKernelGGL(output_projection_simple_kernel<float>, grid, dim3(256), 0, st, x,
+      hipLaunchKernelGGL((output_projection_simple_kernel<float, OT>), grid, dim3(256), 0, st, x,
                          static_cast<const float*>(W_O), out, K, D);
     else
-      hipLaunchKernelGGL(output_projection_simple_kernel<bf16_t>, grid, dim3(256), 0, st, x,
+      hipLaunchKernelGGL((output_projection_simple_kernel<bf16_t, OT>), grid, dim3(256), 0, st, x,
                          static_cast<const bf16_t*>(W_O), out, K, D);
     return check_launch("output_projection_simple_kernel");
   }
   const size_t smem = 2u * OP_ROWS * OP_COLS * 2;
-  float* dst = ks == 1 ? out : part;
+  const bool direct = ks == 1 && direct_ok;
+  float* dst = direct ? reinterpret_cast<float*>(out) : part;
   hipLaunchKernelGGL(output_projection_mfma_kernel, dim3((unsigned)(D / OP_COLS), (unsigned)ks), dim3(256), smem,
                      st, x, static_cast<const bf16_t*>(W_O), dst, sh.B, K, D, K / ks);
   int rc = check_launch("output_projection_mfma_kernel");
-  if (rc || ks == 1) return rc;
+  if (rc || direct) return rc;
   const size_t n = (size_t)sh.B * D;
-  hipLaunchKernelGGL(output_projection_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
+  hipLaunchKernelGGL(output_projection_reduce_kernel<OT>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
                      out, n, ks);
   return check_launch("output_projection_reduce_kernel");
+}
+
+// Scratch floats of the matrix-core path for an output of the given type (a bf16 output always goes
+// through the float partial tiles, also with a single k-range).
+size_t output_projection_scratch_floats(const tpla_shape_t& sh, int D, int out_dtype) {
+  const int ks = output_projection_ksplit(sh, D);
+  if (ks == 0 || (ks == 1 && out_dtype == TPLA_F32)) return 0;
+  return (size_t)ks * sh.B * D;
+}
+
+int launch_output_projection(const tpla_shape_t& sh, const float* x, const void* W_O, int D, float* part, void* out,
+                             int out_dtype, hipStream_t st) {
+  if (out_dtype == TPLA_BF16)
+    return launch_output_projection_to(sh, x, W_O, D, part, static_cast<bf16_t*>(out), st);
+  return launch_output_projection_to(sh, x, W_O, D, part, static_cast<float*>(out), st);
 }
 
 }  // namespace tpla

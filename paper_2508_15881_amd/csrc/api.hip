@@ -145,7 +145,7 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
                          const void* const* pools, const int32_t* block_table, int32_t max_pages_per_seq,
                          const int32_t* seq_lens, int32_t n_splits, void* workspace,
                          size_t workspace_bytes, float* o_lat, float* lse, void* stream,
-                         const void* W_UV_t = nullptr, float* o = nullptr) {
+                         const void* W_UV_t = nullptr, void* o = nullptr, int o_dtype = TPLA_F32) {
   int rc = check_shape(shape);
   if (rc) return rc;
   if (!q_lat || !q_pe || !pools || !block_table || !seq_lens || !workspace || !o_lat)
@@ -215,11 +215,11 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
   }
   if (rc) return rc;
   if (!W_UV_t) return launch_decode_merge(a, st);
-  if (merge_combine_mfma_supported(*shape)) return launch_merge_combine_mfma(a, *shape, W_UV_t, o, st);
+  if (merge_combine_mfma_supported(*shape)) return launch_merge_combine_mfma(a, *shape, W_UV_t, o, o_dtype, st);
   rc = launch_decode_merge(a, st);
   if (rc) return rc;
-  if (combine_mfma_supported(*shape)) return launch_combine_shards_mfma(*shape, o_lat, W_UV_t, o, st);
-  return launch_combine_shards(*shape, o_lat, W_UV_t, o, st);
+  if (combine_mfma_supported(*shape)) return launch_combine_shards_mfma(*shape, o_lat, W_UV_t, o, o_dtype, st);
+  return launch_combine_shards(*shape, o_lat, W_UV_t, o, o_dtype, st);
 }
 
 // ---- scratch of the entry point that takes no workspace ---------------------
@@ -450,39 +450,110 @@ int tpla_decode_shards_combine_static(const tpla_shape_t* shape, const void* q_l
                        n_splits, ws, (size_t)TPLA_STATIC_SCRATCH_BYTES, o_lat, lse, stream, W_UV_t, o);
 }
 
-int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t, float* o,
-                        void* stream) {
+static int check_out_dtype(int32_t d) {
+  if (d != TPLA_F32 && d != TPLA_BF16) return fail(TPLA_ERR_DTYPE, "output dtype %d is neither TPLA_F32 nor TPLA_BF16", d);
+  return TPLA_OK;
+}
+
+int tpla_combine_shards_to(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t, void* o,
+                           int32_t o_dtype, void* stream) {
   int rc = check_shape(shape);
   if (rc) return rc;
+  if ((rc = check_out_dtype(o_dtype))) return rc;
   if (!o_lat || !W_UV_t || !o) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
   if (!aligned16(o_lat) || !aligned16(W_UV_t) || !aligned16(o))
     return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
   if (combine_mfma_supported(*shape))
-    return launch_combine_shards_mfma(*shape, o_lat, W_UV_t, o, (hipStream_t)stream);
-  return launch_combine_shards(*shape, o_lat, W_UV_t, o, (hipStream_t)stream);
+    return launch_combine_shards_mfma(*shape, o_lat, W_UV_t, o, o_dtype, (hipStream_t)stream);
+  return launch_combine_shards(*shape, o_lat, W_UV_t, o, o_dtype, (hipStream_t)stream);
+}
+
+int tpla_combine_shards(const tpla_shape_t* shape, const float* o_lat, const void* W_UV_t, float* o,
+                        void* stream) {
+  return tpla_combine_shards_to(shape, o_lat, W_UV_t, o, TPLA_F32, stream);
+}
+
+int tpla_decode_shards_combine_to(const tpla_shape_t* shape, const void* q_lat, const void* q_pe,
+                                  const void* const* shard_pools, const int32_t* block_table,
+                                  int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t n_splits,
+                                  void* workspace, size_t workspace_bytes, const void* W_UV_t, void* o,
+                                  int32_t o_dtype, float* o_lat, float* lse, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_out_dtype(o_dtype))) return rc;
+  if (!W_UV_t || !o) return fail(TPLA_ERR_NULL, "W_UV_t/o is NULL");
+  return decode_common(shape, shape->g, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
+                       n_splits, workspace, workspace_bytes, o_lat, lse, stream, W_UV_t, o, o_dtype);
 }
 
 size_t tpla_output_projection_workspace_bytes(const tpla_shape_t* shape, int32_t D) {
   if (check_shape(shape) != TPLA_OK || D < 1) return 0;
-  const int ks = output_projection_ksplit(*shape, D);
-  return ks > 1 ? (size_t)ks * shape->B * D * sizeof(float) : 0;
+  // sized for either output type (a bf16 output always passes through float partial tiles)
+  return output_projection_scratch_floats(*shape, D, TPLA_BF16) * sizeof(float);
 }
 
-int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void* W_O, int32_t D,
-                           void* workspace, size_t workspace_bytes, float* out, void* stream) {
-  int rc = check_shape(shape);
-  if (rc) return rc;
+static int output_projection_common(const tpla_shape_t* shape, const float* o, const void* W_O, int32_t D,
+                                    void* workspace, size_t workspace_bytes, void* out, int32_t out_dtype,
+                                    void* stream) {
   if (!o || !W_O || !out) return fail(TPLA_ERR_NULL, "a tensor pointer is NULL");
   if (D < 1) return fail(TPLA_ERR_SHAPE, "D=%d", D);
   if ((long long)shape->H * shape->d_v > 2147483647LL || (long long)shape->B * D > 2147483647LL)
     return fail(TPLA_ERR_UNSUPPORTED, "H*d_v or B*D above 2^31-1");
   if (!aligned16(o) || !aligned16(W_O) || !aligned16(out) || !aligned16(workspace))
     return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
-  const size_t need = tpla_output_projection_workspace_bytes(shape, D);
+  const size_t need = output_projection_scratch_floats(*shape, D, out_dtype) * sizeof(float);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
   if ((D + 255) / 256 > 2147483647 / 2 || shape->B > 65535) return fail(TPLA_ERR_UNSUPPORTED, "grid too large");
-  return launch_output_projection(*shape, o, W_O, D, static_cast<float*>(workspace), out, (hipStream_t)stream);
+  return launch_output_projection(*shape, o, W_O, D, static_cast<float*>(workspace), out, out_dtype,
+                                  (hipStream_t)stream);
+}
+
+int tpla_output_projection_to(const tpla_shape_t* shape, const float* o, const void* W_O, int32_t D,
+                              void* workspace, size_t workspace_bytes, void* out, int32_t out_dtype, void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_out_dtype(out_dtype))) return rc;
+  return output_projection_common(shape, o, W_O, D, workspace, workspace_bytes, out, out_dtype, stream);
+}
+
+int tpla_output_projection(const tpla_shape_t* shape, const float* o, const void* W_O, int32_t D,
+                           void* workspace, size_t workspace_bytes, float* out, void* stream) {
+  return tpla_output_projection_to(shape, o, W_O, D, workspace, workspace_bytes, out, TPLA_F32, stream);
+}
+
+size_t tpla_attention_block_workspace_bytes(const tpla_shape_t* shape, int32_t max_pages_per_seq, int32_t n_splits,
+                                            int32_t D) {
+  const size_t a = tpla_workspace_bytes_all(shape, max_pages_per_seq, n_splits);
+  if (a == 0 || D < 1) return 0;
+  const size_t b = tpla_output_projection_workspace_bytes(shape, D);
+  return a > b ? a : b;
+}
+
+int tpla_decode_shards_project(const tpla_shape_t* shape, const void* q_lat, const void* q_pe,
+                               const void* const* shard_pools, const int32_t* block_table,
+                               int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t n_splits,
+                               void* workspace, size_t workspace_bytes, const void* W_UV_t, const void* W_O,
+                               int32_t D, void* out, int32_t out_dtype, float* o, float* o_lat, float* lse,
+                               void* stream) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if ((rc = check_out_dtype(out_dtype))) return rc;
+  if (!W_UV_t || !o || !W_O || !out) return fail(TPLA_ERR_NULL, "W_UV_t/W_O/o/out is NULL");
+  if (D < 1) return fail(TPLA_ERR_SHAPE, "D=%d", D);
+  // every check of the projection before the first launch: the partial results of the decode and the
+  // partial tiles of the projection use the workspace one after the other
+  const size_t need = output_projection_scratch_floats(*shape, D, out_dtype) * sizeof(float);
+  if (workspace_bytes < need)
+    return fail(TPLA_ERR_WORKSPACE, "workspace has %zu bytes, the projection needs %zu", workspace_bytes, need);
+  if (!aligned16(W_O) || !aligned16(out)) return fail(TPLA_ERR_ALIGN, "pointers must be 16-byte aligned");
+  if ((long long)shape->H * shape->d_v > 2147483647LL || (long long)shape->B * D > 2147483647LL ||
+      (D + 255) / 256 > 2147483647 / 2 || shape->B > 65535)
+    return fail(TPLA_ERR_UNSUPPORTED, "H*d_v, B*D or the grid too large");
+  rc = decode_common(shape, shape->g, q_lat, q_pe, shard_pools, block_table, max_pages_per_seq, seq_lens,
+                     n_splits, workspace, workspace_bytes, o_lat, lse, stream, W_UV_t, o, TPLA_F32);
+  if (rc) return rc;
+  return output_projection_common(shape, o, W_O, D, workspace, workspace_bytes, out, out_dtype, stream);
 }
 
 size_t tpla_prefill_workspace_bytes(const tpla_shape_t* shape, int64_t T) {

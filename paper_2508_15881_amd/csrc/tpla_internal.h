@@ -172,8 +172,9 @@ int launch_append_token_sliced(const tpla_shape_t& sh, const void* c_t, const vo
 
 // Output projection (after the combine): out = x @ W_O.
 int output_projection_ksplit(const tpla_shape_t& sh, int D);
+size_t output_projection_scratch_floats(const tpla_shape_t& sh, int D, int out_dtype);
 int launch_output_projection(const tpla_shape_t& sh, const float* x, const void* W_O, int D, float* part,
-                             float* out, hipStream_t st);
+                             void* out, int out_dtype, hipStream_t st);
 
 // Prefill (un-absorbed MLA, causal, packed sequences): see prefill_mfma.hip.
 bool prefill_mfma_supported(const tpla_shape_t& sh);
@@ -197,18 +198,18 @@ struct MuFactors {
 };
 int launch_absorb_query(const tpla_shape_t& sh, const void* q_nope, const void* W_UK_t,
                         const MuFactors& mu, void* q_lat, hipStream_t st);
-int launch_combine_shards(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
+int launch_combine_shards(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, void* o, int o_dtype,
                           hipStream_t st);
 // Matrix-core variants (bf16 weights, widths that tile): see absorb_combine_mfma.hip.
 bool absorb_mfma_supported(const tpla_shape_t& sh);
 int launch_absorb_query_mfma(const tpla_shape_t& sh, const void* q_nope, const void* W_UK_t,
                              const MuFactors& mu, void* q_lat, hipStream_t st);
 bool combine_mfma_supported(const tpla_shape_t& sh);
-int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, float* o,
+int launch_combine_shards_mfma(const tpla_shape_t& sh, const float* o_lat, const void* W_UV_t, void* o, int o_dtype,
                                hipStream_t st);
 // Split merge fused with the combine: reads the decode's partial results, writes o_lat, lse and o.
 bool merge_combine_mfma_supported(const tpla_shape_t& sh);
-int launch_merge_combine_mfma(const DecodeArgs& a, const tpla_shape_t& sh, const void* W_UV_t, float* o,
+int launch_merge_combine_mfma(const DecodeArgs& a, const tpla_shape_t& sh, const void* W_UV_t, void* o, int o_dtype,
                               hipStream_t st);
 
 // ---- small device helpers -------------------------------------------------

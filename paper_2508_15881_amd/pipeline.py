@@ -39,7 +39,7 @@ def make_shape(w):
 class DecodeStep:
     """Buffers for absorb -> g x decode_shard -> combine on one GPU."""
 
-    def __init__(self, shape, max_pages_per_seq, n_splits=0, device="cuda"):
+    def __init__(self, shape, max_pages_per_seq, n_splits=0, device="cuda", d_model=0):
         self.shape = shape
         self.max_pages = int(max_pages_per_seq)
         self.n_splits = int(n_splits)
@@ -53,6 +53,11 @@ class DecodeStep:
                             B.tpla_workspace_bytes_all(shape, self.max_pages, self.n_splits))
         if self.ws_bytes == 0:
             raise B.TplaError(-2, B.tpla_last_error())
+        # with a block output width the workspace also serves the output projection's partial tiles
+        self.d_model = int(d_model)
+        if self.d_model > 0:
+            self.ws_bytes = max(self.ws_bytes, B.tpla_attention_block_workspace_bytes(shape, self.max_pages, self.n_splits, self.d_model))
+            self.out = torch.empty((Bn, self.d_model), dtype=st, device=device)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
 
     def absorb(self, q_nope, W_UK_t, mu=None):
@@ -76,6 +81,13 @@ class DecodeStep:
         B.tpla_decode_shards_combine(self.shape, self.q_lat, q_pe, shard_pools, block_table, self.max_pages,
                                      seq_lens, self.n_splits, self.workspace, self.ws_bytes, W_UV_t, self.o,
                                      self.o_lat, self.lse)
+
+    def decode_all_project(self, q_pe, shard_pools, block_table, seq_lens, W_UV_t, W_O):
+        """All g slices in one launch, merge + combine, then the block's output projection: one call.
+        self.out [B, d_model] is written in the storage type (bf16 for bf16 shapes)."""
+        B.tpla_decode_shards_project(self.shape, self.q_lat, q_pe, shard_pools, block_table, self.max_pages, seq_lens,
+                                     self.n_splits, self.workspace, self.ws_bytes, W_UV_t, W_O, self.d_model, self.out,
+                                     self.shape.dtype, self.o, self.o_lat, self.lse)
 
     def run(self, q_nope, q_pe, W_UK_t, W_UV_t, shard_pools, block_table, seq_lens, mu=None, fused=True):
         """One decode layer-step.  fused: all slices in one decode launch with the merge and

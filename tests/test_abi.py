@@ -115,6 +115,19 @@ def test_other_entry_points_argument_checks():
     assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, A], A, 4, A, 0, A, 1 << 30, A + 2, A, A, None) == -3
     assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, None], A, 4, A, 0, A, 1 << 30, A, A, A, None) == -1
     assert _code(tp.tpla_decode_shards_combine, s, A, A, [A, A], A, 4, A, 2, A, 16, A, A, A, None) == -4
+    # chosen output types; the attention block in one call checks both stages before any launch
+    assert _code(tp.tpla_combine_shards_to, s, A, A, A, 9) == -5
+    assert _code(tp.tpla_combine_shards_to, s, A, A, None, tp.TPLA_BF16) == -1
+    assert _code(tp.tpla_output_projection_to, s, A, A, 64, A, 1 << 20, A, 9) == -5
+    assert _code(tp.tpla_decode_shards_combine_to, s, A, A, [A, A], A, 4, A, 0, A, 1 << 30, A, A, 9, A, None) == -5
+    big = 1 << 30
+    assert _code(tp.tpla_decode_shards_project, s, A, A, [A, A], A, 4, A, 0, A, big, A, None, 7168, A, tp.TPLA_F32, A, A, None) == -1
+    assert _code(tp.tpla_decode_shards_project, s, A, A, [A, A], A, 4, A, 0, A, big, A, A, 0, A, tp.TPLA_F32, A, A, None) == -2
+    assert _code(tp.tpla_decode_shards_project, s, A, A, [A, A], A, 4, A, 0, A, big, A, A, 7168, A, 3, A, A, None) == -5
+    assert _code(tp.tpla_decode_shards_project, s, A, A, [A, A], A, 4, A, 0, A, 64, A, A, 7168, A, tp.TPLA_BF16, A, A, None) == -4
+    assert _code(tp.tpla_decode_shards_project, s, A, A, [A, A], A, 4, A, 0, A, big, A, A + 2, 7168, A, tp.TPLA_F32, A, A, None) == -3
+    assert tp.tpla_attention_block_workspace_bytes(s, 512, 0, 7168) >= tp.tpla_workspace_bytes_all(s, 512, 0)
+    assert tp.tpla_attention_block_workspace_bytes(s, 512, 0, 0) == 0
     # empty work is accepted without a launch
     tp.tpla_transform_latent(s, tp.TPLA_U_IDENTITY, 0, None, None, A, A, 0, 1)
     tp.tpla_transform_latent_paged(s, tp.TPLA_U_IDENTITY, None, None, A, [A, A], None, 0)

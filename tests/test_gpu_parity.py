@@ -596,6 +596,87 @@ def test_output_projection(dtype, Bn, H, d_v, D):
     assert rel_err(out.cpu().numpy(), ref) <= 1e-5
 
 
+ATTN_BLOCK_CASES = [
+    ("dsv3_ragged", DSV3, [700, 64, 0, 1500, 129], 1024, (0, 3)),
+    ("g4_hadamard_shape", wl.scaled(wl.CONFIGS["ragged_g4"], H=16), [300, 65], 512, (0,)),
+    ("generic_f32", wl.Workload("odd", B=3, H=5, d_c=80, g=2, d_r=24, d_n=16, d_v=16, dtype="f32", seed=11), [200, 0, 65], 96, (0, 2)),
+]
+
+
+@pytest.mark.parametrize("name,w,lens,D,splits", ATTN_BLOCK_CASES, ids=[c[0] for c in ATTN_BLOCK_CASES])
+def test_decode_shards_project_matches_oracle_in_float_and_bf16(name, w, lens, D, splits):
+    """The attention block's output in one call (decode of all slices, merge, value up-projection and
+    sum over slices, then W_O) against the oracle's combine_shards + output_projection, with float
+    and with bfloat16 outputs, and bit for bit against the separate calls."""
+    lens = np.asarray(lens, dtype=np.int32)
+    Bn = len(lens)
+    w = wl.scaled(w, B=Bn)
+    dt = w.dtype
+    probs = [build_shard_problem(w, lens, rng_extra=i) for i in range(w.g)]
+    shape = pl.make_shape(w)
+    dev = "cuda"
+    q_lat = pl.to_device(np.stack([p["q_lat"] for p in probs]), dt)
+    q_pe = pl.to_device(probs[0]["q_pe"], dt)
+    pools = []
+    for i in range(w.g):
+        pool = probs[0]["pool"].copy()
+        for b in range(Bn):
+            for j in range((int(lens[b]) + w.page_tokens - 1) // w.page_tokens):
+                pool[probs[0]["bt"][b, j], :, :w.dl] = probs[i]["pool"][probs[i]["bt"][b, j], :, :w.dl]
+        pools.append(pl.to_device(pool, dt))
+    bt = torch.from_numpy(probs[0]["bt"]).to(dev)
+    ln = torch.from_numpy(lens).to(dev)
+    mp = probs[0]["max_pages"]
+    rng = np.random.default_rng(977)
+    Wv = wl.to_storage(rng.standard_normal((w.H, w.d_c, w.d_v)) * 0.05, dt)
+    Wo = wl.to_storage(rng.standard_normal((w.H * w.d_v, D)) * 0.05, dt)
+    Wv_d, Wo_d = pl.to_device(Wv, dt), pl.to_device(Wo, dt)
+    kpe = [r[:, w.dl:] for r in probs[0]["rows64"]]
+    ref_lat = np.stack([orc.shard_attention(wl.as_f64(probs[i]["q_lat"], dt), wl.as_f64(probs[0]["q_pe"], dt),
+                                            [r[:, :w.dl] for r in probs[i]["rows64"]], kpe, w.sm_scale)[0] for i in range(w.g)])
+    ref_o = orc.combine_shards(ref_lat, wl.as_f64(Wv, dt))
+    ref_out = orc.output_projection(ref_o, wl.as_f64(Wo, dt))
+    nan = float("nan")
+    for n_splits in splits:
+        _say(f"decode_shards_project {name} B={Bn} D={D} n_splits={n_splits}")
+        ws_b = tp.tpla_attention_block_workspace_bytes(shape, mp, n_splits, D)
+        assert ws_b >= tp.tpla_workspace_bytes_all(shape, mp, n_splits) and ws_b >= tp.tpla_output_projection_workspace_bytes(shape, D)
+        ws = torch.empty(ws_b, dtype=torch.uint8, device=dev)
+        o = torch.full((Bn, w.H, w.d_v), nan, dtype=torch.float32, device=dev)
+        o_lat = torch.full((w.g, Bn, w.H, w.dl), nan, dtype=torch.float32, device=dev)
+        out32 = torch.full((Bn, D), nan, dtype=torch.float32, device=dev)
+        out16 = torch.full((Bn, D), nan, dtype=torch.bfloat16, device=dev)
+        tp.tpla_decode_shards_project(shape, q_lat, q_pe, pools, bt, mp, ln, n_splits, ws, ws_b, Wv_d, Wo_d, D,
+                                      out32, tp.TPLA_F32, o, o_lat, None)
+        tp.tpla_decode_shards_project(shape, q_lat, q_pe, pools, bt, mp, ln, n_splits, ws, ws_b, Wv_d, Wo_d, D,
+                                      out16, tp.TPLA_BF16, o, o_lat, None)
+        torch.cuda.synchronize()
+        assert rel_err(o.cpu().numpy(), ref_o) <= TOL[dt]
+        assert rel_err(out32.cpu().numpy(), ref_out) <= TOL[dt]
+        # bfloat16 output: one rounding (2^-9 relative) on top
+        got16 = wl.as_f64(pl.from_device_bits(out16), "bf16")
+        assert rel_err(got16, ref_out) <= max(TOL[dt], 2.0 ** -8)
+        assert np.array_equal(pl.from_device_bits(out16), wl.f32_to_bf16_bits(out32.cpu().numpy()))
+        # the separate calls give the same bits
+        o2 = torch.full_like(o, nan); o_lat2 = torch.full_like(o_lat, nan); out2 = torch.full_like(out32, nan)
+        tp.tpla_decode_shards_combine(shape, q_lat, q_pe, pools, bt, mp, ln, n_splits, ws, ws_b, Wv_d, o2, o_lat2, None)
+        tp.tpla_output_projection(shape, o2, Wo_d, D, ws, ws_b, out2)
+        torch.cuda.synchronize()
+        assert torch.equal(out2, out32) and torch.equal(o2, o)
+        # o itself as bfloat16 from the fused decode + combine call and from the combine alone
+        ob = torch.full((Bn, w.H, w.d_v), nan, dtype=torch.bfloat16, device=dev)
+        tp.tpla_decode_shards_combine_to(shape, q_lat, q_pe, pools, bt, mp, ln, n_splits, ws, ws_b, Wv_d, ob, tp.TPLA_BF16,
+                                         o_lat2, None)
+        oc = torch.full_like(ob, nan)
+        tp.tpla_combine_shards_to(shape, o_lat, Wv_d, oc, tp.TPLA_BF16)
+        of = torch.full_like(o, nan)
+        tp.tpla_combine_shards(shape, o_lat, Wv_d, of)
+        torch.cuda.synchronize()
+        assert np.array_equal(pl.from_device_bits(ob), wl.f32_to_bf16_bits(o.cpu().numpy()))
+        assert np.array_equal(pl.from_device_bits(oc), wl.f32_to_bf16_bits(of.cpu().numpy()))
+        assert rel_err(wl.as_f64(pl.from_device_bits(oc), "bf16"), ref_o) <= max(TOL[dt], 2.0 ** -8)
+
+
 def test_layer_step_as_hip_graph_replays_like_eager():
     """The step captured in a HIP graph: several replays, eager work and synchronisations between
     them, new inputs written into the same tensors; every replay equals the eager result bit for bit."""
