@@ -3,6 +3,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dsv3_32k]
     python bench.py --traffic-calibration        (copy of known size, for scaling rocprofv3's byte counters)
+    python bench.py --wg-timeline [--workload W] (per-workgroup timeline; library built with -DTPLA_WG_TIMELINE)
 
 A step is one decode layer-step over one batch that is already resident in
 HBM: absorb the query, run the attention of all g latent slices one after the
@@ -322,6 +323,74 @@ def traffic_calibration():
                       "read_bytes_per_stream_read_launch": src.numel() * 2 - (src.numel() * 2) % 20480, "launches_each": 5}))
 
 
+def wg_timeline(args):
+    """Per-workgroup timeline of the split kernel (needs a library built with
+    TPLA_EXTRA_HIPCC_FLAGS=-DTPLA_WG_TIMELINE): start skew, time to the first tile, end of the tile
+    loop and end of the workgroup, and how the workgroups' durations differ by placement round
+    (workgroup id / compute units) and by XCC, over several settled launches."""
+    import ctypes
+    import numpy as np
+    import torch
+    import paper_2508_15881_amd as tp
+    from paper_2508_15881_amd import workloads as wl
+    lib = tp.load_library()
+    if not hasattr(lib, "tpla_debug_wg_timeline"):
+        print("bench.py --wg-timeline: build the library with TPLA_EXTRA_HIPCC_FLAGS=-DTPLA_WG_TIMELINE first", file=sys.stderr)
+        sys.exit(1)
+    hip = ctypes.CDLL("libamdhip64.so")
+    p_t, p_w = ctypes.c_void_p(), ctypes.c_void_p()
+    assert lib.tpla_debug_wg_timeline(ctypes.byref(p_t), ctypes.byref(p_w)) == 0
+    w = wl.CONFIGS[args.workload]
+    if args.set:
+        w = wl.scaled(w, **{k: int(v) for k, v in (kv.split("=") for kv in args.set)})
+    p = Prepared(w, args.n_splits)
+    n_wg = p.step.ws_bytes // (w.H * (w.dl + 2) * 4) - w.g * w.B if args.n_splits == 0 else 0
+    assert 0 < n_wg <= 4096, "the timeline covers balanced launches of at most 4096 workgroups"
+    run = lambda: p.step.decode_all(p.q_pe, p.pools, p.bt, p.lens)
+    p.step.absorb(p.q_nope, p.W_UK_t, p.mu)
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < max(args.settle_s, 0.5):
+        for _ in range(50):
+            run()
+        torch.cuda.synchronize()
+    durs, firsts, loops, starts, kern = [], [], [], [], []
+    for _ in range(12):
+        tp.tpla_profile_enable(20)
+        for _ in range(20):
+            run()
+        torch.cuda.synchronize()
+        kern.append(float(np.mean(tp.tpla_profile_collect(20))) * 1e3)
+        buf = np.zeros(4096 * 4, dtype=np.uint64)
+        assert hip.hipMemcpy(buf.ctypes.data_as(ctypes.c_void_p), p_t, buf.nbytes, 2) == 0
+        t = buf.reshape(-1, 4)[:n_wg].astype(np.float64) * 0.01       # microseconds
+        t -= t[:, 0].min()
+        starts.append(t[:, 0]); firsts.append(t[:, 1] - t[:, 0]); loops.append(t[:, 2]); durs.append(t[:, 3] - t[:, 0])
+    tp.tpla_profile_enable(0)
+    where = np.zeros(4096 * 2, dtype=np.uint32)
+    assert hip.hipMemcpy(where.ctypes.data_as(ctypes.c_void_p), p_w, where.nbytes, 2) == 0
+    xcc = (where.reshape(-1, 2)[:n_wg, 0] & 15).astype(int)
+    D = np.array(durs)
+    rel = (D / D.mean(axis=1, keepdims=True)).mean(axis=0)           # systematic part, relative to the launch mean
+    z = (D - D.mean(axis=1, keepdims=True)) / D.std(axis=1, keepdims=True)
+    cc = np.corrcoef(z)
+    pct = lambda x: [round(float(v), 2) for v in np.percentile(np.concatenate(x), [0, 10, 50, 90, 100])]
+    try:
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+    except Exception:
+        cus = 256
+    rounds = np.arange(n_wg) // cus
+    print(json.dumps({
+        "workload": w.name, "workgroups": int(n_wg), "launches": 12 * 20, "kernel_us_mean_with_timeline_code": float(np.mean(kern)),
+        "percentiles": "min, 10 %, median, 90 %, max over workgroups and 12 sampled launches, microseconds",
+        "workgroup_start_after_first": pct(starts), "first_tile_landed_after_start": pct(firsts),
+        "tile_loop_done_after_first_start": pct(loops), "workgroup_duration": pct(durs),
+        "duration_max_over_mean_per_launch": [round(float(d.max() / d.mean()), 3) for d in D],
+        "same_workgroups_slow_every_launch_correlation": round(float((cc.sum() - len(cc)) / (len(cc) * (len(cc) - 1))), 3),
+        "relative_duration_by_placement_round": {str(r): round(float(rel[rounds == r].mean()), 3) for r in sorted(set(rounds.tolist()))},
+        "relative_duration_by_xcc": {str(x): round(float(rel[xcc == x].mean()), 3) for x in sorted(set(xcc.tolist()))},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -341,6 +410,8 @@ def main():
                     help="only the timed steps: no one-slice loop, stage timings, MLA reference or other workloads "
                          "(keeps every launch of the decode kernel in a profile identical)")
     ap.add_argument("--traffic-calibration", action="store_true")
+    ap.add_argument("--wg-timeline", action="store_true",
+                    help="per-workgroup timeline of the split kernel (library built with -DTPLA_WG_TIMELINE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (all g latent slices are computed on it and "
@@ -359,6 +430,9 @@ def main():
     tp.load_library()           # fails loudly when the HIP library is not built
     if args.traffic_calibration:
         traffic_calibration()
+        return
+    if args.wg_timeline:
+        wg_timeline(args)
         return
     dev = "cuda"
     w = wl.CONFIGS[args.workload]

@@ -25,6 +25,22 @@
 namespace tpla {
 
 constexpr int PAGE_TOKENS = 64;
+#ifndef TPLA_H32_STAGES
+#define TPLA_H32_STAGES 4
+#endif
+
+// Measurement build only (-DTPLA_WG_TIMELINE, see bench.py --wg-timeline): every workgroup of the
+// balanced kernel leaves four readings of the 100 MHz wall clock (start, first tile landed, tile loop
+// done, end) and where it ran (XCC id and hardware id registers).  Nothing of this is compiled otherwise.
+#ifdef TPLA_WG_TIMELINE
+__device__ unsigned long long g_wg_times[4096 * 4];
+__device__ unsigned g_wg_where[4096 * 2];
+#define TPLA_TL_MARK(k) do { if (threadIdx.x == 0 && blockIdx.x < 4096) g_wg_times[blockIdx.x * 4 + (k)] = wall_clock64(); } while (0)
+#define TPLA_TL_MARK_ONCE(k) do { if (threadIdx.x == 0 && blockIdx.x < 4096 && g_wg_times[blockIdx.x * 4 + (k)] == 0) g_wg_times[blockIdx.x * 4 + (k)] = wall_clock64(); } while (0)
+#else
+#define TPLA_TL_MARK(k) do { } while (0)
+#define TPLA_TL_MARK_ONCE(k) do { } while (0)
+#endif
 
 // One work item: pages [p0, p1) of sequence b of slice `shard` (L tokens in
 // the sequence, p1 <= its page count); the partial result goes to slot
@@ -164,6 +180,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
     // all waves: tile t visible, tile t-1 no longer read.  A bare barrier:
     // __syncthreads() would add a fence that waits for the loads in flight.
     __builtin_amdgcn_s_barrier();
+    if (t == 0) TPLA_TL_MARK_ONCE(1);
     if (t + FL < ntiles) issue(t + FL);
     const unsigned tile = lds_base + (unsigned)((t % NSTAGE) * TILE_BYTES);
     const int valid = t_end - (t_begin + t * TOK);
@@ -274,6 +291,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
     }
     }
 
+  TPLA_TL_MARK(2);
   float l_tot = l_run + __shfl_xor(l_run, 16);
   l_tot += __shfl_xor(l_tot, 32);
   const size_t item = slot * a.H + head;
@@ -286,12 +304,342 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
   }
 }
 
+// The same work item with 32 heads per wave on 32x32x16 MFMAs.  Every K and V
+// fragment read from LDS then serves twice as many heads: half the LDS reads,
+// half the MFMA issues and half the operand fetches per cache byte.  The price
+// is one wave per SIMD (128 accumulator + 80 query registers for 256-wide
+// slices), so nothing else hides a wave's softmax arithmetic: the loop is
+// software-pipelined instead.  While tile t+1's score MFMAs run (32 cycles of
+// the matrix core each, 8 of the issue port), the wave issues tile t's softmax
+// in their shadow, a few instructions after every MFMA:
+//   S^T[tok, head] = K[tok, :] . Q[head, :]     M = 32 tokens, N = 32 heads, 16 k per MFMA
+//   O^T[dim, head] += V^T[dim, tok] . P^T[tok, head]   M = 32 latent dims, N = 32 heads, 16 tokens per MFMA
+// Lane l holds head l % 32; accumulator element i of a 32x32 result is row
+// 8 (i / 4) + 4 (l / 32) + i % 4.  For the second product the 16 tokens of a
+// k-step are taken in the order in which the score accumulator already holds
+// them (k index 8 (l / 32) + e  <->  token 8 (e / 4) + 4 (l / 32) + e % 4 of the
+// step), so elements 8 s .. 8 s + 7 of the exponentiated scores are the B
+// operand of step s as they stand, and V^T is fetched with two transposing
+// reads per fragment (tokens +0..3 and +8..11 of the lane's half).
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Tile swizzle of the 32-head kernel: piece c of token t sits at c ^ swz32(t) within its group of 8.
+// Its two read patterns differ from the 16-head kernel's: the score operand takes 32 consecutive
+// tokens at one piece (two pieces per instruction), the transposing read 4 consecutive tokens x 4
+// consecutive pieces per 32 lanes.  With t & 7 tokens t and t + 8 collide in the first (5.3 against 3.0
+// cycles per instruction in a read-only loop) and tokens t and t + 2 in the second (3.0 against 1.6);
+// of the 3-bit XOR-linear maps of the token index, those with output bit 2 = token bit 1 and the other
+// two bits from token bits 2 and 3 run both at full rate.
+__device__ __forceinline__ int swz32(int tok) { return ((tok >> 2) & 3) | ((tok & 2) << 1); }
+
+template <int DL, int DR, int NW, int TOK, int NSTAGE>
+__device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, int shard, int b, int L,
+                                              int p0, int p1, size_t slot) {
+  constexpr int RC = (DL + DR) / 8;      // 16-byte pieces per row
+  constexpr int KS = (DL + DR) / 16;     // 16-wide k-steps of the score product
+  constexpr int DB = DL / 32;            // 32-wide blocks of latent dims
+  constexpr int TC = TOK * RC;           // pieces per tile
+  constexpr int NI = TC / 64;            // direct-to-LDS instructions per tile
+  constexpr int CPT = (NI + NW - 1) / NW;   // of which each wave issues this many
+  constexpr int TPP = PAGE_TOKENS / TOK; // tiles per page
+  constexpr int TILE_BYTES = TC * 16;
+  constexpr int ROWB = RC * 16;          // bytes per row
+  constexpr int FL = NSTAGE - 2;         // tiles in flight: tiles t (values) and t+1 (keys) are both in use
+  constexpr int KS1 = 6;                 // score MFMAs issued before the rescale decision
+  static_assert(RC % 8 == 0, "row must be a multiple of 64 elements");
+  static_assert(TOK == 32 && TC % 64 == 0, "one 32-token score block per tile");
+  static_assert(TILE_BYTES % 4096 == 0, "tile bases must leave address bits 5..11 to the lane offsets");
+  static_assert(FL == 1 || FL == 2, "one or two tiles in flight");
+  static_assert(2 * CPT < 64, "vmcnt");
+  static_assert(KS >= KS1 + 4 && KS1 >= 5 && DB >= 4, "pipeline chunking");
+
+  const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)smem);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n32 = lane & 31, hi = lane >> 5;
+  const int vb = shard * a.B + b;
+  int pg_reg = a.block_table[(size_t)b * a.max_pages + min(p0 + lane, p1 - 1)];
+  asm volatile("" : "+v"(pg_reg));
+  const int t_begin = p0 * PAGE_TOKENS;
+  const int t_end = min(p1 * PAGE_TOKENS, L);
+  const int ntiles = (t_end - t_begin + TOK - 1) / TOK;
+  const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
+  const char* pool = static_cast<const char*>(a.pools[shard]);
+  __syncthreads();      // the ring restarts at buffer 0: nobody may still be reading the previous item's tiles
+
+  // ---- direct-to-LDS bookkeeping (as in decode_item) ------------------------
+  int ld_tok[CPT];
+  unsigned ld_goff[CPT];
+  int ld_k[CPT];
+#pragma unroll
+  for (int j = 0; j < CPT; ++j) {
+    int k = wave + j * NW;
+    if (k >= NI) k -= NW;
+    const int x = k * 64 + lane;
+    const int tok = x / RC, cs = x % RC;
+    ld_k[j] = k;
+    ld_tok[j] = tok;
+    ld_goff[j] = (unsigned)((tok * RC + (cs ^ swz32(tok))) * 16);
+  }
+  int pg_base = 0;
+  auto issue = [&](int t) {
+    const int T = p0 * TPP + t;
+    const int pg = t / TPP;
+    if (pg - pg_base >= 64) {
+      pg_base += 64;
+      pg_reg = bt[min(p0 + pg_base + lane, p1 - 1)];
+      asm volatile("" : "+v"(pg_reg));
+    }
+    const int page = __builtin_amdgcn_readlane(pg_reg, pg - pg_base);
+    const char* src = pool + (size_t)page * (PAGE_TOKENS * ROWB) + (size_t)(T % TPP) * TILE_BYTES;
+    const int valid = t_end - (t_begin + t * TOK);
+    char* dst = reinterpret_cast<char*>(smem) + (t % NSTAGE) * TILE_BYTES;
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+      const unsigned off = (ld_tok[j] < valid) ? ld_goff[j] : (ld_goff[j] % ROWB);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + off),
+                                       (__attribute__((address_space(3))) void*)(dst + ld_k[j] * 1024),
+                                       16, 0, 2 /* streaming: do not keep in L2 */);
+    }
+  };
+  // rows of the last tile that lie past the end of the sequence are cleared once it has landed
+  auto clear_tail = [&](int t) {
+    const int valid = t_end - (t_begin + t * TOK);
+    if (valid < TOK) {
+      u32x4* tl = smem + (t % NSTAGE) * TC;
+      for (int x = tid; x < TC; x += NW * 64)
+        if (x / RC >= valid) tl[x] = u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+    }
+  };
+
+  // ---- per-lane LDS byte offsets --------------------------------------------
+  // score product: token n32, piece 2 ks + hi = 8 (ks / 4) + (2 (ks % 4) | hi); the swizzle only
+  // touches the low three bits of the piece index, and (2 j | hi) ^ x = (hi ^ x) ^ 2 j, so the
+  // offsets of ks % 4 = 1, 2, 3 are that of 0 with address bits 5 and 6 flipped
+  const unsigned k_off = (unsigned)(n32 * ROWB + ((hi ^ swz32(n32)) * 16));
+  // output product: 16-lane group gq = (hi, dim half); lane j of it points at token 4 hi + j / 4 of the
+  // k-step and dims 32 db + 16 half + 4 (j % 4) .. +3, i.e. piece 4 db + 2 half + (j % 4) / 2
+  // (db odd: address bit 6 flipped; tokens + 8: swz32 changes by 2, address bit 5 flipped)
+  const int j16 = lane & 15, half = (lane >> 4) & 1;
+  const int v_tok = 4 * hi + (j16 >> 2);
+  const int pl = 2 * half + ((j16 & 3) >> 1);
+  const unsigned v_off = (unsigned)(v_tok * ROWB + ((pl ^ swz32(v_tok)) * 16) + (j16 & 1) * 8);
+
+  f32x16 acc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[d][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  issue(0);
+  if (ntiles > 1) issue(1);
+  if (FL >= 2 && ntiles > 2) issue(2);
+
+  // ---- this wave's 32 heads of the query, as B operands ----------------------
+  const int head = wave * 32 + n32;
+  bf16x8 qreg[KS];
+  {
+    const bf16_t* ql = static_cast<const bf16_t*>(a.q_lat) + ((size_t)vb * a.H + head) * DL;
+    const bf16_t* qp = static_cast<const bf16_t*>(a.q_pe) + ((size_t)b * a.H + head) * DR;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int k0 = ks * 16 + hi * 8;
+      qreg[ks] = (k0 < DL) ? *reinterpret_cast<const bf16x8*>(ql + k0)
+                           : *reinterpret_cast<const bf16x8*>(qp + (k0 - DL));
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));   // complete before the loop
+  }
+
+  // Score MFMAs FIRST .. LAST-1 of the tile at LDS address `tile` into two independent chains (even and
+  // odd k-steps), a ring of 4 K fragments ahead; `between(i)` is called after MFMA i has been issued.
+  bf16x8 kf[4];
+  f32x16 sA, sB;
+  auto score_reads_begin = [&](unsigned tile) {
+    const unsigned kb = tile + k_off;
+    const unsigned ka[4] = {kb, kb ^ 32u, kb ^ 64u, kb ^ 96u};
+    static_for<4>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      lds_read_b128<(i >> 2) * 128>(kf[i], ka[i & 3]);
+    });
+  };
+  auto score_mfmas = [&](unsigned tile, auto first_c, auto last_c, auto&& between) {
+    constexpr int FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+    const unsigned kb = tile + k_off;
+    const unsigned ka[4] = {kb, kb ^ 32u, kb ^ 64u, kb ^ 96u};
+    static_for<LAST - FIRST>([&](auto ic) {
+      constexpr int i = FIRST + decltype(ic)::value;
+      constexpr int ahead = (KS - 1 - i) < 3 ? (KS - 1 - i) : 3;
+      lds_wait<ahead>(kf[i & 3]);
+      if constexpr (i & 1)
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qreg[i], sB, 0, 0, 0);
+      else
+        sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qreg[i], sA, 0, 0, 0);
+      if constexpr (i + 4 < KS) lds_read_b128<((i + 4) >> 2) * 128>(kf[i & 3], ka[i & 3]);
+      between(ic);
+      __builtin_amdgcn_sched_barrier(0);       // keep the arithmetic of this step in this MFMA's shadow
+    });
+  };
+  auto zero_scores = [&]() {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sA[i] = sB[i] = 0.f;
+  };
+  auto nothing = [](auto) {};
+  using C0 = std::integral_constant<int, 0>;
+  using C1 = std::integral_constant<int, KS1>;
+  using C2 = std::integral_constant<int, KS>;
+
+  // ---- prologue: tile 0 has landed; its scores -----------------------------------
+  if (FL >= 2 && ntiles > 2)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * CPT));
+  else if (ntiles > 1)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(CPT));
+  else
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  __builtin_amdgcn_s_barrier();
+  clear_tail(0);
+  float s_cur[16];
+  {
+    zero_scores();
+    score_reads_begin(lds_base);
+    score_mfmas(lds_base, C0{}, C2{}, nothing);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_cur[i] = sA[i] + sB[i];
+  }
+
+  // The accumulators sit in the accumulation registers, which only MFMAs write: rescaling them means
+  // copying all 128 out and back.  So the tile loop itself never rescales: when a tile's scores exceed
+  // the reference by more than LAZY it stops before using them, the (rare) rescale runs outside, and
+  // the loop resumes at the same tile (the score MFMAs of the next tile that were under way start over).
+  int t = 0;
+  bool resumed = false;      // tile t + 1 has already been waited for
+  while (t < ntiles) {
+    float m_pending = m_run;
+    bool rescale = false;
+    for (; t < ntiles; ++t) {
+      const bool has_next = t + 1 < ntiles;
+      if (has_next && !resumed) {
+        // tile t + 1 has landed once only the tiles requested after it are outstanding
+        if (FL >= 2 && t + 2 < ntiles)
+          __builtin_amdgcn_s_waitcnt(vmcnt_imm(CPT));
+        else
+          __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __builtin_amdgcn_s_barrier();          // tile t + 1 visible to all waves, tile t - 1 no longer read
+        if (t + 1 + FL < ntiles) issue(t + 1 + FL);
+        clear_tail(t + 1);
+      }
+      resumed = false;
+      const unsigned tile = lds_base + (unsigned)((t % NSTAGE) * TILE_BYTES);
+      // the last tile has no successor: its own keys are multiplied once more and the result dropped
+      const unsigned tile_next = lds_base + (unsigned)(((has_next ? t + 1 : t) % NSTAGE) * TILE_BYTES);
+      const int valid = t_end - (t_begin + t * TOK);
+
+      // ---- first score MFMAs of tile t + 1; in their shadow: the maximum of tile t's scores ----
+      if (valid < TOK) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (8 * (i >> 2) + 4 * hi + (i & 3) >= valid) s_cur[i] = -INFINITY;
+      }
+      zero_scores();
+      score_reads_begin(tile_next);
+      float m4[4], mx = 0.f;
+      score_mfmas(tile_next, C0{}, C1{}, [&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr (i < 4) m4[i] = fmaxf(fmaxf(s_cur[4 * i], s_cur[4 * i + 1]), fmaxf(s_cur[4 * i + 2], s_cur[4 * i + 3]));
+        if constexpr (i == 4) mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3])) * a.scale_log2;
+      });
+      if (__any(mx > m_run + LAZY)) {
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (t == 0) {
+          m_run = fmaxf(m_run, mx);      // first tile of the item: nothing accumulated yet, nothing to rescale
+        } else {
+          m_pending = fmaxf(m_run, mx);
+          rescale = true;
+          resumed = true;
+          break;
+        }
+      }
+
+      // ---- the other score MFMAs of tile t + 1; in their shadow: tile t's exponentials ----
+      float psum = 0.f;
+      bf16x8 pb[2];
+      score_mfmas(tile_next, C1{}, C2{}, [&](auto ic) {
+        constexpr int i = decltype(ic)::value;      // 0 .. KS - KS1 - 1: the 16 scores dealt over these steps
+        constexpr int per = (16 + (KS - KS1) - 1) / (KS - KS1);
+#pragma unroll
+        for (int e = per * i; e < per * (i + 1) && e < 16; ++e) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s_cur[e], a.scale_log2, -m_run));
+          psum += p;
+          pb[e >> 3][e & 7] = (bf16_t)p;
+        }
+      });
+      l_run += psum;
+
+      // ---- output: O^T += V^T P^T of tile t, a ring of 4 V fragments; in its shadow the new scores
+      //      leave the accumulation registers ----
+      static_for<2>([&](auto sc) {
+        constexpr int s = decltype(sc)::value;
+        u32x2 vlo[4], vhi[4];
+        const unsigned vb0 = tile + v_off + (unsigned)(s * 16 * ROWB);
+        const unsigned va[2] = {vb0, vb0 ^ 64u};
+        const unsigned vh[2] = {vb0 ^ 32u, vb0 ^ 96u};
+        static_for<4>([&](auto ic) {
+          constexpr int d = decltype(ic)::value;
+          lds_read_tr_b64<(d >> 1) * 128>(vlo[d], va[d & 1]);
+          lds_read_tr_b64<(d >> 1) * 128 + 8 * ROWB>(vhi[d], vh[d & 1]);
+        });
+        static_for<DB>([&](auto ic) {
+          constexpr int d = decltype(ic)::value;
+          constexpr int ahead = (DB - 1 - d) < 3 ? (DB - 1 - d) : 3;
+          lds_wait<2 * ahead>(vlo[d & 3], vhi[d & 3]);
+          const u32x4 v4 = {vlo[d & 3][0], vlo[d & 3][1], vhi[d & 3][0], vhi[d & 3][1]};
+          acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v4), pb[s], acc[d], 0, 0, 0);
+          if constexpr (d + 4 < DB) {
+            constexpr int d2 = d + 4;
+            lds_read_tr_b64<(d2 >> 1) * 128>(vlo[d & 3], va[d2 & 1]);
+            lds_read_tr_b64<(d2 >> 1) * 128 + 8 * ROWB>(vhi[d & 3], vh[d2 & 1]);
+          }
+          // 16 sums over the 2 DB output MFMAs of the tile
+          constexpr int step = s * DB + d, per = (16 + 2 * DB - 1) / (2 * DB);
+#pragma unroll
+          for (int e = step * per; e < (step + 1) * per && e < 16; ++e) s_cur[e] = sA[e] + sB[e];
+          __builtin_amdgcn_sched_barrier(0);
+        });
+      });
+    }
+    if (rescale) {
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_pending);
+      l_run *= alpha;
+      m_run = m_pending;
+#pragma unroll
+      for (int d = 0; d < DB; ++d) acc[d] *= alpha;
+    }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const size_t item = slot * a.H + head;
+  float* pacc = a.part_acc + item * DL + 4 * hi;
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<f32x4*>(pacc + 32 * d + 8 * q) = f32x4{acc[d][4 * q], acc[d][4 * q + 1], acc[d][4 * q + 2], acc[d][4 * q + 3]};
+  if (hi == 0) {
+    a.part_ml[item * 2 + 0] = m_run;
+    a.part_ml[item * 2 + 1] = l_tot;
+  }
+}
+
 // Static chunks: workgroup = (slice, sequence, chunk s), pages [s*pps, (s+1)*pps).
 // Waves per SIMD the register allocation must allow: two 4-wave workgroups
 // (or one 8-wave workgroup) per compute unit need 2; a 512-wide slice only
 // fits one workgroup per compute unit in LDS, so it keeps the full budget.
-template <int DL, int NW>
-constexpr int waves_per_simd() { return DL >= 512 ? (NW >= 8 ? 2 : 1) : (NW >= 4 ? 2 : 1); }
+template <int DL, int NW, int HPW = 16>
+constexpr int waves_per_simd() {
+  if (HPW == 32) return DL <= 128 ? 2 : 1;
+  return DL >= 512 ? (NW >= 8 ? 2 : 1) : (NW >= 4 ? 2 : 1);
+}
 // Tiles in the LDS ring (one fewer in flight) and fragment ring depth (LDS reads ahead of the MFMA that
 // consumes them).  Measured: a ring of 4 tiles is no faster than 3 for any width (128-wide slices: 1144
 // against 1122 us on the ragged batch), and fragment rings of 8 or 16 change nothing even where a wave
@@ -301,8 +649,8 @@ constexpr int ring_stages() { return 3; }
 template <int DL, int NW>
 constexpr int frag_ring() { return 4; }
 
-template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR>
-__global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mfma_kernel(DecodeArgs a) {
+template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR, int HPW>
+__global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW, HPW>())) decode_mfma_kernel(DecodeArgs a) {
   extern __shared__ u32x4 smem[];        // NSTAGE tiles
   const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
   const int shard = vb / a.B, b = vb % a.B;
@@ -311,7 +659,10 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
   const int p0 = s * a.pages_per_split;
   if (p0 >= n_pages) return;
   const int p1 = min(p0 + a.pages_per_split, n_pages);
-  decode_item<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
+  if constexpr (HPW == 32)
+    decode_item32<DL, DR, NW, TOK, NSTAGE>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
+  else
+    decode_item<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
 }
 
 // Balanced ranges: the pages of all (slice, sequence) pairs are laid end to
@@ -321,9 +672,17 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
 // whose partial result goes to slot w + v (v = slice * B + sequence; strictly
 // increasing along the items, hence unique).  Workgroup 0 also publishes the
 // page offsets of the sequences for the merge.
-template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR>
-__global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mfma_balanced_kernel(DecodeArgs a) {
+template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR, int HPW>
+__global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW, HPW>())) decode_mfma_balanced_kernel(DecodeArgs a) {
   extern __shared__ u32x4 smem[];
+#ifdef TPLA_WG_TIMELINE
+  if (threadIdx.x == 0 && blockIdx.x < 4096) {
+    g_wg_times[blockIdx.x * 4] = wall_clock64();
+    g_wg_times[blockIdx.x * 4 + 1] = 0;
+    g_wg_where[blockIdx.x * 2] = __builtin_amdgcn_s_getreg((31 << 11) | 20);      // XCC_ID
+    g_wg_where[blockIdx.x * 2 + 1] = __builtin_amdgcn_s_getreg((31 << 11) | 4);   // HW_ID
+  }
+#endif
   const int lane = threadIdx.x & 63;
   const int n_v = a.n_shards * a.B;
   const int w = blockIdx.x;
@@ -357,11 +716,18 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW>())) decode_mf
       hit &= hit - 1;
       const int Ls = __shfl(L, src), p0 = __shfl(p0l, src), p1 = __shfl(p1l, src);
       const int vs = v0 + src;
-      decode_item<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
+      if constexpr (HPW == 32)
+        decode_item32<DL, DR, NW, TOK, NSTAGE>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
+      else
+        decode_item<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
     }
     base += __shfl(incl, 63);
   }
   if (w == 0 && threadIdx.x == 0) a.plan[n_v] = total;
+#ifdef TPLA_WG_TIMELINE
+  __syncthreads();
+  TPLA_TL_MARK(3);
+#endif
 }
 
 bool decode_mfma_supported(const tpla_shape_t& sh) {
@@ -382,12 +748,12 @@ struct KernelInfo {
   bool ready = false;
 };
 
-template <int DL, int NW>
+template <int DL, int NW, int HPW>
 static KernelInfo make_kernel_info() {
-  constexpr int TOK = 32, NSTAGE = ring_stages<DL>(), KR = frag_ring<DL, NW>();
+  constexpr int TOK = 32, NSTAGE = HPW == 32 ? (DL <= 128 ? 3 : TPLA_H32_STAGES) : ring_stages<DL>(), KR = frag_ring<DL, NW>();
   KernelInfo info;
-  info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE, KR>;
-  info.fn_balanced = decode_mfma_balanced_kernel<DL, 64, NW, TOK, NSTAGE, KR>;
+  info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE, KR, HPW>;
+  info.fn_balanced = decode_mfma_balanced_kernel<DL, 64, NW, TOK, NSTAGE, KR, HPW>;
   info.smem = (size_t)NSTAGE * TOK * ((DL + 64) / 8) * 16;
   info.threads = NW * 64;
   // dynamic LDS above the 64 KiB default needs opting in
@@ -411,9 +777,9 @@ static KernelInfo make_kernel_info() {
   return info;
 }
 
-template <int DL, int NW>
+template <int DL, int NW, int HPW = 16>
 static int kernel_info(KernelInfo** out) {
-  static KernelInfo info = make_kernel_info<DL, NW>();   // initialised once, thread-safe
+  static KernelInfo info = make_kernel_info<DL, NW, HPW>();   // initialised once, thread-safe
   if (!info.ready) return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", info.smem);
   *out = &info;
   return TPLA_OK;
@@ -424,8 +790,22 @@ static int kernel_info_dl(int H, KernelInfo** out) {
   switch (H) {
     case 16: return kernel_info<DL, 1>(out);
     case 32: return kernel_info<DL, 2>(out);
+    // -DTPLA_H32 routes 64 and 128 heads to the 32-heads-per-wave instances.  Measured against the
+    // 16-heads-per-wave ones (32 x 32768 tokens, both slices): 269 against 223 us at 64 heads, 448 against
+    // 369 us at 128 -- LDS instructions per tile are halved, but a wave's own VALU instructions do not
+    // run under its MFMAs (per-phase clocks: score MFMAs alone 631 cycles per tile, softmax alone 645,
+    // issued interleaved 1159), so one wave per SIMD loses what two waves overlap; not the default.
+#ifdef TPLA_H32
+    case 64:
+      if constexpr (DL <= 256) return kernel_info<DL, 2, 32>(out);
+      return kernel_info<DL, 4>(out);
+    case 128:
+      if constexpr (DL <= 256) return kernel_info<DL, 4, 32>(out);
+      return kernel_info<DL, 8>(out);
+#else
     case 64: return kernel_info<DL, 4>(out);
     case 128: return kernel_info<DL, 8>(out);
+#endif
   }
   return fail(TPLA_ERR_UNSUPPORTED, "H=%d", H);
 }
@@ -456,7 +836,12 @@ int decode_mfma_blocks_per_cu(const tpla_shape_t& sh) {
 // alike.  Weights in units of 1/128 of the average range.
 void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]) {
   for (int r = 0; r < 4; ++r) wt[r] = 128;
-  const int waves_per_simd_launched = (sh.H / 16) * per_cu / 4;
+#ifdef TPLA_H32
+  const int heads_per_wave = (sh.H >= 64 && sh.d_c / sh.g <= 256) ? 32 : 16;
+#else
+  const int heads_per_wave = 16;
+#endif
+  const int waves_per_simd_launched = (sh.H / heads_per_wave) * per_cu / 4;
   if (waves_per_simd_launched < 2) return;
   if (per_cu == 3) {
     wt[0] = 140;
@@ -464,6 +849,15 @@ void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]
     wt[2] = 115;
   }
 }
+
+#ifdef TPLA_WG_TIMELINE
+// Device addresses of the two timeline arrays ([4096][4] uint64 ticks of 10 ns, [4096][2] uint32).
+extern "C" __attribute__((visibility("default"))) int tpla_debug_wg_timeline(void** times, void** where) {
+  if (hipGetSymbolAddress(times, HIP_SYMBOL(g_wg_times)) != hipSuccess) return TPLA_ERR_HIP;
+  if (hipGetSymbolAddress(where, HIP_SYMBOL(g_wg_where)) != hipSuccess) return TPLA_ERR_HIP;
+  return TPLA_OK;
+}
+#endif
 
 int launch_decode_mfma(const DecodeArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   KernelInfo* k = nullptr;
