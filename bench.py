@@ -338,8 +338,8 @@ def wg_timeline(args):
         print("bench.py --wg-timeline: build the library with TPLA_EXTRA_HIPCC_FLAGS=-DTPLA_WG_TIMELINE first", file=sys.stderr)
         sys.exit(1)
     hip = ctypes.CDLL("libamdhip64.so")
-    p_t, p_w = ctypes.c_void_p(), ctypes.c_void_p()
-    assert lib.tpla_debug_wg_timeline(ctypes.byref(p_t), ctypes.byref(p_w)) == 0
+    p_t, p_w, p_p = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+    assert lib.tpla_debug_wg_timeline(ctypes.byref(p_t), ctypes.byref(p_w), ctypes.byref(p_p)) == 0
     w = wl.CONFIGS[args.workload]
     if args.set:
         w = wl.scaled(w, **{k: int(v) for k, v in (kv.split("=") for kv in args.set)})
@@ -379,6 +379,18 @@ def wg_timeline(args):
     except Exception:
         cus = 256
     rounds = np.arange(n_wg) // cus
+    # phase clocks (only the 32-heads-per-wave instances record them), from the last launch
+    ph = np.zeros(4096 * 5, dtype=np.uint64)
+    assert hip.hipMemcpy(ph.ctypes.data_as(ctypes.c_void_p), p_p, ph.nbytes, 2) == 0
+    ph = ph.reshape(-1, 5)[:n_wg].astype(np.float64)
+    phase = None
+    if ph[:, 4].sum() > 0:
+        n_items = max(1.0, float(np.count_nonzero(ph[:, 4])))
+        phase = {"what": "shader clocks per 32-token tile of wave 0, mean over the workgroups of the last launch",
+                 "plain_score_product_of_an_items_first_tile": float(ph[:, 0].sum() / n_items),
+                 "wait_barrier_and_tile_requests": float(ph[:, 1].sum() / ph[:, 4].sum()),
+                 "score_mfmas_with_previous_tiles_softmax_between_them": float(ph[:, 2].sum() / ph[:, 4].sum()),
+                 "output_mfmas": float(ph[:, 3].sum() / ph[:, 4].sum())}
     print(json.dumps({
         "workload": w.name, "workgroups": int(n_wg), "launches": 12 * 20, "kernel_us_mean_with_timeline_code": float(np.mean(kern)),
         "percentiles": "min, 10 %, median, 90 %, max over workgroups and 12 sampled launches, microseconds",
@@ -388,6 +400,7 @@ def wg_timeline(args):
         "same_workgroups_slow_every_launch_correlation": round(float((cc.sum() - len(cc)) / (len(cc) * (len(cc) - 1))), 3),
         "relative_duration_by_placement_round": {str(r): round(float(rel[rounds == r].mean()), 3) for r in sorted(set(rounds.tolist()))},
         "relative_duration_by_xcc": {str(x): round(float(rel[xcc == x].mean()), 3) for x in sorted(set(xcc.tolist()))},
+        "phase_clocks_32_heads_per_wave": phase,
     }))
 
 

@@ -9,7 +9,9 @@ import ctypes
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "lib", "libtpla.so")
+# TPLA_LIBRARY selects another build of the same library (e.g. a measurement build made with
+# TPLA_LIB_NAME=... python -m paper_2508_15881_amd.build); there is still no fallback.
+_LIB_PATH = os.environ.get("TPLA_LIBRARY") or os.path.join(_PKG, "lib", "libtpla.so")
 
 TPLA_F32, TPLA_BF16 = 0, 1
 TPLA_U_IDENTITY, TPLA_U_HADAMARD, TPLA_U_DENSE = 0, 1, 2

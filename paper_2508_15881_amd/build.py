@@ -15,7 +15,12 @@ CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB_DIR = os.path.join(PKG, "lib")
-LIB_PATH = os.path.join(LIB_DIR, "libtpla.so")
+# TPLA_LIB_NAME: file name of the library to write (measurement builds with extra flags get their own name
+# and object folder, so the default library stays as it is)
+LIB_NAME = os.environ.get("TPLA_LIB_NAME", "libtpla.so")
+LIB_PATH = os.path.join(LIB_DIR, LIB_NAME)
+if LIB_NAME != "libtpla.so":
+    OBJ_DIR = os.path.join(OBJ_DIR, LIB_NAME.replace(".so", ""))
 
 SOURCES = ["api.hip", "decode_mfma.hip", "decode_generic.hip", "transform.hip", "transform_mfma.hip", "absorb_combine.hip",
            "absorb_combine_mfma.hip", "pca.hip", "prefill_mfma.hip"]

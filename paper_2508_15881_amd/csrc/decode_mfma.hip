@@ -35,11 +35,17 @@ constexpr int PAGE_TOKENS = 64;
 #ifdef TPLA_WG_TIMELINE
 __device__ unsigned long long g_wg_times[4096 * 4];
 __device__ unsigned g_wg_where[4096 * 2];
+// per workgroup (wave 0) of the 32-heads-per-wave instances: shader clocks spent in the plain score product of
+// an item's first tile, in waiting for / requesting tiles, in the score MFMAs with the previous tile's softmax
+// issued between them, in the output MFMAs; and the number of tiles
+__device__ unsigned long long g_wg_phase[4096 * 5];
+#define TPLA_PH_CLK(x) do { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); x = clock64(); } while (0)
 #define TPLA_TL_MARK(k) do { if (threadIdx.x == 0 && blockIdx.x < 4096) g_wg_times[blockIdx.x * 4 + (k)] = wall_clock64(); } while (0)
 #define TPLA_TL_MARK_ONCE(k) do { if (threadIdx.x == 0 && blockIdx.x < 4096 && g_wg_times[blockIdx.x * 4 + (k)] == 0) g_wg_times[blockIdx.x * 4 + (k)] = wall_clock64(); } while (0)
 #else
 #define TPLA_TL_MARK(k) do { } while (0)
 #define TPLA_TL_MARK_ONCE(k) do { } while (0)
+#define TPLA_PH_CLK(x) do { } while (0)
 #endif
 
 // One work item: pages [p0, p1) of sequence b of slice `shard` (L tokens in
@@ -500,12 +506,17 @@ __device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, 
   __builtin_amdgcn_s_barrier();
   clear_tail(0);
   float s_cur[16];
+  [[maybe_unused]] unsigned long long ph[5] = {0, 0, 0, 0, 0}, c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+  TPLA_TL_MARK_ONCE(1);
   {
+    TPLA_PH_CLK(c0);
     zero_scores();
     score_reads_begin(lds_base);
     score_mfmas(lds_base, C0{}, C2{}, nothing);
 #pragma unroll
     for (int i = 0; i < 16; ++i) s_cur[i] = sA[i] + sB[i];
+    TPLA_PH_CLK(c1);
+    ph[0] += c1 - c0;
   }
 
   // The accumulators sit in the accumulation registers, which only MFMAs write: rescaling them means
@@ -519,6 +530,7 @@ __device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, 
     bool rescale = false;
     for (; t < ntiles; ++t) {
       const bool has_next = t + 1 < ntiles;
+      TPLA_PH_CLK(c0);
       if (has_next && !resumed) {
         // tile t + 1 has landed once only the tiles requested after it are outstanding
         if (FL >= 2 && t + 2 < ntiles)
@@ -530,6 +542,7 @@ __device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, 
         clear_tail(t + 1);
       }
       resumed = false;
+      TPLA_PH_CLK(c1);
       const unsigned tile = lds_base + (unsigned)((t % NSTAGE) * TILE_BYTES);
       // the last tile has no successor: its own keys are multiplied once more and the result dropped
       const unsigned tile_next = lds_base + (unsigned)(((has_next ? t + 1 : t) % NSTAGE) * TILE_BYTES);
@@ -575,6 +588,7 @@ __device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, 
         }
       });
       l_run += psum;
+      TPLA_PH_CLK(c2);
 
       // ---- output: O^T += V^T P^T of tile t, a ring of 4 V fragments; in its shadow the new scores
       //      leave the accumulation registers ----
@@ -607,6 +621,8 @@ __device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, 
           __builtin_amdgcn_sched_barrier(0);
         });
       });
+      TPLA_PH_CLK(c3);
+      ph[1] += c1 - c0; ph[2] += c2 - c1; ph[3] += c3 - c2; ph[4] += 1;
     }
     if (rescale) {
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_pending);
@@ -617,6 +633,11 @@ __device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, 
     }
   }
 
+#ifdef TPLA_WG_TIMELINE
+  if (tid == 0 && blockIdx.x < 4096)
+    for (int k = 0; k < 5; ++k) g_wg_phase[blockIdx.x * 5 + k] += ph[k];
+#endif
+  TPLA_TL_MARK(2);
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const size_t item = slot * a.H + head;
   float* pacc = a.part_acc + item * DL + 4 * hi;
@@ -679,6 +700,7 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW, HPW>())) deco
   if (threadIdx.x == 0 && blockIdx.x < 4096) {
     g_wg_times[blockIdx.x * 4] = wall_clock64();
     g_wg_times[blockIdx.x * 4 + 1] = 0;
+    for (int k = 0; k < 5; ++k) g_wg_phase[blockIdx.x * 5 + k] = 0;
     g_wg_where[blockIdx.x * 2] = __builtin_amdgcn_s_getreg((31 << 11) | 20);      // XCC_ID
     g_wg_where[blockIdx.x * 2 + 1] = __builtin_amdgcn_s_getreg((31 << 11) | 4);   // HW_ID
   }
@@ -851,10 +873,11 @@ void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]
 }
 
 #ifdef TPLA_WG_TIMELINE
-// Device addresses of the two timeline arrays ([4096][4] uint64 ticks of 10 ns, [4096][2] uint32).
-extern "C" __attribute__((visibility("default"))) int tpla_debug_wg_timeline(void** times, void** where) {
+// Device addresses of the timeline arrays ([4096][4] uint64 ticks of 10 ns, [4096][2] uint32, [4096][5] uint64).
+extern "C" __attribute__((visibility("default"))) int tpla_debug_wg_timeline(void** times, void** where, void** phase) {
   if (hipGetSymbolAddress(times, HIP_SYMBOL(g_wg_times)) != hipSuccess) return TPLA_ERR_HIP;
   if (hipGetSymbolAddress(where, HIP_SYMBOL(g_wg_where)) != hipSuccess) return TPLA_ERR_HIP;
+  if (hipGetSymbolAddress(phase, HIP_SYMBOL(g_wg_phase)) != hipSuccess) return TPLA_ERR_HIP;
   return TPLA_OK;
 }
 #endif
