@@ -6,7 +6,7 @@
 // through LDS and comes back through the transposing read, which hands lane j
 // the 4 rows of column j.  The float o_lat is split into bf16 hi + lo parts
 // (two MFMAs) so the combine keeps float accuracy.
-#include "tpla_internal.h"
+#include "lds_tile.h"
 
 namespace tpla {
 
@@ -503,110 +503,166 @@ int launch_merge_combine_mfma(const DecodeArgs& a, const tpla_shape_t& sh, const
 // Output projection  out[b, n] = sum_k x[b, k] W[k, n]  (x = the combined
 // per-head outputs flattened to [B, H d_v], W = W_O [H d_v, D]; Sec. 3.3: the
 // value up-projection is not merged into W_O, so this runs after the combine).
-// A weight-streaming skinny GEMM: grid (D / 64, KSPLIT); a workgroup owns 64
-// output columns and one contiguous k-range, walks it in chunks of OP_ROWS
-// rows double-buffered in LDS (next chunk in registers while the current one
-// feeds the MFMAs), and writes a float partial tile; a second kernel sums the
-// KSPLIT partials in order.  Inside a chunk wave w owns rows 64w..64w+63.
+// A weight-streaming skinny GEMM: grid (D / 128, KSPLIT); a workgroup owns 128
+// output columns and one contiguous k-range and walks it in chunks of OP_ROWS
+// rows.  A chunk = the weight rows (16 KB) and the matching columns of 32 rows
+// of x (8 KB, float), both brought in by direct-to-LDS loads into a ring of
+// OP_NST buffers, so that three chunks per workgroup are in flight whatever the
+// waves are doing and every vector-memory operation of the loop is one of these
+// loads (the wait counts below rely on that).  Wave w owns columns 32w..32w+31
+// over all rows of a chunk: no sum across waves.  x is split into bf16 hi + lo
+// (two MFMAs) so the product keeps float accuracy.  The float partial tiles of
+// the KSPLIT ranges are summed in order by a second kernel.
 constexpr int OP_COLS = 128;
-constexpr int OP_ROWS = 128;
+constexpr int OP_ROWS = 64;
+constexpr int OP_NST = 4;
+static_assert(OP_NST >= 3 && OP_NST <= 6, "the wait counts cover one to four younger chunks");
+constexpr int OP_W_BYTES = OP_ROWS * OP_COLS * 2;     // 16 rows of 16 pieces per KB: 16 instructions
+constexpr int OP_X_BYTES = 32 * OP_ROWS * 4;          // 32 rows of x, 16 pieces each: 8 instructions
+constexpr int OP_STAGE = OP_W_BYTES + OP_X_BYTES;
+constexpr int OP_LOADS = (OP_W_BYTES + OP_X_BYTES) / 1024 / 4;   // per wave and chunk
+
+template <int OFF>
+__device__ __forceinline__ void lds_read_f4(f32x4& dst, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+
 __global__ void __launch_bounds__(256) output_projection_mfma_kernel(const float* __restrict__ x,
-                                                                     const bf16_t* __restrict__ W,
-                                                                     float* __restrict__ part, int B, int K,
-                                                                     int N, int k_per_split) {
-  extern __shared__ u32x4 slab4[];                 // 2 buffers of OP_ROWS x OP_COLS bf16
-  constexpr int PPR = OP_COLS / 8;                 // 16 pieces per row (256 bytes: all banks)
-  constexpr int PIECES = OP_ROWS * PPR;            // 2048 per chunk
-  constexpr int PT = PIECES / 256;                 // 8 per thread
-  constexpr int WK = OP_ROWS / 4;                  // 32 rows = one k-step per wave and chunk
-  constexpr int NCB = OP_COLS / 16;                // 8 column blocks, all owned by every wave
-  static_assert(WK == 32, "one MFMA k-step per wave and chunk");
+                                                                        const bf16_t* __restrict__ W,
+                                                                        float* __restrict__ part, int B, int K,
+                                                                        int N, int k_per_split) {
+  extern __shared__ u32x4 ring4[];                 // OP_NST stages of [W chunk | x chunk]
+  char* ring = reinterpret_cast<char*>(ring4);
+  const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)ring4);
   const int c0 = blockIdx.x * OP_COLS, kz = blockIdx.y;
   const int k_begin = kz * k_per_split;
   const int n_chunks = k_per_split / OP_ROWS;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j16 = lane & 15, q4 = lane >> 4;
+  const int tid = threadIdx.x, lane = tid & 63, j16 = lane & 15, q4 = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_mb = (B + 15) / 16;
+
+  // Direct-to-LDS bookkeeping.  Instruction k of a region fills its pieces [64k, 64k + 64): row
+  // 4k + q4, position j16.  This wave issues k = wave + 4j, i.e. rows 4 wave + q4 + 16 j; the
+  // piece that belongs at position j16 of such a row is j16 ^ swizzle(row), the same for every j.
+  const int wr = 4 * wave + q4;
+  const char* w_src = reinterpret_cast<const char*>(W + (size_t)(k_begin + wr) * N + c0 + 8 * (j16 ^ wswz(wr)));
+  const size_t w_rows16 = (size_t)16 * N * 2, w_chunk = (size_t)OP_ROWS * N * 2;
+
+  // LDS read offsets.  Weights: rows 32 ks + 8 q4 + (j16 >> 2) (+4), piece pair of column block
+  // 2 wave + cb.  x: row 16 m + j16, pieces 8 ks + 2 q4 + {0, 1}, stored at piece ^ (row & 15).
+  const int r0 = 8 * q4 + (j16 >> 2);
+  unsigned b_off[2], a_off[2][2];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+    b_off[cb] = (unsigned)((r0 * 16 + ((2 * (2 * wave + cb) + ((j16 & 3) >> 1)) ^ wswz(r0))) * 16 + (j16 & 1) * 8);
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      a_off[ks][h] = (unsigned)(OP_W_BYTES + (j16 * 16 + ((8 * ks + 2 * q4 + h) ^ j16)) * 16);
+
   for (int mb0 = 0; mb0 < n_mb; mb0 += 2) {
-    f32x4 acc[2][NCB];
+    const char* x_src[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int bl = wr + 16 * j;                  // row of the x chunk, 0..31
+      const int b = min(16 * mb0 + bl, B - 1);     // rows past the batch repeat the last one, never stored
+      x_src[j] = reinterpret_cast<const char*>(x + (size_t)b * K + k_begin + 4 * (j16 ^ (bl & 15)));
+    }
+    auto issue = [&](int t) {
+      char* dst = ring + (t % OP_NST) * OP_STAGE + wave * 1024;
+      const char* ws = w_src + (size_t)t * w_chunk;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ws + j * w_rows16),
+                                         (__attribute__((address_space(3))) void*)(dst + j * 4096), 16, 0,
+                                         2 /* streaming: the weights are read once */);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(x_src[j] + (size_t)t * (OP_ROWS * 4)),
+            (__attribute__((address_space(3))) void*)(dst + OP_W_BYTES + j * 4096), 16, 0, 0);
+    };
+    static_assert(OP_LOADS == 6, "four weight and two x instructions per wave and chunk");
+
+    f32x4 acc[2][2];
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) acc[m][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    u32x4 wreg[PT];
-    float4 xa[2][2];
-    auto fetch = [&](int t) {
-      const bf16_t* Wc = W + (size_t)(k_begin + t * OP_ROWS) * N + c0;
+      for (int cb = 0; cb < 2; ++cb) acc[m][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // the previous pass is done with LDS and its stores have left (they would share the counter)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
 #pragma unroll
-      for (int j = 0; j < PT; ++j) {
-        const int p = tid + j * 256, r = p / PPR, pc = p % PPR;
-        wreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Wc + (size_t)r * N + 8 * pc));
-      }
-#pragma unroll
-      for (int m = 0; m < 2; ++m) {
-        const int b = min(16 * (mb0 + m) + j16, B - 1);
-        const float* src = x + (size_t)b * K + k_begin + t * OP_ROWS + WK * wave + 8 * q4;
-        xa[m][0] = *reinterpret_cast<const float4*>(src);
-        xa[m][1] = *reinterpret_cast<const float4*>(src + 4);
-      }
-    };
-    auto stage = [&](int buf) {
-#pragma unroll
-      for (int j = 0; j < PT; ++j) {
-        const int p = tid + j * 256, r = p / PPR, pc = p % PPR;
-        slab4[buf * PIECES + r * PPR + (pc ^ wswz(r))] = wreg[j];
-      }
-    };
-    __syncthreads();                 // the previous pass is done with LDS
-    fetch(0);
+    for (int t = 0; t < OP_NST - 1; ++t)
+      if (t < n_chunks) issue(t);
     for (int t = 0; t < n_chunks; ++t) {
-      stage(t & 1);
-      bf16x8 ah[2], al[2];
-#pragma unroll
-      for (int m = 0; m < 2; ++m) {
-        const float xs[8] = {xa[m][0].x, xa[m][0].y, xa[m][0].z, xa[m][0].w,
-                             xa[m][1].x, xa[m][1].y, xa[m][1].z, xa[m][1].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const bf16_t hi16 = (bf16_t)xs[e];
-          ah[m][e] = hi16;
-          al[m][e] = (bf16_t)(xs[e] - (float)hi16);
-        }
+      // chunk t has landed once only the loads of the chunks requested after it are outstanding
+      switch (min(n_chunks - 1 - t, OP_NST - 2)) {
+        case 0: __builtin_amdgcn_s_waitcnt(vmcnt_imm(0)); break;
+        case 1: __builtin_amdgcn_s_waitcnt(vmcnt_imm(OP_LOADS)); break;
+        case 2: __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * OP_LOADS)); break;
+        case 3: __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * OP_LOADS)); break;
+        default: __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * OP_LOADS)); break;
       }
-      __syncthreads();               // chunk t visible; nobody still reads the buffer chunk t+1 will use
-      if (t + 1 < n_chunks) fetch(t + 1);
-      const char* slab = reinterpret_cast<const char*>(slab4 + (t & 1) * PIECES);
+      __builtin_amdgcn_s_barrier();          // chunk t visible to all waves, chunk t-1 no longer read
+      if (t + OP_NST - 1 < n_chunks) issue(t + OP_NST - 1);
+      const unsigned st = lds_base + (unsigned)((t % OP_NST) * OP_STAGE);
+      f32x4 xf[2][2][2];                     // [ks][m][half]
+      u32x2 wlo[2][2], whi[2][2];            // [ks][cb]
+      static_for<2>([&](auto kc) {
+        constexpr int ks = decltype(kc)::value;
+        lds_read_f4<0>(xf[ks][0][0], st + a_off[ks][0]);
+        lds_read_f4<0>(xf[ks][0][1], st + a_off[ks][1]);
+        lds_read_f4<4096>(xf[ks][1][0], st + a_off[ks][0]);
+        lds_read_f4<4096>(xf[ks][1][1], st + a_off[ks][1]);
+        lds_read_tr_b64<ks * 8192>(wlo[ks][0], st + b_off[0]);
+        lds_read_tr_b64<ks * 8192 + 1024>(whi[ks][0], st + b_off[0]);
+        lds_read_tr_b64<ks * 8192>(wlo[ks][1], st + b_off[1]);
+        lds_read_tr_b64<ks * 8192 + 1024>(whi[ks][1], st + b_off[1]);
+      });
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(xf[0][0][0]), "+v"(xf[0][0][1]), "+v"(xf[0][1][0]), "+v"(xf[0][1][1]), "+v"(xf[1][0][0]),
+                     "+v"(xf[1][0][1]), "+v"(xf[1][1][0]), "+v"(xf[1][1][1]), "+v"(wlo[0][0]), "+v"(whi[0][0]),
+                     "+v"(wlo[0][1]), "+v"(whi[0][1]), "+v"(wlo[1][0]), "+v"(whi[1][0]), "+v"(wlo[1][1]),
+                     "+v"(whi[1][1])
+                   :
+                   : "memory");
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        const bf16x8 bf = read_b_frag<PPR>(slab, WK * wave, cb, j16, q4);
+      for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 ah[2], al[2];
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-          acc[m][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[m], bf, acc[m][cb], 0, 0, 0);
-          acc[m][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[m], bf, acc[m][cb], 0, 0, 0);
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float v = xf[ks][m][e >> 2][e & 3];
+            const bf16_t hi16 = (bf16_t)v;
+            ah[m][e] = hi16;
+            al[m][e] = (bf16_t)(v - (float)hi16);
+          }
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          const u32x4 w4 = {wlo[ks][cb][0], wlo[ks][cb][1], whi[ks][cb][0], whi[ks][cb][1]};
+          const bf16x8 bf = __builtin_bit_cast(bf16x8, w4);
+#pragma unroll
+          for (int m = 0; m < 2; ++m) {
+            acc[m][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[m], bf, acc[m][cb], 0, 0, 0);
+            acc[m][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[m], bf, acc[m][cb], 0, 0, 0);
+          }
         }
       }
     }
-    // sum the four waves' tiles through LDS; wave w finishes column blocks 2w, 2w+1
-    __syncthreads();
-    f32x4* red = reinterpret_cast<f32x4*>(slab4);    // [wave][m][cb][lane]
+    // acc[m][cb][i]: row 16 (mb0 + m) + 4 q4 + i, column c0 + 32 wave + 16 cb + j16
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) red[((wave * 2 + m) * NCB + cb) * 64 + lane] = acc[m][cb];
-    __syncthreads();
-#pragma unroll
-    for (int m = 0; m < 2; ++m)
-#pragma unroll
-      for (int c2 = 0; c2 < 2; ++c2) {
-        const int cb = 2 * wave + c2;
-        f32x4 tsum = red[((0 * 2 + m) * NCB + cb) * 64 + lane];
-#pragma unroll
-        for (int w2 = 1; w2 < 4; ++w2) tsum += red[((w2 * 2 + m) * NCB + cb) * 64 + lane];
+      for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int bb = 16 * (mb0 + m) + 4 * q4 + i;
-          if (bb < B) part[((size_t)kz * B + bb) * N + c0 + 16 * cb + j16] = tsum[i];
+          if (bb < B) part[((size_t)kz * B + bb) * N + c0 + 32 * wave + 16 * cb + j16] = acc[m][cb][i];
         }
-      }
   }
 }
 
@@ -638,7 +694,9 @@ int output_projection_ksplit(const tpla_shape_t& sh, int D) {
   const long long K = (long long)sh.H * sh.d_v;
   if (sh.dtype != TPLA_BF16 || D % OP_COLS != 0 || K % OP_ROWS != 0 || K > 2147483647LL) return 0;
   const int slabs = D / OP_COLS;
-  int ks = (2 * device_cu_count() + slabs - 1) / slabs;      // about two workgroups per compute unit
+  // about one workgroup per compute unit (its ring takes 96 KB of LDS): for D = 7168, K = 8192 at B = 32 that is
+  // 224 workgroups of 32 chunks, 27 us for both kernels; 448 of 16 chunks on a ring of 3 took 29.5 us
+  int ks = (device_cu_count() + slabs - 1) / slabs;
   const int chunks = (int)(K / OP_ROWS);
   if (ks > chunks) ks = chunks;
   if (ks < 1) ks = 1;
@@ -662,7 +720,14 @@ static int launch_output_projection_to(const tpla_shape_t& sh, const float* x, c
                          static_cast<const bf16_t*>(W_O), out, K, D);
     return check_launch("output_projection_simple_kernel");
   }
-  const size_t smem = 2u * OP_ROWS * OP_COLS * 2;
+  constexpr size_t smem = (size_t)OP_NST * OP_STAGE;
+  // dynamic LDS above the 64 KiB default needs opting in, once
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(output_projection_mfma_kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(TPLA_ERR_HIP, "cannot raise the dynamic LDS limit to %zu", smem);
+  }
   const bool direct = ks == 1 && direct_ok;
   float* dst = direct ? reinterpret_cast<float*>(out) : part;
   hipLaunchKernelGGL(output_projection_mfma_kernel, dim3((unsigned)(D / OP_COLS), (unsigned)ks), dim3(256), smem,

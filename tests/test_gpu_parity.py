@@ -580,7 +580,10 @@ def test_absorb_and_combine(dtype, Bn, H, g):
 
 
 @pytest.mark.parametrize("dtype,Bn,H,d_v,D", [("bf16", 32, 64, 128, 7168), ("bf16", 5, 32, 128, 1024), ("bf16", 40, 16, 64, 320),
-                                              ("f32", 3, 4, 32, 96), ("bf16", 2, 5, 16, 100)])
+                                              ("f32", 3, 4, 32, 96), ("bf16", 2, 5, 16, 100),
+                                              # matrix-core path: three passes over the batch; 32, 3 and 6 chunks per k-range
+                                              ("bf16", 70, 64, 128, 7168), ("bf16", 33, 24, 128, 2048), ("bf16", 8, 24, 128, 4096),
+                                              ("bf16", 4, 2, 64, 4096)])     # one chunk per k-range
 def test_output_projection(dtype, Bn, H, d_v, D):
     _say(f"output_projection {dtype} B={Bn} H={H} d_v={d_v} D={D}")
     rng = np.random.default_rng(71)
