@@ -98,6 +98,11 @@ def cpu_baseline(w, model, budget_s=12.0):
                       % (n_seq, w.B, done_tokens, t_total)}
 
 
+def _under_profiler():
+    """True when rocprofv3 (or another tool that preloads a GPU library into every child) runs this process."""
+    return "rocprof" in os.environ.get("LD_PRELOAD", "").lower() or any(k.startswith("ROCPROF") for k in os.environ)
+
+
 def _shader_clock_mhz():
     """Current shader clock from rocm-smi (None if the tool is missing or says nothing)."""
     import subprocess
@@ -609,7 +614,10 @@ def main():
 
     # shader clock and socket power under load: the decode step runs at the chip's power limit, the pure reader does not
     power_state = None
-    if not args.skip_extras:
+    if not args.skip_extras and _under_profiler():
+        power_state = {"skipped": "a profiler is attached to this process: the two tools are scripts whose interpreter "
+                                  "would be started from a process the profiler's library has already put on the GPU"}
+    elif not args.skip_extras:
         power_state = {
             "what": "[shader clock MHz (rocm-smi), socket power W (amd-smi)] sampled while the GPU runs the named work back to back",
             "decode_steps": _clock_while(lambda: p.run_step(pools)),

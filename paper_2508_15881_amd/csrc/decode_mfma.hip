@@ -327,17 +327,6 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
 // step), so elements 8 s .. 8 s + 7 of the exponentiated scores are the B
 // operand of step s as they stand, and V^T is fetched with two transposing
 // reads per fragment (tokens +0..3 and +8..11 of the lane's half).
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-// Tile swizzle of the 32-head kernel: piece c of token t sits at c ^ swz32(t) within its group of 8.
-// Its two read patterns differ from the 16-head kernel's: the score operand takes 32 consecutive
-// tokens at one piece (two pieces per instruction), the transposing read 4 consecutive tokens x 4
-// consecutive pieces per 32 lanes.  With t & 7 tokens t and t + 8 collide in the first (5.3 against 3.0
-// cycles per instruction in a read-only loop) and tokens t and t + 2 in the second (3.0 against 1.6);
-// of the 3-bit XOR-linear maps of the token index, those with output bit 2 = token bit 1 and the other
-// two bits from token bits 2 and 3 run both at full rate.
-__device__ __forceinline__ int swz32(int tok) { return ((tok >> 2) & 3) | ((tok & 2) << 1); }
-
 template <int DL, int DR, int NW, int TOK, int NSTAGE>
 __device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, int shard, int b, int L,
                                               int p0, int p1, size_t slot) {

@@ -60,4 +60,14 @@ __device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
 // fetches from.
 __device__ __forceinline__ int swz(int tok) { return tok & 7; }
 
+// Tile swizzle of the kernels that feed 32x32x16 MFMAs (32 heads or 32 queries per wave): piece c of
+// token t sits at c ^ swz32(t) within its group of 8.  Their two read patterns differ from the
+// 16-wide kernels': the score operand takes 32 consecutive tokens at one piece (two pieces per
+// instruction), the transposing read 4 consecutive tokens x 4 consecutive pieces per 32 lanes.  With
+// t & 7 tokens t and t + 8 collide in the first (5.3 against 3.0 cycles per instruction in a read-only
+// loop) and tokens t and t + 2 in the second (3.0 against 1.6); of the 3-bit XOR-linear maps of the
+// token index, those with output bit 2 = token bit 1 and the other two bits from token bits 2 and 3
+// run both at full rate.
+__device__ __forceinline__ int swz32(int tok) { return ((tok >> 2) & 3) | ((tok & 2) << 1); }
+
 }  // namespace tpla

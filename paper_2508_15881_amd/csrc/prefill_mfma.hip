@@ -409,6 +409,221 @@ __global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma_kernel(P
   }
 }
 
+// The same kernel with 32 queries per wave as one block on 32x32x16 MFMAs: half as many MFMA issues
+// for the same matrix-core cycles, one cross-lane step instead of two in the row maximum, and the tile
+// swizzle of the 32-wide fragments (swz32).  Sᵀ[key, query] lands with lane = query (lane & 31) and
+// the two half-waves holding keys {0-3, 8-11, 16-19, 24-27} and {4-7, 12-15, 20-23, 28-31}: exactly
+// the B operand of Oᵀ += Vᵀ Pᵀ when Vᵀ is fetched with its keys in that order.
+__global__ void __launch_bounds__(PF_NW * 64, 2) prefill_attention_mfma32_kernel(PrefillArgs a) {
+  extern __shared__ u32x4 smem[];
+  constexpr int ROWB = PF_RC * 16;
+  static_assert(PF_TILE_BYTES % 4096 == 0, "tile bases must leave address bits 5..11 to the lane offsets");
+  static_assert(PF_QT == PF_NW * 32 && PF_TOK == 32, "32 queries per wave, 32 keys per tile");
+  const int seq = blockIdx.y;
+  const int per_group = a.n_qt * a.head_group;
+  const int hg = blockIdx.x / per_group, rem = blockIdx.x - hg * per_group;
+  const int h = hg * a.head_group + rem % a.head_group;
+  const int qt = a.n_qt - 1 - rem / a.head_group;          // long key ranges first
+  const int t0 = min(max(a.cu[seq], 0), a.T), L = min(max(a.cu[seq + 1], t0), a.T) - t0;
+  if (qt * PF_QT >= L) return;
+  const int q0 = qt * PF_QT;
+  const int kend = min(L, q0 + PF_QT);
+  const int ntiles = (kend + PF_TOK - 1) / PF_TOK;
+
+  const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)smem);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n32 = lane & 31, hi = lane >> 5;
+
+  // ---- direct-to-LDS bookkeeping (as in the 16-wide kernel, with the other swizzle) ----
+  int ld_tok[PF_CPT];
+  const char* ld_cur[PF_CPT];
+  unsigned ld_step[PF_CPT];
+  const char* kv_base = reinterpret_cast<const char*>(a.kv) + ((size_t)t0 * a.H + h) * 512;
+  const char* kpe_base = reinterpret_cast<const char*>(a.k_pe) + (size_t)t0 * 128;
+  const unsigned kv_pitch = (unsigned)a.H * 512u;
+#pragma unroll
+  for (int j = 0; j < PF_CPT; ++j) {
+    const int x = (wave + j * PF_NW) * 64 + lane;
+    const int tok = x / PF_RC, cs = x % PF_RC;
+    const int cg = cs ^ swz32(tok);
+    ld_tok[j] = tok;
+    const bool from_kv = cg < 32;
+    ld_step[j] = from_kv ? kv_pitch : 128u;
+    ld_cur[j] = (from_kv ? kv_base + cg * 16 : kpe_base + (cg - 32) * 16) + (size_t)tok * ld_step[j];
+  }
+  auto issue = [&](int t) {
+    char* dst = reinterpret_cast<char*>(smem) + (t % PF_NSTAGE) * PF_TILE_BYTES;
+    if ((t + 1) * PF_TOK <= L) {
+#pragma unroll
+      for (int j = 0; j < PF_CPT; ++j) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ld_cur[j],
+                                         (__attribute__((address_space(3))) void*)(dst + (wave + j * PF_NW) * 1024),
+                                         16, 0, 0);
+        ld_cur[j] += (size_t)PF_TOK * ld_step[j];
+      }
+    } else {
+      // last tile of the sequence: keys past its end repeat the last key (finite values, masked below)
+#pragma unroll
+      for (int j = 0; j < PF_CPT; ++j) {
+        const int over = max(0, t * PF_TOK + ld_tok[j] - (L - 1));
+        const char* src = ld_cur[j] - (size_t)over * ld_step[j];
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(dst + (wave + j * PF_NW) * 1024),
+                                         16, 0, 0);
+      }
+    }
+  };
+
+  // ---- per-lane LDS byte offsets ----
+  // score product: key n32, piece 16 + 2 ks + hi = 8 (2 + ks / 4) + (2 (ks % 4) | hi); the swizzle only
+  // touches the low three bits of the piece index and (2 j | hi) ^ x = (hi ^ x) ^ 2 j, so the offsets
+  // of ks % 4 = 1, 2, 3 are that of 0 with address bits 5 and 6 flipped
+  const unsigned k_off = (unsigned)(n32 * ROWB + ((hi ^ swz32(n32)) * 16));
+  // output product: 16-lane group (hi, dim half); lane j of it points at key 4 hi + j / 4 of the k-step
+  // and dims 32 d + 16 half + 4 (j % 4) .. +3, i.e. piece 4 d + 2 half + (j % 4) / 2
+  const int j16 = lane & 15, half = (lane >> 4) & 1;
+  const int v_tok = 4 * hi + (j16 >> 2);
+  const int pl = 2 * half + ((j16 & 3) >> 1);
+  const unsigned v_off = (unsigned)(v_tok * ROWB + ((pl ^ swz32(v_tok)) * 16) + (j16 & 1) * 8);
+
+  issue(0);
+  if (ntiles > 1) issue(1);
+
+  // ---- this wave's 32 queries as B operands: lane holds query qbase + n32, k = 16 ks + 8 hi .. +7 ----
+  constexpr int KS = 12;                   // 16-wide k-steps of the 192-wide score product
+  constexpr int DB = 4;                    // 32-wide blocks of the 128 value dims
+  const int qbase = q0 + wave * 32;
+  bf16x8 qreg[KS];
+  {
+    const size_t row = (size_t)(t0 + min(qbase + n32, L - 1)) * a.H + h;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int k0 = ks * 16 + hi * 8;
+      qreg[ks] = (k0 < 128) ? *reinterpret_cast<const bf16x8*>(a.q_nope + row * 128 + k0)
+                            : *reinterpret_cast<const bf16x8*>(a.q_pe + row * 64 + (k0 - 128));
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));   // complete before the loop
+  }
+
+  f32x16 acc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[d][i] = 0.f;
+  // lsum: the softmax denominators, accumulated on the matrix cores as one more output block whose A
+  // operand is all ones (every row of it holds sum_key P[key, query] of the bf16-rounded weights)
+  float m_run = -INFINITY;
+  f32x16 lsum;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) lsum[i] = 0.f;
+  const int last_tile = (qbase + 31) / PF_TOK;   // later tiles hold no key <= this wave's last query
+
+  for (int t = 0; t < ntiles; ++t) {
+    if (t + 1 < ntiles)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(PF_CPT));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();            // tile t visible to all waves, tile t-1 no longer read
+    if (t + 2 < ntiles) issue(t + 2);
+    if (t > last_tile) continue;             // wave-uniform; the barriers above are still reached
+    const int key0 = t * PF_TOK;
+    const unsigned tile = lds_base + (unsigned)((t % PF_NSTAGE) * PF_TILE_BYTES);
+
+    // ---- scores: one accumulation chain, a ring of 4 K fragments ahead ----
+    f32x16 sc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+    {
+      bf16x8 kf[4];
+      const unsigned kb = tile + k_off;
+      const unsigned ka[4] = {kb, kb ^ 32u, kb ^ 64u, kb ^ 96u};
+      static_for<4>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        lds_read_b128<(2 + (i >> 2)) * 128>(kf[i], ka[i & 3]);
+      });
+      static_for<KS>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int ahead = (KS - 1 - i) < 3 ? (KS - 1 - i) : 3;
+        lds_wait<ahead>(kf[i & 3]);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qreg[i], sc, 0, 0, 0);
+        if constexpr (i + 4 < KS) lds_read_b128<(2 + ((i + 4) >> 2)) * 128>(kf[i & 3], ka[i & 3]);
+      });
+    }
+
+    // the V fragments of the first 16 keys start now: their LDS latency passes under the softmax arithmetic
+    u32x2 vlo[DB], vhi[DB];
+    const unsigned vb0 = tile + v_off;
+    const unsigned va[2] = {vb0, vb0 ^ 64u};
+    const unsigned vh[2] = {vb0 ^ 32u, vb0 ^ 96u};
+    static_for<DB>([&](auto ic) {
+      constexpr int d = decltype(ic)::value;
+      lds_read_tr_b64<(d >> 1) * 128>(vlo[d], va[d & 1]);
+      lds_read_tr_b64<(d >> 1) * 128 + 8 * ROWB>(vhi[d], vh[d & 1]);
+    });
+
+    // ---- causal mask + online softmax: lane = one query, keys key0 + 8 j + 4 hi + i at index 4 j + i ----
+    if (key0 + PF_TOK - 1 > qbase) {         // the tile reaches past this wave's first query
+      const int query = qbase + n32;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (key0 + 8 * (i >> 2) + 4 * hi + (i & 3) > query) sc[i] = -INFINITY;
+    }
+    float mx = sc[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sc[i]);
+    mx *= a.scale_log2;
+    if (__any(mx > m_run + LAZY)) {
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
+      lsum *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int d = 0; d < DB; ++d) acc[d] *= alpha;
+    }
+    bf16x8 pb[2];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      pb[i >> 3][i & 7] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(sc[i], a.scale_log2, -m_run));
+
+    // ---- output: O^T += V^T P^T, 16 keys per step; the second step's fragments refill the ring ----
+    static_for<DB>([&](auto ic) {
+      constexpr int d = decltype(ic)::value;
+      lds_wait<6>(vlo[d], vhi[d]);           // fragments d+1.. of this step and 0..d-1 of the next stay in flight
+      const u32x4 v4 = {vlo[d][0], vlo[d][1], vhi[d][0], vhi[d][1]};
+      acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v4), pb[0], acc[d], 0, 0, 0);
+      lds_read_tr_b64<(d >> 1) * 128 + 16 * ROWB>(vlo[d], va[d & 1]);
+      lds_read_tr_b64<(d >> 1) * 128 + 24 * ROWB>(vhi[d], vh[d & 1]);
+    });
+    static_for<DB>([&](auto ic) {
+      constexpr int d = decltype(ic)::value;
+      lds_wait<2 * (DB - 1 - d)>(vlo[d], vhi[d]);
+      const u32x4 v4 = {vlo[d][0], vlo[d][1], vhi[d][0], vhi[d][1]};
+      acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v4), pb[1], acc[d], 0, 0, 0);
+    });
+    const u32x4 one4 = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+    lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, one4), pb[0], lsum, 0, 0, 0);
+    lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, one4), pb[1], lsum, 0, 0, 0);
+  }
+
+  // ---- normalise and store: lane holds query qbase + n32, dims 32 d + 8 j + 4 hi .. +3 at index 4 j .. ----
+  const float l_tot = lsum[0];
+  const int query = qbase + n32;
+  if (query < L) {
+    const float inv = 1.0f / l_tot;
+    float* po = a.o + ((size_t)(t0 + query) * a.H + h) * 128 + 4 * hi;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const f32x4 v = {acc[d][4 * j] * inv, acc[d][4 * j + 1] * inv, acc[d][4 * j + 2] * inv, acc[d][4 * j + 3] * inv};
+        *reinterpret_cast<f32x4*>(po + 32 * d + 8 * j) = v;
+      }
+  }
+}
+
 bool prefill_mfma_supported(const tpla_shape_t& sh) {
   return sh.dtype == TPLA_BF16 && sh.d_n == 128 && sh.d_v == 128 && sh.d_r == 64 && sh.d_c % 128 == 0 &&
          sh.d_c <= 512;
@@ -457,7 +672,12 @@ int launch_prefill_attention(const tpla_shape_t& sh, const void* q_nope, const v
   a.head_group = sh.H % 8 == 0 ? 8 : (sh.H % 4 == 0 ? 4 : (sh.H % 2 == 0 ? 2 : 1));
   if ((long long)a.n_qt * sh.H > 2147483647LL) return fail(TPLA_ERR_UNSUPPORTED, "grid too large");
   const dim3 grid((unsigned)(a.n_qt * sh.H), sh.B);
+  // -DTPLA_PREFILL32 selects the 32-queries-per-wave kernel (same results to rounding order; measured slower)
+#ifdef TPLA_PREFILL32
+  hipLaunchKernelGGL(prefill_attention_mfma32_kernel, grid, dim3(PF_NW * 64), PF_NSTAGE * PF_TILE_BYTES, st, a);
+#else
   hipLaunchKernelGGL(prefill_attention_mfma_kernel, grid, dim3(PF_NW * 64), PF_NSTAGE * PF_TILE_BYTES, st, a);
+#endif
   return check_launch("prefill_attention_mfma_kernel");
 }
 
