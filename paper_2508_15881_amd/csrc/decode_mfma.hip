@@ -310,6 +310,281 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, u32x4* smem, in
   }
 }
 
+// The same work item for rows too wide for two workgroups per compute unit (576-wide rows: one tile is
+// 36 KB), where decode_item would leave every SIMD with a single wave and nothing to run under its MFMAs.
+// Two waves share 16 heads.  Of a 32-token tile each computes the scores of 16 tokens (half the score
+// MFMAs) and hands them to its partner through LDS; both then run the same softmax on all 32 tokens --
+// same inputs, same operations, so their running reference and sum stay equal bit for bit -- and each
+// multiplies the weights into its own half of the latent dims (half the output MFMAs, 64 accumulator
+// registers instead of 128, which is what lets two waves share a SIMD).  The hand-over would cost a
+// second barrier per tile; instead the loop is skewed by one tile: round r computes the scores of tile r
+// and the softmax and output product of tile r - 1, and the round's one barrier publishes the tile and
+// the partner's scores together.  Ring: tiles r - 1 and r in use, r + 1 and r + 2 in flight.
+// LDS: NSTAGE tiles, then two buffers of one f32x4 per lane of every wave for the scores.
+template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR>
+__device__ __forceinline__ void decode_item_shared(const DecodeArgs& a, u32x4* smem, int shard, int b, int L,
+                                                   int p0, int p1, size_t slot) {
+  constexpr int RC = (DL + DR) / 8;      // 16-byte pieces per row
+  constexpr int KS = (DL + DR) / 32;     // k-steps of the score product
+  constexpr int DBH = DL / 32;           // 16-wide blocks of this wave's half of the latent dims
+  constexpr int TC = TOK * RC;           // pieces per tile
+  constexpr int NI = TC / 64;            // direct-to-LDS instructions per tile
+  constexpr int NWT = 2 * NW;            // waves in the workgroup
+  constexpr int CPT = (NI + NWT - 1) / NWT;
+  constexpr int TPP = PAGE_TOKENS / TOK;
+  constexpr int TILE_BYTES = TC * 16;
+  constexpr int VR = 4;                  // V fragments in flight
+  static_assert(TOK == 32 && NSTAGE == 4, "two tiles in use, two in flight");
+  static_assert(RC % 8 == 0 && TC % 64 == 0 && DBH % VR == 0, "tile shape");
+  static_assert(KR >= 4 && (KR & (KR - 1)) == 0 && KR <= 16, "fragment ring depth");
+
+  const unsigned lds_base = (unsigned)(uintptr_t)((__attribute__((address_space(3))) char*)smem);
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int half = wv / NW, wave = wv % NW;      // half 0: tokens 0-15 and the first DL/2 dims; wave: heads 16 wave ..
+  const int partner = (1 - half) * NW + wave;
+  const int j16 = lane & 15, q4 = lane >> 4;
+  const int vb = shard * a.B + b;
+  int pg_reg = a.block_table[(size_t)b * a.max_pages + min(p0 + lane, p1 - 1)];
+  asm volatile("" : "+v"(pg_reg));
+  const int t_begin = p0 * PAGE_TOKENS;
+  const int t_end = min(p1 * PAGE_TOKENS, L);
+  // scalar: the rounds below branch on it, and a branch the compiler takes for divergent would put
+  // register copies between an LDS read in assembly and the wait that makes its result valid
+  const int ntiles = __builtin_amdgcn_readfirstlane((t_end - t_begin + TOK - 1) / TOK);
+  const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
+  const char* pool = static_cast<const char*>(a.pools[shard]);
+  // the ring and the score buffers restart: nobody may still be reading the previous item's
+  __syncthreads();
+
+  // ---- direct-to-LDS bookkeeping (as in decode_item, over all waves of the workgroup) ----
+  int ld_tok[CPT];
+  unsigned ld_goff[CPT];
+  int ld_k[CPT];
+#pragma unroll
+  for (int j = 0; j < CPT; ++j) {
+    int k = wv + j * NWT;
+    if (k >= NI) k -= NWT;                       // surplus instruction: repeats the wave's previous one
+    const int x = k * 64 + lane;
+    const int tok = x / RC, cs = x % RC;
+    ld_k[j] = k;
+    ld_tok[j] = tok;
+    ld_goff[j] = (unsigned)((tok * RC + (cs ^ swz(tok))) * 16);
+  }
+  int pg_base = 0;
+  auto issue = [&](int t) {
+    const int T = p0 * TPP + t;
+    const int pg = t / TPP;
+    if (pg - pg_base >= 64) {
+      pg_base += 64;
+      pg_reg = bt[min(p0 + pg_base + lane, p1 - 1)];
+      asm volatile("" : "+v"(pg_reg));
+    }
+    const int page = __builtin_amdgcn_readlane(pg_reg, pg - pg_base);
+    const char* src = pool + (size_t)page * (PAGE_TOKENS * RC * 16) + (size_t)(T % TPP) * TILE_BYTES;
+    const int valid = t_end - (t_begin + t * TOK);
+    char* dst = reinterpret_cast<char*>(smem) + (t % NSTAGE) * TILE_BYTES;
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+      const unsigned off = (ld_tok[j] < valid) ? ld_goff[j] : (ld_goff[j] % (RC * 16));
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + off),
+                                       (__attribute__((address_space(3))) void*)(dst + ld_k[j] * 1024),
+                                       16, 0, 2 /* streaming: do not keep in L2 */);
+    }
+  };
+  // rows of a tile past the end of the sequence are cleared once it has landed (the last tile only)
+  auto clear_tail = [&](int t) {
+    const int valid = t_end - (t_begin + t * TOK);
+    if (valid < TOK) {
+      u32x4* tl = smem + (t % NSTAGE) * TC;
+      for (int x = tid; x < TC; x += NWT * 64)
+        if (x / RC >= valid) tl[x] = u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+    }
+  };
+
+  // ---- per-lane LDS byte offsets ----
+  // score product: token 16 half + j16, piece 4 ks + q4
+  const int k_tok = 16 * half + j16;
+  const int xk = swz(k_tok);
+  unsigned k_off[2];
+  k_off[0] = (unsigned)((k_tok * RC + ((q4) ^ xk)) * 16);
+  k_off[1] = (unsigned)((k_tok * RC + ((4 | q4) ^ xk)) * 16);
+  // output product: token 4 q4 + (j16 >> 2) (+16), dims (DL / 2) half + 16 d + 4 (j16 & 3) .. +4
+  const int v_tok = 4 * q4 + (j16 >> 2);
+  const int xv = swz(v_tok);
+  const int cb = (j16 & 3) >> 1;
+  unsigned v_off[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+    v_off[d] = (unsigned)((v_tok * RC + (((d << 1) | cb) ^ xv)) * 16 + (j16 & 1) * 8 + half * DL);   // DL bytes = DL / 2 dims
+
+  f32x4 acc[DBH];
+#pragma unroll
+  for (int d = 0; d < DBH; ++d) acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+
+  issue(0);
+  if (ntiles > 1) issue(1);
+
+  // ---- the 16 heads of this wave pair, as B operands ----
+  const int head = wave * 16 + j16;
+  bf16x8 qreg[KS];
+  {
+    const bf16_t* ql = static_cast<const bf16_t*>(a.q_lat) + ((size_t)vb * a.H + head) * DL;
+    const bf16_t* qp = static_cast<const bf16_t*>(a.q_pe) + ((size_t)b * a.H + head) * DR;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int k0 = ks * 32 + q4 * 8;
+      qreg[ks] = (k0 < DL) ? *reinterpret_cast<const bf16x8*>(ql + k0)
+                           : *reinterpret_cast<const bf16x8*>(qp + (k0 - DL));
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));   // complete before the loop
+  }
+
+  // scores of this wave's 16 tokens of the tile at LDS address `tile`
+  auto scores = [&](unsigned tile) {
+    f32x4 sc = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 kf[KR];
+    const unsigned ka[2] = {tile + k_off[0], tile + k_off[1]};
+    static_for<KR>([&](auto ic) {
+      constexpr int ks = decltype(ic)::value;
+      lds_read_b128<(ks >> 1) * 128>(kf[ks], ka[ks & 1]);
+    });
+    static_for<KS>([&](auto ic) {
+      constexpr int ks = decltype(ic)::value;
+      constexpr int ahead = (KS - 1 - ks) < KR - 1 ? (KS - 1 - ks) : KR - 1;
+      lds_wait<ahead>(kf[ks & (KR - 1)]);
+      sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks & (KR - 1)], qreg[ks], sc, 0, 0, 0);
+      if constexpr (ks + KR < KS) lds_read_b128<((ks + KR) >> 1) * 128>(kf[ks & (KR - 1)], ka[(ks + KR) & 1]);
+    });
+    return sc;
+  };
+
+  // ---- round 0: the scores of tile 0 ----
+  if (ntiles > 1)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(CPT));
+  else
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  __builtin_amdgcn_s_barrier();
+  TPLA_TL_MARK_ONCE(1);
+  if (ntiles > 2) issue(2);
+  clear_tail(0);
+  // The hand-over is written with a plain store (the compiler then keeps the wait states an MFMA result
+  // needs before an LDS instruction may read it) and read with inline assembly like the tiles (a plain
+  // LDS load after a direct-to-LDS load would make the compiler wait for every load in flight).
+  f32x4* x_own = reinterpret_cast<f32x4*>(smem + NSTAGE * TC) + wv * 64 + lane;
+  const unsigned x_partner = lds_base + (unsigned)(NSTAGE * TILE_BYTES + (partner * 64 + lane) * 16);
+  constexpr unsigned XBUF = NWT * 64 * 16;       // bytes per hand-over buffer
+  f32x4 s_own = scores(lds_base);
+  x_own[0] = s_own;
+
+  // ---- round r: scores of tile r (while there is one), softmax and output product of tile r - 1 ----
+  for (int r = 1; r <= ntiles; ++r) {
+    const bool more = r < ntiles;
+    // tile r has landed once only tile r + 1 (requested in the round before) is outstanding
+    if (r + 1 < ntiles)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(CPT));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    // the hand-over written in round r - 1 must have left this wave before the barrier publishes it
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();        // tile r and the partners' scores of tile r - 1 visible; tile r - 2 no longer read
+    if (r + 2 < ntiles) issue(r + 2);
+    if (more) clear_tail(r);
+    const f32x4 s_prev = s_own;
+    f32x4 s_partner;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(s_partner) : "v"(x_partner + ((r - 1) & 1) * XBUF) : "memory");
+    if (more) {
+      s_own = scores(lds_base + (unsigned)((r % NSTAGE) * TILE_BYTES));
+      x_own[(r & 1) * (XBUF / 16)] = s_own;
+    }
+    // one wait on one path for both cases, straight after the branch (which does not touch s_partner)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(s_partner) : : "memory");
+    const unsigned tile = lds_base + (unsigned)(((r - 1) % NSTAGE) * TILE_BYTES);
+    const int valid = t_end - (t_begin + (r - 1) * TOK);
+
+    // the first V fragments start now, under the softmax arithmetic
+    u32x2 vlo[VR], vhi[VR];
+    unsigned va[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) va[d] = tile + v_off[d];
+    static_for<VR>([&](auto ic) {
+      constexpr int d = decltype(ic)::value;
+      lds_read_tr_b64<(d >> 2) * 128>(vlo[d], va[d & 3]);
+      lds_read_tr_b64<(d >> 2) * 128 + 16 * RC * 16>(vhi[d], va[d & 3]);
+    });
+
+    // ---- online softmax on all 32 tokens (lane = one head; tokens 16 tb + 4 q4 + i) ----
+    f32x4 sacc[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      sacc[0][i] = half ? s_partner[i] : s_prev[i];
+      sacc[1][i] = half ? s_prev[i] : s_partner[i];
+    }
+    if (valid < TOK) {
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (16 * tb + 4 * q4 + i >= valid) sacc[tb][i] = -INFINITY;
+    }
+    float mx = sacc[0][0];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mx = fmaxf(mx, sacc[tb][i]);
+    mx *= a.scale_log2;
+    if (__any(mx > m_run + LAZY)) {
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int d = 0; d < DBH; ++d) acc[d] *= alpha;
+    }
+    float psum = 0.f;
+    bf16x8 pb;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[tb][i], a.scale_log2, -m_run));
+        psum += p;
+        pb[4 * tb + i] = (bf16_t)p;
+      }
+    l_run += psum;
+
+    // ---- output: O^T += V^T P^T over this wave's half of the dims ----
+    static_for<DBH>([&](auto ic) {
+      constexpr int d = decltype(ic)::value;
+      constexpr int ahead = (DBH - 1 - d) < VR - 1 ? (DBH - 1 - d) : VR - 1;
+      lds_wait<2 * ahead>(vlo[d & (VR - 1)], vhi[d & (VR - 1)]);
+      const u32x4 v4 = {vlo[d & (VR - 1)][0], vlo[d & (VR - 1)][1], vhi[d & (VR - 1)][0], vhi[d & (VR - 1)][1]};
+      acc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v4), pb, acc[d], 0, 0, 0);
+      if constexpr (d + VR < DBH) {
+        constexpr int d2 = d + VR;
+        lds_read_tr_b64<(d2 >> 2) * 128>(vlo[d & (VR - 1)], va[d2 & 3]);
+        lds_read_tr_b64<(d2 >> 2) * 128 + 16 * RC * 16>(vhi[d & (VR - 1)], va[d2 & 3]);
+      }
+    });
+  }
+
+  TPLA_TL_MARK(2);
+  float l_tot = l_run + __shfl_xor(l_run, 16);
+  l_tot += __shfl_xor(l_tot, 32);
+  const size_t item = slot * a.H + head;
+  float* pacc = a.part_acc + item * DL + (DL / 2) * half + 4 * q4;
+#pragma unroll
+  for (int d = 0; d < DBH; ++d) *reinterpret_cast<f32x4*>(pacc + 16 * d) = acc[d];
+  if (q4 == 0 && half == 0) {
+    a.part_ml[item * 2 + 0] = m_run;
+    a.part_ml[item * 2 + 1] = l_tot;
+  }
+}
+
 // The same work item with 32 heads per wave on 32x32x16 MFMAs.  Every K and V
 // fragment read from LDS then serves twice as many heads: half the LDS reads,
 // half the MFMA issues and half the operand fetches per cache byte.  The price
@@ -645,8 +920,10 @@ __device__ __forceinline__ void decode_item32(const DecodeArgs& a, u32x4* smem, 
 // Waves per SIMD the register allocation must allow: two 4-wave workgroups
 // (or one 8-wave workgroup) per compute unit need 2; a 512-wide slice only
 // fits one workgroup per compute unit in LDS, so it keeps the full budget.
+constexpr int HPW_PAIR = 8;      // value of HPW that selects decode_item_shared: 16 heads per pair of waves
 template <int DL, int NW, int HPW = 16>
 constexpr int waves_per_simd() {
+  if (HPW == HPW_PAIR) return 2 * NW >= 8 ? 2 : 1;
   if (HPW == 32) return DL <= 128 ? 2 : 1;
   return DL >= 512 ? (NW >= 8 ? 2 : 1) : (NW >= 4 ? 2 : 1);
 }
@@ -660,7 +937,7 @@ template <int DL, int NW>
 constexpr int frag_ring() { return 4; }
 
 template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR, int HPW>
-__global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW, HPW>())) decode_mfma_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(NW * 64 * (HPW == HPW_PAIR ? 2 : 1), (waves_per_simd<DL, NW, HPW>())) decode_mfma_kernel(DecodeArgs a) {
   extern __shared__ u32x4 smem[];        // NSTAGE tiles
   const int vb = blockIdx.x / a.n_splits, s = blockIdx.x % a.n_splits;   // vb = slice * B + sequence
   const int shard = vb / a.B, b = vb % a.B;
@@ -671,6 +948,8 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW, HPW>())) deco
   const int p1 = min(p0 + a.pages_per_split, n_pages);
   if constexpr (HPW == 32)
     decode_item32<DL, DR, NW, TOK, NSTAGE>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
+  else if constexpr (HPW == HPW_PAIR)
+    decode_item_shared<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
   else
     decode_item<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, shard, b, L, p0, p1, (size_t)vb * a.n_splits + s);
 }
@@ -683,7 +962,7 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW, HPW>())) deco
 // increasing along the items, hence unique).  Workgroup 0 also publishes the
 // page offsets of the sequences for the merge.
 template <int DL, int DR, int NW, int TOK, int NSTAGE, int KR, int HPW>
-__global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW, HPW>())) decode_mfma_balanced_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(NW * 64 * (HPW == HPW_PAIR ? 2 : 1), (waves_per_simd<DL, NW, HPW>())) decode_mfma_balanced_kernel(DecodeArgs a) {
   extern __shared__ u32x4 smem[];
 #ifdef TPLA_WG_TIMELINE
   if (threadIdx.x == 0 && blockIdx.x < 4096) {
@@ -729,6 +1008,8 @@ __global__ void __launch_bounds__(NW * 64, (waves_per_simd<DL, NW, HPW>())) deco
       const int vs = v0 + src;
       if constexpr (HPW == 32)
         decode_item32<DL, DR, NW, TOK, NSTAGE>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
+      else if constexpr (HPW == HPW_PAIR)
+        decode_item_shared<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
       else
         decode_item<DL, DR, NW, TOK, NSTAGE, KR>(a, smem, vs / a.B, vs % a.B, Ls, p0, p1, (size_t)w + vs);
     }
@@ -761,12 +1042,17 @@ struct KernelInfo {
 
 template <int DL, int NW, int HPW>
 static KernelInfo make_kernel_info() {
-  constexpr int TOK = 32, NSTAGE = HPW == 32 ? (DL <= 128 ? 3 : TPLA_H32_STAGES) : ring_stages<DL>(), KR = frag_ring<DL, NW>();
+  constexpr int TOK = 32, KR = frag_ring<DL, NW>();
+  constexpr int NSTAGE = HPW == HPW_PAIR ? 4 : HPW == 32 ? (DL <= 128 ? 3 : TPLA_H32_STAGES) : ring_stages<DL>();
   KernelInfo info;
   info.fn = decode_mfma_kernel<DL, 64, NW, TOK, NSTAGE, KR, HPW>;
   info.fn_balanced = decode_mfma_balanced_kernel<DL, 64, NW, TOK, NSTAGE, KR, HPW>;
   info.smem = (size_t)NSTAGE * TOK * ((DL + 64) / 8) * 16;
   info.threads = NW * 64;
+  if (HPW == HPW_PAIR) {
+    info.smem += (size_t)2 * (2 * NW) * 64 * 16;     // the two hand-over buffers
+    info.threads *= 2;
+  }
   // dynamic LDS above the 64 KiB default needs opting in
   if (info.smem > 64 * 1024 &&
       (hipFuncSetAttribute(reinterpret_cast<const void*>(info.fn), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -800,7 +1086,12 @@ template <int DL>
 static int kernel_info_dl(int H, KernelInfo** out) {
   switch (H) {
     case 16: return kernel_info<DL, 1>(out);
-    case 32: return kernel_info<DL, 2>(out);
+    case 32:
+      if constexpr (DL == 512) {     // as for 64 heads below
+        static const bool pair_ok = [] { KernelInfo* k = nullptr; return kernel_info<DL, 2, HPW_PAIR>(&k) == TPLA_OK; }();
+        if (pair_ok) return kernel_info<DL, 2, HPW_PAIR>(out);
+      }
+      return kernel_info<DL, 2>(out);
     // -DTPLA_H32 routes 64 and 128 heads to the 32-heads-per-wave instances.  Measured against the
     // 16-heads-per-wave ones (32 x 32768 tokens, both slices): 269 against 223 us at 64 heads, 448 against
     // 369 us at 128 -- LDS instructions per tile are halved, but a wave's own VALU instructions do not
@@ -814,7 +1105,13 @@ static int kernel_info_dl(int H, KernelInfo** out) {
       if constexpr (DL <= 256) return kernel_info<DL, 4, 32>(out);
       return kernel_info<DL, 8>(out);
 #else
-    case 64: return kernel_info<DL, 4>(out);
+    case 64:
+      // 576-wide rows: pairs of waves per 16 heads (160 KB of LDS); the plain instance if the device refuses that
+      if constexpr (DL == 512) {
+        static const bool pair_ok = [] { KernelInfo* k = nullptr; return kernel_info<DL, 4, HPW_PAIR>(&k) == TPLA_OK; }();
+        if (pair_ok) return kernel_info<DL, 4, HPW_PAIR>(out);
+      }
+      return kernel_info<DL, 4>(out);
     case 128: return kernel_info<DL, 8>(out);
 #endif
   }

@@ -17,8 +17,8 @@ from gpu_common import TOL, rel_err
 pytestmark = pytest.mark.gpu
 
 
-def _run_config(name, sample):
-    w = wl.CONFIGS[name]
+def _run_config(name, sample, w=None):
+    w = wl.CONFIGS[name] if w is None else w
     print(f"full-size {name}: B={w.B} tokens~{w.B * (w.context or 26800)} sample={sample}", flush=True)
     dev = "cuda"
     shape = pl.make_shape(w)
@@ -97,6 +97,12 @@ def test_full_size_dsv3_4k():
 @pytest.mark.timeout(300)
 def test_full_size_dsv3_32k():
     _run_config("dsv3_32k", [0, 17, 31])
+
+
+@pytest.mark.timeout(400)
+def test_full_size_mla_shaped_g1():
+    """576-wide rows (one device of head-split MLA): 64 heads as pairs of waves, work items of 32 tiles."""
+    _run_config("dsv3_32k with g = 1, B = 8", [0, 7], wl.scaled(wl.CONFIGS["dsv3_32k"], g=1, B=8))
 
 
 @pytest.mark.timeout(600)

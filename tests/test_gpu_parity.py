@@ -28,6 +28,10 @@ MFMA_CASES = [
     ("kimi_g2_H32", KIMI, [129, 1000, 5, 64]),
     ("ragged_g4_H64", RAGGED, [3000, 17, 256, 4097]),
     ("mla_g1_H64", wl.scaled(DSV3, g=1), [333, 64, 1025]),
+    # 576-wide rows with 64 heads run as pairs of waves: one tile, whole tiles, odd and even tile counts,
+    # ragged tails in the first and the second half of a tile, empty sequences, more than 64 pages per item
+    ("mla_g1_H64_tiles", wl.scaled(DSV3, g=1), [1, 15, 16, 17, 32, 33, 48, 63, 64, 65, 96, 97, 0, 127, 129, 4500]),
+    ("mla_g1_H32", wl.scaled(KIMI, g=1), [1, 33, 64, 97, 700, 0, 2049]),
     ("dsv3_g2_H128", wl.scaled(DSV3, H=128), [500, 130]),
     ("dsv3_g2_H16", wl.scaled(DSV3, H=16), [500, 130]),
 ]
