@@ -19,6 +19,13 @@
 // LDS reads of the tiles are issued from inline assembly with hand-placed
 // lgkmcnt waits: the compiler would otherwise make every LDS read wait for
 // all outstanding direct-to-LDS loads, which would serialise the prefetch.
+// The compiler takes the destination of such a read for valid from the moment
+// it is issued: read, wait and first use must stay in straight-line code, or a
+// register copy may land between the read and its wait.
+//
+// Three bodies for a work item: decode_item (16 heads per wave; the default),
+// decode_item_shared (576-wide rows: two waves per 16 heads, scores handed
+// over through LDS) and decode_item32 (32 heads per wave, build flag TPLA_H32).
 #include <hip/hip_ext.h>
 #include "lds_tile.h"
 
