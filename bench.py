@@ -215,45 +215,51 @@ class Prepared:
         self.step.run(self.q_nope, self.q_pe, self.W_UK_t, self.W_UV_t, pools, self.bt, self.lens, self.mu)
 
 
-def settle(p, min_s, max_s, batch=40):
+def settle(p, min_s, max_s, batch=40, keep_events_for=0):
     """Holds the GPU under the decode step until the split kernel's time has settled: batches of
     `batch` event-timed steps, at least min_s, until three batch means in a row agree to 2 %
-    (at most max_s).  Returns what happened; nothing of it enters the timed region."""
+    (at most max_s).  Returns what happened; nothing of it enters the timed region.
+    keep_events_for = N leaves event pairs for N launches in place, so that the timed region can follow
+    without the pause that creating them would be (the first launches after a pause run slower)."""
     import numpy as np
     import torch
     import paper_2508_15881_amd as tp
+    cap = max(batch, keep_events_for)
+    tp.tpla_profile_enable(cap)
     means, t0 = [], time.perf_counter()
     while True:
-        tp.tpla_profile_enable(batch)
         for _ in range(batch):
             p.run_step()
         torch.cuda.synchronize()
-        means.append(float(np.mean(tp.tpla_profile_collect(batch))) * 1e3)
+        means.append(float(np.mean(tp.tpla_profile_collect(cap)[:batch])) * 1e3)
         el = time.perf_counter() - t0
         agreed = len(means) >= 3 and max(means[-3:]) <= 1.02 * min(means[-3:])
         if (el >= min_s and agreed) or el >= max_s:
             break
-    tp.tpla_profile_enable(0)
+    if not keep_events_for:
+        tp.tpla_profile_enable(0)
     return {"settle_s": el, "steps": batch * len(means), "agreed_to_2pct": bool(agreed),
             "launch_us_first_batch": means[0], "launch_us_slowest_batch": max(means), "launch_us_last_batch": means[-1]}
 
 
-def timed_region(p, warmup, steps, pools=None):
+def timed_region(p, warmup, steps, pools=None, events_ready=False):
     """W untimed warm-up steps, then exactly K steps between two synchronisations, the split kernel of
-    every step bracketed by HIP events on the launch stream.  Returns (ms_per_step, kernel ms list)."""
+    every step bracketed by HIP events on the launch stream (the warm-up steps carry events too and
+    their readings are dropped: the events exist before the first step, so nothing but the
+    synchronisation separates warm-up and timed steps).  Returns (ms_per_step, kernel ms list)."""
     import torch
     import paper_2508_15881_amd as tp
+    if not events_ready:
+        tp.tpla_profile_enable(warmup + steps)
     for _ in range(warmup):
         p.run_step(pools)
-    torch.cuda.synchronize()
-    tp.tpla_profile_enable(steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
         p.run_step(pools)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kern_ms = tp.tpla_profile_collect(steps)
+    kern_ms = tp.tpla_profile_collect(warmup + steps)[warmup:]
     tp.tpla_profile_enable(0)
     return (t1 - t0) * 1e3 / steps, kern_ms
 
@@ -287,9 +293,9 @@ def measure_other(name, args):
     from paper_2508_15881_amd import workloads as wl
     w = wl.CONFIGS[name]
     p = Prepared(w, 0)
-    st = settle(p, min(args.settle_s, 0.5), max(1.5, args.settle_s))
     steps = max(args.steps, 50)
-    ms_per_step, kern_ms = timed_region(p, args.warmup, steps)
+    st = settle(p, min(args.settle_s, 0.5), max(1.5, args.settle_s), keep_events_for=args.warmup + steps)
+    ms_per_step, kern_ms = timed_region(p, args.warmup, steps, events_ready=True)
     ls = launch_stats(kern_ms)
     launch_bytes = w.g * p.shard_bytes
     achieved = launch_bytes / (ls["launch_us"] * 1e-6) / 1e9
@@ -467,8 +473,9 @@ def main():
 
     # ---- settle, W warm-up steps, then the timed region: exactly K steps ----------
     n_sets_rotated = p.n_sets
-    settled = settle(p, args.settle_s, 3.0 * args.settle_s) if args.settle_s > 0 else None
-    ms_per_step, kern_ms = timed_region(p, args.warmup, args.steps)
+    settled = (settle(p, args.settle_s, 3.0 * args.settle_s, keep_events_for=args.warmup + args.steps)
+               if args.settle_s > 0 else None)
+    ms_per_step, kern_ms = timed_region(p, args.warmup, args.steps, events_ready=settled is not None)
 
     cache_resident = None
     if p.n_sets > 1:
