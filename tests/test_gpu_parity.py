@@ -34,6 +34,13 @@ MFMA_CASES = [
     ("mla_g1_H32", wl.scaled(KIMI, g=1), [1, 33, 64, 97, 700, 0, 2049]),
     ("dsv3_g2_H128", wl.scaled(DSV3, H=128), [500, 130]),
     ("dsv3_g2_H16", wl.scaled(DSV3, H=16), [500, 130]),
+    # the remaining instances of the matrix-core kernel (slice width x head count), so that each is
+    # compared with the oracle in both its static-chunk and its balanced form
+    ("g4_H16", wl.scaled(RAGGED, H=16), [300, 65, 1]),
+    ("g4_H32", wl.scaled(RAGGED, H=32), [300, 65, 1]),
+    ("g4_H128", wl.scaled(RAGGED, H=128), [300, 65, 1]),
+    ("mla_g1_H16", wl.scaled(DSV3, g=1, H=16), [300, 65, 1]),
+    ("mla_g1_H128", wl.scaled(DSV3, g=1, H=128), [300, 65, 1]),
 ]
 
 
