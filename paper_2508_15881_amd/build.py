@@ -61,6 +61,17 @@ def build(verbose=True):
     return LIB_PATH
 
 
+def device_assembly(source, extra_flags=()):
+    """The gfx950 assembly hipcc generates for one source file of csrc/, as text (same flags as build()).
+    Used by tests/test_isa_lds_waits.py, which checks this build's own kernels on the CPU machine."""
+    out_dir = os.path.join(OBJ_DIR, "asm")
+    os.makedirs(out_dir, exist_ok=True)
+    path = os.path.join(out_dir, source.replace(".hip", ".s"))
+    _run([HIPCC] + FLAGS + list(extra_flags) + ["-S", "--cuda-device-only", os.path.join(CSRC, source), "-o", path])
+    with open(path) as f:
+        return f.read()
+
+
 def build_host_sanitized(driver_cpp, exe_path, verbose=False):
     """Second build configuration, for the CPU machine only: the same sources with AddressSanitizer
     and UndefinedBehaviorSanitizer on the HOST code (device code is compiled as usual, unsanitised),
