@@ -97,9 +97,11 @@ def test_the_checker_sees_a_copy_before_the_wait():
     assert [v[0] for v in check_kernel(ring)] == [4]
 
 
-@pytest.mark.parametrize("source", SOURCES)
-def test_no_instruction_touches_an_lds_read_before_its_wait(source):
-    kernels = _kernels(b.device_assembly(source))
+# the third entry: the 32-heads-per-wave instances, which only exist in the measurement build
+@pytest.mark.parametrize("source,flags", [(s, ()) for s in SOURCES] + [("decode_mfma.hip", ("-DTPLA_H32",))],
+                         ids=SOURCES + ["decode_mfma.hip-H32"])
+def test_no_instruction_touches_an_lds_read_before_its_wait(source, flags):
+    kernels = _kernels(b.device_assembly(source, flags))
     assert kernels, source
     n_reads = 0
     for name, insts in kernels.items():
