@@ -85,6 +85,7 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_page
   p.balanced = 0;
   p.n_wg = 0;
   for (int r = 0; r < 4; ++r) p.round_wt[r] = 1;
+  p.xcc_wt[0] = p.xcc_wt[1] = 1;
   int32_t n = n_splits_req;
   if (n <= 0 && sh.dtype == TPLA_BF16 && decode_mfma_supported(sh)) {
     // Automatic plan of the matrix-core kernel: exactly as many workgroups as
@@ -102,7 +103,7 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_page
     if (n_wg > most) n_wg = (int)most;
     // A full launch of long ranges: the workgroup placed first on a compute unit runs ahead of the
     // ones placed after it, so the ranges are sized by placement round for all to end together.
-    if (n_wg == cus * per_cu && most / n_wg >= 32) decode_mfma_round_weights(sh, per_cu, p.round_wt);
+    if (n_wg == cus * per_cu && cus % 8 == 0 && most / n_wg >= 32) decode_mfma_round_weights(sh, per_cu, p.round_wt, p.xcc_wt);
     p.balanced = 1;
     p.n_wg = n_wg;
     p.n_splits = 1;
@@ -188,6 +189,8 @@ static int decode_common(const tpla_shape_t* shape, int n_shards, const void* q_
   a.geom.W = plan.n_wg;
   a.geom.n_cus = device_cu_count();
   for (int r = 0; r < 4; ++r) a.geom.wt[r] = plan.round_wt[r];
+  a.geom.wx[0] = plan.xcc_wt[0];
+  a.geom.wx[1] = plan.xcc_wt[1];
   a.o_lat = o_lat;
   a.lse = lse;
   a.n_shards = n_shards;

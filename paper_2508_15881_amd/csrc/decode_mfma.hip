@@ -1149,10 +1149,25 @@ int decode_mfma_blocks_per_cu(const tpla_shape_t& sh) {
 // 12 KB tiles, 24 KB in flight per workgroup) the lone last round does not, and weighted ranges take
 // the ragged batch from 1122 to 1073 us.  With one wave per SIMD (32 heads and fewer) the rounds run
 // alike.  Weights in units of 1/128 of the average range.
-void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]) {
+//
+// The XCCs differ too, the same way on every box measured: workgroups on the odd-numbered ones take
+// 4 % (64 heads, 256-wide slices) to 9 % (32 heads; 128-wide slices) longer over equal ranges than
+// those on the even-numbered ones.  Workgroups are dealt to the XCCs in turn, so the odd positions of a
+// round get shorter ranges.  Measured on one box with the weight of the odd positions at 128 (equal),
+// 123, 118, 113, 108 / 128: 64 heads, 256-wide: 221.9, 219.7, 220.4, 223.6 us; 32 heads: 414.3, 410.8,
+// 404.7, 405.5 us (another box: 113 399.2, 108 406.7, 103 414.2); 128-wide ragged batch: 1072, 1061,
+// 1051, 1047 us (other box: 113 1043, 108 1057, 103 1069); 576-wide: 232.5, 229.1, 229.6, 229.4 us.
+// Whole steps on a third box, equal against weighted: 32 heads 446 -> 431 us, ragged batch 1138 -> 1121 us.
+void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4], int32_t wx[2]) {
   for (int r = 0; r < 4; ++r) wt[r] = 128;
+  const int dl = sh.d_c / sh.g;
+  wx[0] = 128;
+  // 64 heads over 256- or 576-wide rows stay equal: the gain there is within the spread between boxes, and equal
+  // ranges end on sequence boundaries when the lengths are equal (one partial result per workgroup instead of two:
+  // the layer-step took 3 us longer with the weights); 128 heads: not measured
+  wx[1] = dl == 128 ? 113 : (sh.H <= 32 ? 115 : 128);
 #ifdef TPLA_H32
-  const int heads_per_wave = (sh.H >= 64 && sh.d_c / sh.g <= 256) ? 32 : 16;
+  const int heads_per_wave = (sh.H >= 64 && dl <= 256) ? 32 : 16;
 #else
   const int heads_per_wave = 16;
 #endif

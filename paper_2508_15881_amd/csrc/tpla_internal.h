@@ -27,29 +27,34 @@ struct SplitPlan {
   int32_t n_splits;          // static
   int32_t pages_per_split;   // static
   int32_t round_wt[4];       // balanced: weight of the ranges of each placement round
+  int32_t xcc_wt[2];         // balanced: weight of the ranges of even / odd workgroups
 };
 SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_pages_per_seq, int32_t n_splits_req);
 
 // Balanced plan.  The T pages of all (slice, sequence) pairs are laid end to end and cut into W
 // ranges, one per workgroup; range w is [plan_start(w), plan_start(w + 1)).  Ranges are weighted by
 // the placement round of their workgroup (round = w / n_cus; the hardware fills every compute unit
-// once before it places a second workgroup on any): a range of round r is wt[r] / wt[0] times as
-// long as one of round 0.  All weights equal = ranges [w T / W, (w + 1) T / W).
+// once before it places a second workgroup on any) and by the parity of its position in the round
+// (workgroups go to the eight XCCs in turn and n_cus is a multiple of 8 on the hardware, so this is the
+// parity of the XCC): the weight of range w is wt[w / n_cus] * wx[(w % n_cus) & 1].
+// All weights equal = ranges [w T / W, (w + 1) T / W).
 struct BalancedPlan {
   int32_t W;        // ranges = workgroups
   int32_t n_cus;    // workgroups per placement round
   int32_t wt[4];    // weight of a range of round min(r, 3); positive
+  int32_t wx[2];    // weight of a range at an even / odd position of its round; positive
 };
 // Sum of the weights of ranges 0 .. w-1.
 __host__ __device__ __forceinline__ long long plan_cum(const BalancedPlan& p, int w) {
   long long c = 0;
   int r = 0, left = w;
+  const long long pair = (long long)p.wx[0] + p.wx[1];
   while (r < 3 && left > p.n_cus) {
-    c += (long long)p.n_cus * p.wt[r];
+    c += ((long long)(p.n_cus / 2) * pair + (long long)(p.n_cus & 1) * p.wx[0]) * p.wt[r];
     left -= p.n_cus;
     ++r;
   }
-  return c + (long long)left * p.wt[r];
+  return c + ((long long)(left / 2) * pair + (long long)(left & 1) * p.wx[0]) * p.wt[r];
 }
 // First page of range w, 0 <= w <= W (T pages in all; T * total weight stays below 2^62).
 __host__ __device__ __forceinline__ int plan_start(const BalancedPlan& p, long long T, int w) {
@@ -57,16 +62,18 @@ __host__ __device__ __forceinline__ int plan_start(const BalancedPlan& p, long l
 }
 // The range that holds page c, 0 <= c < T.
 __host__ __device__ __forceinline__ int balanced_owner(const BalancedPlan& p, int c, int T) {
-  // first guess from the inverse of the piecewise linear cumulative weight, then step to the exact range
+  // first guess from the inverse of the piecewise linear cumulative weight (with the mean of the two
+  // parity weights), then step to the exact range
   const long long total = plan_cum(p, p.W);
+  const long long pair = (long long)p.wx[0] + p.wx[1];
   long long x = ((long long)c * total) / T;
   int r = 0, base = 0;
-  while (r < 3 && base + p.n_cus < p.W && x >= (long long)p.n_cus * p.wt[r]) {
-    x -= (long long)p.n_cus * p.wt[r];
+  while (r < 3 && base + p.n_cus < p.W && x >= plan_cum(p, base + p.n_cus) - plan_cum(p, base)) {
+    x -= plan_cum(p, base + p.n_cus) - plan_cum(p, base);
     base += p.n_cus;
     ++r;
   }
-  int w = base + (int)(x / p.wt[r]);
+  int w = base + (int)(2 * x / (p.wt[r] * pair));
   if (w > p.W - 1) w = p.W - 1;
   while (w + 1 < p.W && plan_start(p, T, w + 1) <= c) ++w;
   while (w > 0 && plan_start(p, T, w) > c) --w;
@@ -77,7 +84,8 @@ __host__ __device__ __forceinline__ int balanced_owner(const BalancedPlan& p, in
 __host__ __device__ __forceinline__ bool plan_sparse(const BalancedPlan& p, long long T) {
   int m = p.wt[0];
   for (int r = 1; r < 4; ++r) m = p.wt[r] < m ? p.wt[r] : m;
-  return T * m < plan_cum(p, p.W);
+  const int mx = p.wx[0] < p.wx[1] ? p.wx[0] : p.wx[1];
+  return T * m * mx < plan_cum(p, p.W);
 }
 // Whether range w meets the pages [c0, c1) (only in doubt when plan_sparse()).
 __host__ __device__ __forceinline__ bool balanced_range_meets(const BalancedPlan& p, int w, int T, int c0, int c1) {
@@ -122,9 +130,9 @@ bool decode_mfma_supported(const tpla_shape_t& sh);
 // Workgroups of the matrix-core kernel for this shape that fit on one compute
 // unit (0 = unknown).
 int decode_mfma_blocks_per_cu(const tpla_shape_t& sh);
-// Range weights by placement round for a launch that puts per_cu workgroups of the matrix-core
-// kernel on every compute unit (all equal where the rounds run equally fast).
-void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]);
+// Range weights by placement round (wt) and by even / odd position in the round (wx) for a launch that
+// puts per_cu workgroups of the matrix-core kernel on every compute unit.
+void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4], int32_t wx[2]);
 // ev_start / ev_stop (both or neither): events that receive the kernel's begin and end times.
 int launch_decode_mfma(const DecodeArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr,
                        hipEvent_t ev_stop = nullptr);

@@ -218,6 +218,8 @@ static void plan_checks() {
   const int Ws[] = {1, 2, 3, 7, 16, 40, 256, 512, 768};
   const int wts[][4] = {{1, 1, 1, 1}, {135, 121, 128, 128}, {140, 129, 115, 128}, {128, 128, 128, 128}, {3, 1, 1, 7}};
   const int cus[] = {256, 8, 5};
+  const int wxs[][2] = {{1, 1}, {128, 118}, {100, 131}};
+  for (const auto& wx : wxs)
   for (const auto& wt : wts)
     for (int n_cus : cus)
       for (int W : Ws)
@@ -226,6 +228,8 @@ static void plan_checks() {
           p.W = W;
           p.n_cus = n_cus;
           for (int r = 0; r < 4; ++r) p.wt[r] = wt[r];
+          p.wx[0] = wx[0];
+          p.wx[1] = wx[1];
           const int n_seq = 1 + (int)((lcg(st) + 1.0) * 6.0);
           std::vector<int> pages((size_t)n_seq), excl((size_t)n_seq);
           int T = 0;
@@ -239,7 +243,7 @@ static void plan_checks() {
           if (T == 0) continue;
           EXPECT(tpla::plan_start(p, T, 0) == 0 && tpla::plan_start(p, T, W) == T);
           for (int w = 0; w < W; ++w) EXPECT(tpla::plan_start(p, T, w) <= tpla::plan_start(p, T, w + 1));
-          if (wt[0] == wt[1] && wt[1] == wt[2] && wt[2] == wt[3])      // equal weights: the plain equal shares
+          if (wt[0] == wt[1] && wt[1] == wt[2] && wt[2] == wt[3] && wx[0] == wx[1])      // equal weights: the plain equal shares
             for (int w = 0; w <= W; ++w) EXPECT(tpla::plan_start(p, T, w) == (int)((long long)w * T / W));
           for (int c = 0; c < T; ++c) {
             const int w = tpla::balanced_owner(p, c, T);
@@ -274,12 +278,16 @@ static void plan_checks() {
         }
   // the weighted plans of the library's own launches leave no range empty (the merge relies on it:
   // it only looks for empty ranges when there are fewer pages than ranges)
-  const int full[][6] = {{512, 256, 135, 121, 128, 128}, {768, 256, 140, 129, 115, 128}};
+  const int full[][8] = {{512, 256, 135, 121, 128, 128, 128, 128}, {768, 256, 140, 129, 115, 128, 128, 128},
+                         {768, 256, 140, 129, 115, 128, 128, 113}, {512, 256, 128, 128, 128, 128, 128, 123},
+                         {512, 256, 128, 128, 128, 128, 128, 115}, {256, 256, 128, 128, 128, 128, 128, 123}};
   for (const auto& f : full) {
     tpla::BalancedPlan p;
     p.W = f[0];
     p.n_cus = f[1];
     for (int r = 0; r < 4; ++r) p.wt[r] = f[2 + r];
+    p.wx[0] = f[6];
+    p.wx[1] = f[7];
     for (int T : {32 * f[0], 32 * f[0] + 17, 100000, 2000000})
       for (int w = 0; w < p.W; ++w) EXPECT(tpla::plan_start(p, T, w) < tpla::plan_start(p, T, w + 1));
   }
