@@ -411,6 +411,10 @@ def wg_timeline(args):
         "same_workgroups_slow_every_launch_correlation": round(float((cc.sum() - len(cc)) / (len(cc) * (len(cc) - 1))), 3),
         "relative_duration_by_placement_round": {str(r): round(float(rel[rounds == r].mean()), 3) for r in sorted(set(rounds.tolist()))},
         "relative_duration_by_xcc": {str(x): round(float(rel[xcc == x].mean()), 3) for x in sorted(set(xcc.tolist()))},
+        # how the last sampled launch was dealt to the XCCs: workgroup w ran on XCC (w + offset) % 8 for one offset?
+        "xcc_of_workgroups_0_to_15": xcc[:16].tolist(),
+        "workgroups_on_xcc_w_plus_offset_mod_8": {str(o): int(np.sum((np.arange(n_wg) + o) % 8 == xcc)) for o in range(8)
+                                                  if np.sum((np.arange(n_wg) + o) % 8 == xcc) > 0},
         "phase_clocks_32_heads_per_wave": phase,
     }))
 
@@ -487,6 +491,13 @@ def main():
 
     # one device's share: the same kernel launched for one slice at a time
     one_ms = one_slice_launches(p, min(args.steps, 200)) if not args.skip_extras else [float("nan")]
+
+    # the other model-shaped workloads, one after the other, each with its own pools -- before the extra
+    # stages below, of which the prefill and the PCA passes leave the GPU hot enough to cost the kernels that
+    # follow them several per cent
+    others = None
+    if not args.skip_extras and args.others:
+        others = {name: measure_other(name, args) for name in args.others.split(",") if name != w.name}
 
     shard_bytes = p.shard_bytes
     value = w.g * shard_bytes / (ms_per_step * 1e-3) / 1e9
@@ -722,9 +733,8 @@ def main():
         "paper_context": "paper reports only ratios: TPLA vs MLA decode 1.79x (DeepSeek-V3) / 1.93x (Kimi-K2) at 32K, "
                          "2 GPUs of an unnamed model, BF16, FlashAttention-3, MoE removed (Sec. 5.4.1)",
     }
-    # the other model-shaped workloads, one after the other, each with its own pools
-    if not args.skip_extras and args.others:
-        out["other_workloads"] = {name: measure_other(name, args) for name in args.others.split(",") if name != w.name}
+    if others is not None:
+        out["other_workloads"] = others
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, model)
     print(json.dumps(out).replace("NaN", "null"))

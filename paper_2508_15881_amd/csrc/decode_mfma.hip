@@ -1161,7 +1161,12 @@ int decode_mfma_blocks_per_cu(const tpla_shape_t& sh) {
 void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4], int32_t wx[2]) {
   for (int r = 0; r < 4; ++r) wt[r] = 128;
   const int dl = sh.d_c / sh.g;
-  wx[0] = 128;
+  wx[0] = wx[1] = 128;
+#ifdef TPLA_EQUAL_RANGES      // measurement build: the plan without any weights, for the timeline comparison
+  (void)dl;
+  (void)per_cu;
+  return;
+#endif
   // 64 heads over 256- or 576-wide rows stay equal: the gain there is within the spread between boxes, and equal
   // ranges end on sequence boundaries when the lengths are equal (one partial result per workgroup instead of two:
   // the layer-step took 3 us longer with the weights); 128 heads: not measured
