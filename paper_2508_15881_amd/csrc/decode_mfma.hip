@@ -1147,8 +1147,11 @@ int decode_mfma_blocks_per_cu(const tpla_shape_t& sh) {
 // workgroups still keep the memory system full when they are alone at the end, and sizing the ranges by
 // round made the launch slower (227 against 222 us at 32 x 32768 tokens); with three (128-wide slices:
 // 12 KB tiles, 24 KB in flight per workgroup) the lone last round does not, and weighted ranges take
-// the ragged batch from 1122 to 1073 us.  With one wave per SIMD (32 heads and fewer) the rounds run
-// alike.  Weights in units of 1/128 of the average range.
+// the ragged batch from 1122 to 1073 us with 140 : 129 : 115.  With the XCC weights below in place the
+// best round weights are further apart (one box, same units: 140:129:115 1047 us, 143:130:112 1035,
+// 146:130:109 1026, 149:131:106 1022, 152:131:103 1034, 155:132:100 1040, 160:132:95 1055 us; on
+// another box 1072 -> 1051 us for 149:131:106 against 140:129:115).  With one wave per SIMD (32 heads
+// and fewer) the rounds run alike.  Weights in units of 1/128 of the average range.
 //
 // The XCCs differ too, the same way on every box measured: workgroups on the odd-numbered ones take
 // 4 % (64 heads, 256-wide slices) to 9 % (32 heads; 128-wide slices) longer over equal ranges than
@@ -1179,9 +1182,9 @@ void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]
   const int waves_per_simd_launched = (sh.H / heads_per_wave) * per_cu / 4;
   if (waves_per_simd_launched < 2) return;
   if (per_cu == 3) {
-    wt[0] = 140;
-    wt[1] = 129;
-    wt[2] = 115;
+    wt[0] = 149;
+    wt[1] = 131;
+    wt[2] = 106;
   }
 }
 

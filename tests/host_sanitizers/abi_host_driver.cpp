@@ -216,7 +216,7 @@ static void pca_checks() {
 static void plan_checks() {
   uint64_t st = 99;
   const int Ws[] = {1, 2, 3, 7, 16, 40, 256, 512, 768};
-  const int wts[][4] = {{1, 1, 1, 1}, {135, 121, 128, 128}, {140, 129, 115, 128}, {128, 128, 128, 128}, {3, 1, 1, 7}};
+  const int wts[][4] = {{1, 1, 1, 1}, {135, 121, 128, 128}, {149, 131, 106, 128}, {128, 128, 128, 128}, {3, 1, 1, 7}};
   const int cus[] = {256, 8, 5};
   const int wxs[][2] = {{1, 1}, {128, 118}, {100, 131}};
   for (const auto& wx : wxs)
@@ -279,7 +279,7 @@ static void plan_checks() {
   // the weighted plans of the library's own launches leave no range empty (the merge relies on it:
   // it only looks for empty ranges when there are fewer pages than ranges)
   const int full[][8] = {{512, 256, 135, 121, 128, 128, 128, 128}, {768, 256, 140, 129, 115, 128, 128, 128},
-                         {768, 256, 140, 129, 115, 128, 128, 113}, {512, 256, 128, 128, 128, 128, 128, 123},
+                         {768, 256, 149, 131, 106, 128, 128, 113}, {512, 256, 128, 128, 128, 128, 128, 123},
                          {512, 256, 128, 128, 128, 128, 128, 115}, {256, 256, 128, 128, 128, 128, 128, 123}};
   for (const auto& f : full) {
     tpla::BalancedPlan p;
