@@ -1170,10 +1170,9 @@ void decode_mfma_round_weights(const tpla_shape_t& sh, int per_cu, int32_t wt[4]
   (void)per_cu;
   return;
 #endif
-  // 64 heads over 256- or 576-wide rows stay equal: the gain there is within the spread between boxes, and equal
-  // ranges end on sequence boundaries when the lengths are equal (one partial result per workgroup instead of two:
-  // the layer-step took 3 us longer with the weights); 128 heads: not measured
-  wx[1] = dl == 128 ? 113 : (sh.H <= 32 ? 115 : 128);
+  // 64 heads over 256-wide slices stay equal: the gain there (1 %) is within the spread between boxes and the
+  // layer-step did not follow it (3 us longer with the weights); 128 heads: not measured
+  wx[1] = dl == 128 ? 113 : (sh.H <= 32 ? 115 : (sh.H == 64 && dl == 512 ? 123 : 128));
 #ifdef TPLA_H32
   const int heads_per_wave = (sh.H >= 64 && dl <= 256) ? 32 : 16;
 #else
