@@ -41,8 +41,12 @@ def kernel_source_digest():
     while it still matches."""
     h = hashlib.sha256()
     for name in ("decode_mfma.hip", "lds_tile.h", "tpla_internal.h", "api.hip"):
-        with open(os.path.join(ROOT, "paper_2508_15881_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2508_15881_amd", "csrc", name), "r") as f:
+            text = f.read()
+        # comments and layout do not change the kernel: the digest is over the code alone
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", " ", text)
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 

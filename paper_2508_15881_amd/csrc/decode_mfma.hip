@@ -1100,10 +1100,11 @@ static int kernel_info_dl(int H, KernelInfo** out) {
       }
       return kernel_info<DL, 2>(out);
     // -DTPLA_H32 routes 64 and 128 heads to the 32-heads-per-wave instances.  Measured against the
-    // 16-heads-per-wave ones (32 x 32768 tokens, both slices): 269 against 223 us at 64 heads, 448 against
-    // 369 us at 128 -- LDS instructions per tile are halved, but a wave's own VALU instructions do not
-    // run under its MFMAs (per-phase clocks: score MFMAs alone 631 cycles per tile, softmax alone 645,
-    // issued interleaved 1159), so one wave per SIMD loses what two waves overlap; not the default.
+    // 16-heads-per-wave ones (32 x 32768 tokens, both slices): 266 against 219 us at 64 heads, 432 against
+    // 356 us at 128 -- LDS instructions per tile are halved, but a wave's own VALU instructions do not
+    // run under its MFMAs (per-phase clocks: the score MFMAs of a tile alone 678 cycles, with the softmax
+    // of the previous tile issued between them 1158), so one wave per SIMD loses what two waves overlap;
+    // not the default.
 #ifdef TPLA_H32
     case 64:
       if constexpr (DL <= 256) return kernel_info<DL, 2, 32>(out);
