@@ -316,12 +316,15 @@ __global__ void __launch_bounds__(MC_NW * 64) merge_combine_mfma_kernel(DecodeAr
       first = vb * a.n_splits;
       cnt = min((n_pages + a.pages_per_split - 1) / a.pages_per_split, a.n_splits);
     } else {
-      T = a.plan[n_v];
-      c0 = a.plan[vb];
-      w0 = balanced_owner(a.geom, c0, T);
-      cnt = balanced_owner(a.geom, c0 + n_pages - 1, T) - w0 + 1;
+      // the split kernel left the slots of every (slice, sequence) in the plan table
+      w0 = a.plan[n_v + 1 + vb];
+      cnt = a.plan[2 * n_v + 1 + vb];
       first = w0 + vb;
-      sparse = plan_sparse(a.geom, T);
+      sparse = a.plan[3 * n_v + 1] != 0;
+      if (sparse) {
+        T = a.plan[n_v];
+        c0 = a.plan[vb];
+      }
     }
     auto live = [&](int s) -> bool {
       if (s >= cnt) return false;

@@ -128,14 +128,14 @@ SplitPlan plan_splits(const tpla_shape_t& sh, int32_t n_shards, int32_t max_page
 }
 
 // Partial-result slots of a plan, and the workspace: acc [slots, H, dl] floats,
-// (reference, sum) [slots, H, 2] floats, then (balanced) the page-offset table.
+// (reference, sum) [slots, H, 2] floats, then (balanced) the plan table the split kernel leaves for the merge.
 static size_t plan_slots(const tpla_shape_t& sh, int n_shards, const SplitPlan& p) {
   return p.balanced ? (size_t)p.n_wg + (size_t)n_shards * sh.B : (size_t)n_shards * sh.B * p.n_splits;
 }
 static size_t workspace_for(const tpla_shape_t& sh, int n_shards, const SplitPlan& p) {
   const size_t dl = (size_t)(sh.d_c / sh.g);
   size_t bytes = plan_slots(sh, n_shards, p) * sh.H * (dl + 2) * sizeof(float);
-  if (p.balanced) bytes += (((size_t)n_shards * sh.B + 1) * sizeof(int32_t) + 15) / 16 * 16;
+  if (p.balanced) bytes += ((3 * (size_t)n_shards * sh.B + 2) * sizeof(int32_t) + 15) / 16 * 16;
   return bytes;
 }
 

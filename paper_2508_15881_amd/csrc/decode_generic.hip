@@ -137,8 +137,9 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
       // some ranges in between are empty and are left out, 64 candidates at a time
       const int n_v = a.n_shards * a.B;
       const int T = a.plan[n_v], c0 = a.plan[vb];
-      const int w0 = balanced_owner(a.geom, c0, T), w1 = balanced_owner(a.geom, c0 + n_pages - 1, T);
-      if (!plan_sparse(a.geom, T)) {
+      // first owner and number of ranges: left in the plan table by the split kernel
+      const int w0 = a.plan[n_v + 1 + vb], w1 = w0 + a.plan[2 * n_v + 1 + vb] - 1;
+      if (a.plan[3 * n_v + 1] == 0) {
         cnt = w1 - w0 + 1;
         for (int s = lane; s < cnt; s += 64) slot_of[s] = w0 + s + vb;
       } else {

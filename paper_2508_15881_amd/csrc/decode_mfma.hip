@@ -1022,7 +1022,40 @@ __global__ void __launch_bounds__(NW * 64 * (HPW == HPW_PAIR ? 2 : 1), (waves_pe
     }
     base += __shfl(incl, 63);
   }
-  if (w == 0 && threadIdx.x == 0) a.plan[n_v] = total;
+  if (w == 0 && threadIdx.x == 0) {
+    a.plan[n_v] = total;
+    a.plan[3 * n_v + 1] = plan_sparse(a.geom, total) ? 1 : 0;
+  }
+  // What the merge needs of the plan, once per launch instead of once per lane of the merge kernel: for
+  // every (slice, sequence) the range that owns its first page and the number of ranges up to the owner
+  // of its last.  Dealt over the workgroups (pair v to workgroup v mod W, one lane of its first wave) and
+  // done after the workgroup's own range: inside the scan above it cost the ragged batch 7 % (the owner
+  // search then lives in the loop that holds the items' registers).
+  if (threadIdx.x < 64 && w < n_v) {
+    int base2 = 0;
+    for (int v0 = 0; v0 < n_v; v0 += 64) {
+      const int v = v0 + lane;
+      const int L = (v < n_v) ? seq_len_clipped(a, v % a.B) : 0;
+      const int pg = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
+      int incl = pg;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d);
+        if (lane >= d) incl += o;
+      }
+      const int excl = base2 + incl - pg;
+      if (v < n_v && v % a.n_wg == w) {
+        int w0 = 0, cnt = 0;
+        if (pg > 0) {
+          w0 = balanced_owner(a.geom, excl, total);
+          cnt = balanced_owner(a.geom, excl + pg - 1, total) - w0 + 1;
+        }
+        a.plan[n_v + 1 + v] = w0;
+        a.plan[2 * n_v + 1 + v] = cnt;
+      }
+      base2 += __shfl(incl, 63);
+    }
+  }
 #ifdef TPLA_WG_TIMELINE
   __syncthreads();
   TPLA_TL_MARK(3);

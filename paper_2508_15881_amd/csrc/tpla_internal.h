@@ -57,26 +57,45 @@ __host__ __device__ __forceinline__ long long plan_cum(const BalancedPlan& p, in
   return c + ((long long)(left / 2) * pair + (long long)(left & 1) * p.wx[0]) * p.wt[r];
 }
 // First page of range w, 0 <= w <= W (T pages in all; T * total weight stays below 2^62).
+// total = plan_cum(p, p.W), for callers that need several ranges.
+__host__ __device__ __forceinline__ int plan_start(const BalancedPlan& p, long long T, int w, long long total) {
+  return (int)(T * plan_cum(p, w) / total);
+}
 __host__ __device__ __forceinline__ int plan_start(const BalancedPlan& p, long long T, int w) {
-  return (int)(T * plan_cum(p, w) / plan_cum(p, p.W));
+  return plan_start(p, T, w, plan_cum(p, p.W));
+}
+__host__ __device__ __forceinline__ bool plan_equal_weights(const BalancedPlan& p) {
+  return p.wt[0] == p.wt[1] && p.wt[1] == p.wt[2] && p.wt[2] == p.wt[3] && p.wx[0] == p.wx[1];
 }
 // The range that holds page c, 0 <= c < T.
 __host__ __device__ __forceinline__ int balanced_owner(const BalancedPlan& p, int c, int T) {
-  // first guess from the inverse of the piecewise linear cumulative weight (with the mean of the two
-  // parity weights), then step to the exact range
+  if (plan_equal_weights(p) && (long long)T * p.W < 2147483647LL) {
+    // equal ranges [w T / W, (w + 1) T / W): the owner of c is the last w with w T / W <= c, in 32-bit arithmetic
+    const unsigned w = (((unsigned)c + 1u) * (unsigned)p.W + (unsigned)T - 1u) / (unsigned)T - 1u;
+    return (int)w;
+  }
+  // First guess from the inverse of the piecewise linear cumulative weight (with the mean of the two
+  // parity weights) in floating point, then steps to the exact range with the test
+  //   plan_start(w) <= c   <=>   T cum(w) < (c + 1) total
+  // which needs no division (a 64-bit integer division costs the GPU a hundred instructions; the
+  // guess only decides how many steps follow, the result is exact either way).
   const long long total = plan_cum(p, p.W);
-  const long long pair = (long long)p.wx[0] + p.wx[1];
-  long long x = ((long long)c * total) / T;
+  const double pair = (double)p.wx[0] + (double)p.wx[1];
+  double x = (double)c * (double)total / (double)T;
   int r = 0, base = 0;
-  while (r < 3 && base + p.n_cus < p.W && x >= plan_cum(p, base + p.n_cus) - plan_cum(p, base)) {
-    x -= plan_cum(p, base + p.n_cus) - plan_cum(p, base);
+  while (r < 3 && base + p.n_cus < p.W) {
+    const double round_weight = (double)(plan_cum(p, base + p.n_cus) - plan_cum(p, base));
+    if (x < round_weight) break;
+    x -= round_weight;
     base += p.n_cus;
     ++r;
   }
-  int w = base + (int)(2 * x / (p.wt[r] * pair));
+  int w = base + (int)(2.0 * x / ((double)p.wt[r] * pair));
   if (w > p.W - 1) w = p.W - 1;
-  while (w + 1 < p.W && plan_start(p, T, w + 1) <= c) ++w;
-  while (w > 0 && plan_start(p, T, w) > c) --w;
+  if (w < 0) w = 0;
+  const long long bound = ((long long)c + 1) * total;
+  while (w + 1 < p.W && (long long)T * plan_cum(p, w + 1) < bound) ++w;
+  while (w > 0 && !((long long)T * plan_cum(p, w) < bound)) --w;
   return w;
 }
 // Whether some range of the plan may be empty (fewer pages than ranges; with weights, fewer than
@@ -121,7 +140,11 @@ struct DecodeArgs {
   int32_t n_splits, pages_per_split;
   int32_t balanced, n_wg;
   BalancedPlan geom;     // balanced: ranges and their weights (geom.W == n_wg)
-  int32_t* plan;         // balanced: [n_shards * B + 1] first page of every sequence, then the total
+  // balanced, written by workgroup 0 of the split kernel for the merge (n_v = n_shards * B entries each):
+  // [0, n_v) first page of every (slice, sequence) in the laid-out order; [n_v] total pages T;
+  // [n_v + 1, 2 n_v + 1) the range that owns its first page; [2 n_v + 1, 3 n_v + 1) how many ranges from
+  // there to the owner of its last page (0 for an empty sequence); [3 n_v + 1] plan_sparse(T)
+  int32_t* plan;
   float scale_log2;      // sm_scale * log2(e)
 };
 

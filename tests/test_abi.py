@@ -64,8 +64,9 @@ def test_workspace_bytes():
     assert one == 2 * 1 * 64 * (256 + 2) * 4
     assert tp.tpla_workspace_bytes(s, 512, 8) == 8 * one
     assert tp.tpla_workspace_bytes(s, 4, 100) == 4 * one          # never more splits than pages
-    auto = tp.tpla_workspace_bytes(s, 512, 0)      # balanced plan: one slot per workgroup and per sequence
-    assert auto > one and (auto - 16) % (64 * (256 + 2) * 4) == 0
+    auto = tp.tpla_workspace_bytes(s, 512, 0)      # balanced plan: one slot per workgroup and per sequence,
+    plan_table = (3 * 2 + 2) * 4                   # then three ints per sequence (B = 2) and two more, in whole 16 bytes
+    assert auto > one and (auto - plan_table) % (64 * (256 + 2) * 4) == 0
     assert tp.tpla_workspace_bytes_all(s, 512, 0) >= auto
     assert tp.tpla_workspace_bytes_all(s, 512, 3) == 2 * tp.tpla_workspace_bytes(s, 512, 3)
     assert tp.tpla_workspace_bytes(s, 0, 0) == 0
