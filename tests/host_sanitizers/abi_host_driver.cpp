@@ -290,6 +290,32 @@ static void plan_checks() {
     p.wx[1] = f[7];
     for (int T : {32 * f[0], 32 * f[0] + 17, 100000, 2000000})
       for (int w = 0; w < p.W; ++w) EXPECT(tpla::plan_start(p, T, w) < tpla::plan_start(p, T, w + 1));
+    // owners at the edges of every range for page counts on both sides of the 32-bit path's limit
+    // (T W < 2^31) and far beyond it
+    for (int T : {4194303, 4194304, 4194305, 2796202, 2796203, 123456789, 2000000000})
+      for (int w = 0; w < p.W; ++w) {
+        const int lo = tpla::plan_start(p, T, w), hi = tpla::plan_start(p, T, w + 1);
+        EXPECT(lo < hi);
+        EXPECT(tpla::balanced_owner(p, lo, T) == w && tpla::balanced_owner(p, hi - 1, T) == w);
+        EXPECT(tpla::balanced_owner(p, lo + (hi - lo) / 2, T) == w);
+      }
+  }
+  // the same with equal weights (the 32-bit path and its fallback)
+  for (int W : {1, 3, 256, 512, 768}) {
+    tpla::BalancedPlan p;
+    p.W = W;
+    p.n_cus = 256;
+    for (int r = 0; r < 4; ++r) p.wt[r] = 128;
+    p.wx[0] = p.wx[1] = 128;
+    for (long long T64 : {2147483647LL / W - 1, 2147483647LL / W, 2147483647LL / W + 1, 2147483647LL / W + 2, 2000000000LL}) {
+      if (T64 > 2147483647LL) continue;
+      const int T = (int)T64;
+      for (int w = 0; w < W; ++w) {
+        const int lo = tpla::plan_start(p, T, w), hi = tpla::plan_start(p, T, w + 1);
+        EXPECT(lo == (int)((long long)w * T / W) && lo < hi);
+        EXPECT(tpla::balanced_owner(p, lo, T) == w && tpla::balanced_owner(p, hi - 1, T) == w);
+      }
+    }
   }
 }
 
