@@ -223,7 +223,13 @@ int launch_transform_paged_mfma(const TransformArgs& t, const tpla_shape_t& sh, 
 // straight from global memory costs one cache access per lane; staged, every
 // global load is a full 128-byte line per 8 lanes and the operand reads are
 // 16-byte LDS reads (pieces XOR-swizzled so that 16 rows hit 16 bank groups).
-// The next chunk is in registers while the current one feeds the MFMAs.
+// A wave stages the 32 rows it multiplies itself, so the loop over the chunks
+// has no workgroup barrier.  The next row block is in registers while the
+// current one feeds the MFMAs.  Measured and not kept: 64 x 64 outputs per wave
+// (4 x 4 MFMA tiles, 32-k chunks, a ring of 4 chunks in registers: 12 instead
+// of 20 LDS reads per 32 MFMAs) was 6 % slower, with the fragments read one
+// chunk ahead 20 % slower (the registers no longer hold it all); the matrix
+// cores are busy 0.38 of the time either way, at 2.25 GHz.
 // As in the Hadamard pass the slab's columns are ordered so that a lane owns 4
 // adjacent output columns.  The d_c/64 workgroups that read the same rows sit
 // on one XCD (block ids congruent mod 8): the rows come from that XCD's L2
@@ -278,15 +284,16 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
     const size_t page = page_ids ? (size_t)page_ids[pg] : (size_t)pg;
     return page * (size_t)page_tokens + slot;
   };
-  // staging: piece x = tid + 512 j of a chunk is row x / 8, 16-byte piece x % 8; it lives at
-  // piece position (x % 8) ^ ((row >> 1) & 7) of its row
+  // staging: a wave stages the 32 rows it multiplies itself (so no wave ever waits for another): its
+  // j-th load takes rows 32 wave + 8 j .. + 8, lane / 8 the row and lane % 8 the 16-byte piece, which
+  // lives at piece position (lane % 8) ^ ((row >> 1) & 7) of its row
+  static_assert(DENSE_LD * 8 == 32, "a wave stages its own 32 rows");
   int st_row[DENSE_LD];
   unsigned st_dst[DENSE_LD];
 #pragma unroll
   for (int j = 0; j < DENSE_LD; ++j) {
-    const int x = tid + DENSE_WAVES * 64 * j;
-    st_row[j] = x >> 3;
-    st_dst[j] = (unsigned)(st_row[j] * 8 + ((x & 7) ^ ((st_row[j] >> 1) & 7)));
+    st_row[j] = 32 * wave + 8 * j + (lane >> 3);
+    st_dst[j] = (unsigned)(st_row[j] * 8 + ((lane & 7) ^ ((st_row[j] >> 1) & 7)));
   }
   // operand reads: row 32 wave + 16 mt + lo, piece 4 ks + hi of the chunk
   unsigned a_off[2][2];
@@ -314,7 +321,7 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
   auto row_sources = [&](int rb, const bf16_t* (&src)[DENSE_LD]) {
 #pragma unroll
     for (int j = 0; j < DENSE_LD; ++j) {
-      const size_t tok = whole_groups ? group_token(rb, j) + (st_row[j] - 64 * j)
+      const size_t tok = whole_groups ? group_token(rb, wave >> 1) + (st_row[j] - 64 * (wave >> 1))
                                       : token_of(min(rb * DENSE_ROWS + st_row[j], last));
       src[j] = mla_pool + tok * in_pitch + 8 * (tid & 7);
     }
@@ -357,6 +364,7 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
     kpe_request(worker);
   }
 
+  __syncthreads();                                   // the slab of U is in place
   for (int rb = worker; rb < n_row_blocks; rb += row_workers) {
     const int row0 = rb * DENSE_ROWS;
     const int rb_next = rb + row_workers;
@@ -369,10 +377,15 @@ __global__ void __launch_bounds__(DENSE_WAVES * 64) transform_paged_dense_mfma_k
       for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     static_for<NCH>([&](auto chc) {
       constexpr int ch = decltype(chc)::value;
-      __syncthreads();                               // the previous chunk (and, first time, the slab) is settled
+      // The staged rows are private to the wave and a wave's LDS instructions complete in order: the
+      // writes below land after the previous chunk's reads and before this chunk's.  The wave barriers
+      // only keep the compiler from moving an LDS access across them.
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int j = 0; j < DENSE_LD; ++j) stage[st_dst[j]] = blk[ch][j];
-      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
       if (more) {
 #pragma unroll
         for (int j = 0; j < DENSE_LD; ++j) blk[ch][j] = *reinterpret_cast<const u32x4*>(src[j] + DENSE_KC * ch);
