@@ -985,18 +985,22 @@ __global__ void __launch_bounds__(NW * 64 * (HPW == HPW_PAIR ? 2 : 1), (waves_pe
   const int w = blockIdx.x;
   // every wave scans the lengths by itself (no LDS, no barrier)
   int total = 0;
+  int L_first = 0;               // length of pair `lane`: the later passes do not load the first 64 again
   for (int v0 = 0; v0 < n_v; v0 += 64) {
     const int v = v0 + lane;
-    int pg = (v < n_v) ? (seq_len_clipped(a, v % a.B) + PAGE_TOKENS - 1) / PAGE_TOKENS : 0;
+    const int L = (v < n_v) ? seq_len_clipped(a, v % a.B) : 0;
+    if (v0 == 0) L_first = L;
+    int pg = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) pg += __shfl_xor(pg, m);
     total += pg;
   }
-  const int start = plan_start(a.geom, total, w), end = plan_start(a.geom, total, w + 1);
+  int start, end;
+  plan_range(a.geom, total, w, &start, &end);
   int base = 0;
   for (int v0 = 0; v0 < n_v; v0 += 64) {
     const int v = v0 + lane;
-    const int L = (v < n_v) ? seq_len_clipped(a, v % a.B) : 0;
+    const int L = v0 == 0 ? L_first : ((v < n_v) ? seq_len_clipped(a, v % a.B) : 0);
     const int pg = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
     int incl = pg;                               // inclusive prefix sum over the wave
 #pragma unroll
@@ -1035,7 +1039,7 @@ __global__ void __launch_bounds__(NW * 64 * (HPW == HPW_PAIR ? 2 : 1), (waves_pe
     int base2 = 0;
     for (int v0 = 0; v0 < n_v; v0 += 64) {
       const int v = v0 + lane;
-      const int L = (v < n_v) ? seq_len_clipped(a, v % a.B) : 0;
+      const int L = v0 == 0 ? L_first : ((v < n_v) ? seq_len_clipped(a, v % a.B) : 0);
       const int pg = (L + PAGE_TOKENS - 1) / PAGE_TOKENS;
       int incl = pg;
 #pragma unroll

@@ -67,6 +67,18 @@ __host__ __device__ __forceinline__ int plan_start(const BalancedPlan& p, long l
 __host__ __device__ __forceinline__ bool plan_equal_weights(const BalancedPlan& p) {
   return p.wt[0] == p.wt[1] && p.wt[1] == p.wt[2] && p.wt[2] == p.wt[3] && p.wx[0] == p.wx[1];
 }
+// Range w as [*start, *end) = [plan_start(w), plan_start(w + 1)), 0 <= w < W: equal ranges of not too many
+// pages in 32-bit arithmetic (every workgroup of the split kernel begins with this).
+__host__ __device__ __forceinline__ void plan_range(const BalancedPlan& p, int T, int w, int* start, int* end) {
+  if (plan_equal_weights(p) && (long long)T * p.W < 2147483647LL) {
+    *start = (int)((unsigned)w * (unsigned)T / (unsigned)p.W);
+    *end = (int)(((unsigned)w + 1u) * (unsigned)T / (unsigned)p.W);
+    return;
+  }
+  const long long total = plan_cum(p, p.W);
+  *start = plan_start(p, T, w, total);
+  *end = plan_start(p, T, w + 1, total);
+}
 // The range that holds page c, 0 <= c < T.
 __host__ __device__ __forceinline__ int balanced_owner(const BalancedPlan& p, int c, int T) {
   if (plan_equal_weights(p) && (long long)T * p.W < 2147483647LL) {

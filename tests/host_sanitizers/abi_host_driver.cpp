@@ -242,7 +242,13 @@ static void plan_checks() {
           }
           if (T == 0) continue;
           EXPECT(tpla::plan_start(p, T, 0) == 0 && tpla::plan_start(p, T, W) == T);
-          for (int w = 0; w < W; ++w) EXPECT(tpla::plan_start(p, T, w) <= tpla::plan_start(p, T, w + 1));
+          for (int w = 0; w < W; ++w) {
+            EXPECT(tpla::plan_start(p, T, w) <= tpla::plan_start(p, T, w + 1));
+            EXPECT(tpla::plan_start(p, T, w) == (int)((long long)T * tpla::plan_cum(p, w) / tpla::plan_cum(p, W)));
+            int r0 = -1, r1 = -1;
+            tpla::plan_range(p, T, w, &r0, &r1);                         // what a workgroup computes for itself
+            EXPECT(r0 == tpla::plan_start(p, T, w) && r1 == tpla::plan_start(p, T, w + 1));
+          }
           if (wt[0] == wt[1] && wt[1] == wt[2] && wt[2] == wt[3] && wx[0] == wx[1])      // equal weights: the plain equal shares
             for (int w = 0; w <= W; ++w) EXPECT(tpla::plan_start(p, T, w) == (int)((long long)w * T / W));
           for (int c = 0; c < T; ++c) {
@@ -296,6 +302,7 @@ static void plan_checks() {
       for (int w = 0; w < p.W; ++w) {
         const int lo = tpla::plan_start(p, T, w), hi = tpla::plan_start(p, T, w + 1);
         EXPECT(lo < hi);
+        EXPECT(lo == (int)((long long)T * tpla::plan_cum(p, w) / tpla::plan_cum(p, p.W)));
         EXPECT(tpla::balanced_owner(p, lo, T) == w && tpla::balanced_owner(p, hi - 1, T) == w);
         EXPECT(tpla::balanced_owner(p, lo + (hi - lo) / 2, T) == w);
       }
@@ -313,6 +320,9 @@ static void plan_checks() {
       for (int w = 0; w < W; ++w) {
         const int lo = tpla::plan_start(p, T, w), hi = tpla::plan_start(p, T, w + 1);
         EXPECT(lo == (int)((long long)w * T / W) && lo < hi);
+        int r0 = -1, r1 = -1;
+        tpla::plan_range(p, T, w, &r0, &r1);
+        EXPECT(r0 == lo && r1 == hi);
         EXPECT(tpla::balanced_owner(p, lo, T) == w && tpla::balanced_owner(p, hi - 1, T) == w);
       }
     }
