@@ -41,8 +41,11 @@ __device__ __forceinline__ bf16x8 read_b_frag(const char* slab, int k0, int cb, 
 }
 
 // ---------------------------------------------------------------------------
-// absorb: grid (H, d_c / 128); 4 waves, wave w owns columns 32w..32w+31 of the
-// slab; LDS slab = W_UK'[h][0..d_n)[c0..c0+128).
+// absorb: grid (H, d_c / 128, Z); 4 waves, wave w owns columns 32w..32w+31 of the
+// slab; LDS slab = W_UK'[h][0..d_n)[c0..c0+128).  A workgroup walks over blocks of 16
+// sequences, one dependent load per block, so batches of more than 32 sequences are
+// dealt over Z workgroups per (head, column block), each staging the slab for itself
+// (32 KB from L2): block mb goes to z = mb mod Z.
 constexpr int AQ_COLS = 128;
 __global__ void __launch_bounds__(256) absorb_query_mfma_kernel(const bf16_t* __restrict__ q_nope,
                                                                 const bf16_t* __restrict__ W, MuFactors mu,
@@ -75,10 +78,11 @@ __global__ void __launch_bounds__(256) absorb_query_mfma_kernel(const bf16_t* __
     for (int ks = 0; ks < KS_MAX; ++ks)
       if (ks < KS) av[ks] = *reinterpret_cast<const bf16x8*>(qrow + 32 * ks);
   };
-  load_rows(0);
+  const int mb0 = blockIdx.z, mb_step = gridDim.z;
+  load_rows(mb0);                              // mb0 < n_mb by the launch
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  for (int mb = 0; mb < n_mb; ++mb) {
+  for (int mb = mb0; mb < n_mb; mb += mb_step) {
     f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
     for (int ks = 0; ks < KS_MAX; ++ks) {
@@ -90,7 +94,7 @@ __global__ void __launch_bounds__(256) absorb_query_mfma_kernel(const bf16_t* __
         }
       }
     }
-    if (mb + 1 < n_mb) load_rows(mb + 1);     // under this block's stores
+    if (mb + mb_step < n_mb) load_rows(mb + mb_step);     // under this block's stores
     // acc[cb][i]: sequence 16 mb + 4 q4 + i, column c0 + 32 wave + 16 cb + j16
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
@@ -114,7 +118,9 @@ bool absorb_mfma_supported(const tpla_shape_t& sh) {
 int launch_absorb_query_mfma(const tpla_shape_t& sh, const void* q_nope, const void* W_UK_t,
                              const MuFactors& mu, void* q_lat, hipStream_t st) {
   const size_t smem = (size_t)sh.d_n * AQ_COLS * 2;
-  hipLaunchKernelGGL(absorb_query_mfma_kernel, dim3((unsigned)sh.H, (unsigned)(sh.d_c / AQ_COLS)), dim3(256),
+  const int n_mb = (sh.B + 15) / 16;
+  const int Z = n_mb <= 2 ? 1 : (n_mb + 1) / 2 < 8 ? (n_mb + 1) / 2 : 8;   // two blocks per workgroup, at most 8 deep
+  hipLaunchKernelGGL(absorb_query_mfma_kernel, dim3((unsigned)sh.H, (unsigned)(sh.d_c / AQ_COLS), (unsigned)Z), dim3(256),
                      smem, st, static_cast<const bf16_t*>(q_nope), static_cast<const bf16_t*>(W_UK_t), mu,
                      static_cast<bf16_t*>(q_lat), sh.B, sh.H, sh.d_n, sh.d_c, sh.g);
   return check_launch("absorb_query_mfma_kernel");
