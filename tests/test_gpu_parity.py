@@ -567,7 +567,10 @@ def test_append_token_sliced():
 
 
 # ------------------------------------------------------------ absorb / combine
-@pytest.mark.parametrize("dtype,Bn,H,g", [("bf16", 5, 64, 2), ("bf16", 17, 32, 4), ("f32", 3, 4, 2)])
+@pytest.mark.parametrize("dtype,Bn,H,g", [("bf16", 5, 64, 2), ("bf16", 17, 32, 4), ("f32", 3, 4, 2),
+                                          # batches whose blocks of 16 sequences are dealt over 2, 5 and 8 workgroups
+                                          # per (head, column block) of the absorb kernel, ragged last block
+                                          ("bf16", 37, 16, 2), ("bf16", 130, 16, 1), ("bf16", 300, 16, 4)])
 def test_absorb_and_combine(dtype, Bn, H, g):
     _say(f"absorb/combine {dtype} B={Bn} H={H} g={g}")
     d_c, d_n, d_v, d_r = (512, 128, 128, 64) if dtype == "bf16" else (64, 32, 32, 16)
